@@ -1,0 +1,160 @@
+"""numpy/ctypes front end of the fp64 CPU oracle (``cottn_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke`` and by the
+``cpu_baseline`` leg of ``bench.py``; the product package never imports it, and it never
+imports the product package.  Every function converts its inputs to contiguous float64
+(bf16/fp32 values convert exactly) and returns fresh float64 arrays.
+
+Shapes: Q, K, V, dO are [B, H, N, d]; s is [H]; states are [B, H, d, d] stored
+[d_key][d_value] and do not contain the scale s.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from .build import LIB, build
+
+_lib = None
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _f64(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _p(a):
+    return a.ctypes.data_as(_dp) if a is not None else None
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(ctypes.c_int(n))
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _dims(Q):
+    B, H, N, d = Q.shape
+    return ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(N), ctypes.c_int(d)
+
+
+def normalize_rows(X, eps=1e-6):
+    """Row L2 normalisation x / max(||x||, eps) over the last axis (Sec. 3.2)."""
+    X = _f64(X)
+    d = X.shape[-1]
+    out = np.empty_like(X)
+    den = np.empty(X.shape[:-1], dtype=np.float64)
+    _load().oracle_normalize_rows(_p(X), ctypes.c_long(X.size // d), ctypes.c_int(d),
+                                  ctypes.c_double(eps), _p(out), _p(den))
+    return out, den
+
+
+def similarity(Q, K, eps=1e-6):
+    """Unmasked cosine-similarity matrix [N, N] of one unit; Q, K are [N, d] (Sec. 3.1)."""
+    Q, K = _f64(Q), _f64(K)
+    N, d = Q.shape
+    P = np.empty((N, N), dtype=np.float64)
+    _load().oracle_similarity(_p(Q), _p(K), ctypes.c_int(N), ctypes.c_int(d),
+                              ctypes.c_double(eps), _p(P))
+    return P
+
+
+def fwd_quadratic(Q, K, V, s, eps=1e-6, causal=True):
+    """The definition: s_h (Qhat Khat^T (.) M) V, or without mask (Sec. 4)."""
+    Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
+    O = np.empty_like(Q)
+    _load().oracle_fwd_quadratic(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+                                 ctypes.c_int(1 if causal else 0), _p(O))
+    return O
+
+
+def fwd_recurrent(Q, K, V, s, eps=1e-6, S0=None):
+    """The RNN form (Sec. 5); returns (O, final state)."""
+    Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
+    B, H, N, d = Q.shape
+    S0 = _f64(S0) if S0 is not None else None
+    O = np.empty_like(Q)
+    S = np.empty((B, H, d, d), dtype=np.float64)
+    _load().oracle_fwd_recurrent(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+                                 _p(S0), _p(O), _p(S))
+    return O, S
+
+
+def state_total(K, V, eps=1e-6):
+    """Khat^T V over the whole sequence, [B, H, d, d] (Sec. 4, eq. subQuadCos right bracket)."""
+    K, V = _f64(K), _f64(V)
+    B, H, N, d = K.shape
+    S = np.empty((B, H, d, d), dtype=np.float64)
+    _load().oracle_state_total(_p(K), _p(V), *_dims(K), ctypes.c_double(eps), _p(S))
+    return S
+
+
+def step(q, k, v, s, S, eps=1e-6):
+    """One decode step; q, k, v are [B, H, d]; returns (o, new state) without touching S."""
+    q, k, v, s = _f64(q), _f64(k), _f64(v), _f64(s)
+    S = _f64(S).copy()
+    B, H, d = q.shape
+    o = np.empty_like(q)
+    _load().oracle_step(_p(q), _p(k), _p(v), _p(s), _p(S), ctypes.c_int(B), ctypes.c_int(H),
+                        ctypes.c_int(d), ctypes.c_double(eps), _p(o))
+    return o, S
+
+
+def bwd_quadratic(Q, K, V, s, dO, eps=1e-6, causal=True):
+    """Brute-force gradients wrt raw Q, K, V and s; returns (dQ, dK, dV, ds)."""
+    Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    ds = np.empty_like(s)
+    _load().oracle_bwd_quadratic(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q),
+                                 ctypes.c_double(eps), ctypes.c_int(1 if causal else 0),
+                                 _p(dQ), _p(dK), _p(dV), _p(ds))
+    return dQ, dK, dV, ds
+
+
+def bwd_recurrent(Q, K, V, s, dO, eps=1e-6):
+    """Linear-time causal gradients (forward and reverse cumulative sums, Sec. 4)."""
+    Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    ds = np.empty_like(s)
+    _load().oracle_bwd_recurrent(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q),
+                                 ctypes.c_double(eps), _p(dQ), _p(dK), _p(dV), _p(ds))
+    return dQ, dK, dV, ds
+
+
+def _rows(rows):
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32).reshape(-1, 3))
+    return r, r.ctypes.data_as(_ip), ctypes.c_int(r.shape[0])
+
+
+def fwd_rows(Q, K, V, s, rows, eps=1e-6, causal=True):
+    """Rows (b, h, i) of the definition, each from its own sum; returns [len(rows), d]."""
+    Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
+    r, rp, n = _rows(rows)
+    out = np.empty((r.shape[0], Q.shape[-1]), dtype=np.float64)
+    _load().oracle_fwd_rows(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+                            ctypes.c_int(1 if causal else 0), rp, n, _p(out))
+    return out
+
+
+def bwd_rows(Q, K, V, s, dO, rows, eps=1e-6, causal=True):
+    """Rows (b, h, t) of the brute-force dQ, dK, dV; returns three [len(rows), d] arrays."""
+    Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
+    r, rp, n = _rows(rows)
+    d = Q.shape[-1]
+    dQ = np.empty((r.shape[0], d), dtype=np.float64)
+    dK, dV = np.empty_like(dQ), np.empty_like(dQ)
+    _load().oracle_bwd_rows(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q), ctypes.c_double(eps),
+                            ctypes.c_int(1 if causal else 0), rp, n, _p(dQ), _p(dK), _p(dV))
+    return dQ, dK, dV
