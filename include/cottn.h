@@ -1,0 +1,139 @@
+/* cottn.h — C ABI of the cosine-attention (Cottention) library for MI355X (gfx950).
+ *
+ * Operation (paper notation: N(X) = row-wise L2 normalisation, Sec. 3.2; M = lower-triangular
+ * ones including the diagonal, Sec. 4).  With Qh = N(Q), Kh = N(K) and a given positive
+ * per-head scale s[h] (the stabiliser of Sec. 3.3 taken as a number):
+ *
+ *   causal         O = s_h * (Qh Kh^T (.) M) V                          (Sec. 4, eq. attn_1)
+ *                  computed in linear memory as the cumulative sum of Kh^T V states
+ *                  (Sec. 4, eq. attn_2), regrouped into chunks of `chunk` rows;
+ *   bidirectional  O = s_h * Qh (Kh^T V)                                (Sec. 4, eq. subQuadCos)
+ *   decode step    S <- S + kh^T v ;  o = s_h * qh S                    (Sec. 5, eq. hidden_state_obs)
+ *   backward       the three gradient formulas of Sec. 4 followed by the chain rule through
+ *                  the normalisation and the scale: gradients are with respect to the RAW
+ *                  Q, K, V and to s.
+ *
+ * Conventions common to every entry point
+ *   - All tensor arguments are DEVICE pointers, contiguous, row-major, innermost dimension d:
+ *     Q, K, V, O, dO, dQ, dK, dV are [B][H][N][d]; q, k, v, o are [B][H][d]; s and ds are
+ *     float[H]; states are float[B][H][d][d] laid out [d_key][d_value] = sum_j kh_j^T v_j
+ *     and do NOT contain s (it is applied at read-out, so a state written by
+ *     cottn_fwd_causal can be continued by cottn_step).
+ *   - `dtype` is the storage type of Q, K, V, O, dO, dQ, dK, dV, q, k, v, o:
+ *     COTTN_F32 (fp32 arithmetic) or COTTN_BF16 (bf16 MFMA operands, fp32 accumulation,
+ *     outputs rounded to nearest-even).  s, ds, states and the workspace are always fp32.
+ *   - Normalisation is x / max(||x||_2, eps); rows with ||x|| <= eps are x / eps.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing, never
+ *     synchronises, and enqueues all work on `hip_stream` (a hipStream_t; NULL = the default
+ *     stream).  Inputs are read-only; outputs are fully overwritten (ds is overwritten, not
+ *     accumulated into).  Outputs must not alias inputs.
+ *   - Base pointers of tensors must be 16-byte aligned; the workspace 256-byte aligned.
+ *   - Supported shapes: d in {32, 64, 128}; B, H, N >= 1 (N == 0 is accepted and does
+ *     nothing but define the outputs that do not depend on rows); chunk in {0, 64, 128, 256}
+ *     for bf16 (0 = library default, 64) with chunk*d <= 16384, and chunk in {0, 32} for fp32.
+ *     N need not be a multiple of chunk.
+ *   - Return value: COTTN_OK or a cottn_status error code.  Argument errors are detected
+ *     before anything is enqueued (so they can be exercised without a GPU); HIP launch
+ *     failures return COTTN_E_HIP.  No entry point throws, aborts or prints.
+ *   - `workspace` must hold at least cottn_workspace_bytes(op, ...) bytes for the same
+ *     arguments; it may be NULL when that size is 0.  Its contents on entry are ignored
+ *     and on exit unspecified.  Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef COTTN_H
+#define COTTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { COTTN_F32 = 0, COTTN_BF16 = 1 } cottn_dtype;
+
+typedef enum {
+  COTTN_OK = 0,
+  COTTN_E_NULL = 1,      /* a required pointer is NULL */
+  COTTN_E_SHAPE = 2,     /* B, H, N, d or chunk outside the supported set */
+  COTTN_E_DTYPE = 3,     /* dtype is neither COTTN_F32 nor COTTN_BF16 */
+  COTTN_E_ALIGN = 4,     /* a pointer is not aligned as required */
+  COTTN_E_WORKSPACE = 5, /* workspace NULL or smaller than cottn_workspace_bytes() */
+  COTTN_E_HIP = 6,       /* a HIP call failed (launch error) */
+  COTTN_E_ARG = 7        /* any other invalid argument (eps <= 0, unknown op, ...) */
+} cottn_status;
+
+typedef enum {
+  COTTN_OP_FWD_CAUSAL = 0,
+  COTTN_OP_BWD_CAUSAL = 1,
+  COTTN_OP_FWD_BIDIR = 2,
+  COTTN_OP_BWD_BIDIR = 3,
+  COTTN_OP_STEP = 4
+} cottn_op;
+
+/* Bytes of workspace the given operation needs for these arguments (0 for COTTN_OP_STEP).
+ * Returns (size_t)-1 if the arguments are not supported.  Host only; touches no GPU. */
+size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int dtype);
+
+/* Number of sequence segments per (batch, head) the library will scan in parallel for
+ * these arguments (1 = one serial chunk scan per (b, h)); 0 if unsupported.  Informational:
+ * the chunked regrouping of the cumulative sum of eq. attn_2 is exact for any value.
+ * cottn_tune_segments(g) forces the value for later calls in this process (g <= 0 restores
+ * the built-in heuristic); it must not be called concurrently with other entry points. */
+int cottn_segments(int op, int B, int H, int N, int d, int chunk, int dtype);
+void cottn_tune_segments(int segments);
+
+/* Static, NUL-terminated description of a status code. */
+const char* cottn_status_string(int status);
+
+/* Causal forward (Sec. 4, eq. attn_1 / attn_2).
+ *   Q, K, V [B][H][N][d] in, s [H] in, O [B][H][N][d] out.
+ *   state: NULL, or float[B][H][d][d] out = sum over all N rows of kh^T v (Sec. 5's hidden
+ *   state after the last token, transposed to [d_key][d_value], without s). */
+int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s, void* O,
+                     float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                     int d, int chunk, int dtype, float eps, void* hip_stream);
+
+/* Causal backward (Sec. 4, gradient formulas; dK and dV use the cumulative sum that runs
+ * backward in time).  Takes the raw Q, K, V of the forward call and dO = dL/dO; writes
+ * dQ, dK, dV (same shape and dtype) and ds[H] = dL/ds (overwritten). */
+int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                     void* dQ, void* dK, void* dV, float* ds, void* workspace,
+                     size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                     float eps, void* hip_stream);
+
+/* Bidirectional forward (Sec. 4, eq. subQuadCos, right-hand side).
+ *   state: NULL, or float[B][H][d][d] out = Kh^T V. */
+int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
+                    float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                    int d, int dtype, float eps, void* hip_stream);
+
+/* Bidirectional backward: gradients of cottn_fwd_bidir with respect to raw Q, K, V and s
+ * (the gradient formulas of Sec. 4 with the mask M removed). */
+int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                    void* dQ, void* dK, void* dV, float* ds, void* workspace,
+                    size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                    void* hip_stream);
+
+/* One recurrent decode step for B*H independent states (Sec. 5, eq. hidden_state_obs):
+ *   state[b][h] += kh^T v  (in place), then  o[b][h] = s_h * qh state[b][h]
+ * (the state is read AFTER the update).  q, k, v, o are [B][H][d] in `dtype`. */
+int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
+               void* o, int B, int H, int d, int dtype, float eps, void* hip_stream);
+
+/* Per-kernel timing for benchmarks.  After cottn_profile_start(), every kernel the library
+ * launches is bracketed by two HIP events on its stream; cottn_profile_stop() waits for
+ * those events, adds each kernel's elapsed time to a per-kernel-name total and stops
+ * recording.  The three getters read the totals gathered by the last start/stop pair:
+ * cottn_profile_count() distinct kernel names, and for 0 <= i < count its name (static
+ * storage), number of launches and summed duration in milliseconds.  Profiling adds the
+ * cost of the event records to every launch; it is off by default.  Not thread-safe. */
+int cottn_profile_start(void);
+int cottn_profile_stop(void);
+int cottn_profile_count(void);
+const char* cottn_profile_name(int i);
+long cottn_profile_launches(int i);
+double cottn_profile_ms(int i);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COTTN_H */

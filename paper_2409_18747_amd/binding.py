@@ -1,0 +1,202 @@
+"""ctypes binding of libcottn.so: the same names as the C ABI (include/cottn.h), taking torch
+tensors.  Argument marshalling only — every step of the computation runs in the HIP kernels.
+PyTorch supplies device memory and the stream handle, nothing else.
+
+The library must have been built (``python -m paper_2409_18747_amd.build``); there is no
+fallback: a missing library raises at first use.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+library_path = os.path.join(_HERE, "libcottn.so")
+
+COTTN_F32, COTTN_BF16 = 0, 1
+OP_FWD_CAUSAL, OP_BWD_CAUSAL, OP_FWD_BIDIR, OP_BWD_BIDIR, OP_STEP = range(5)
+
+
+class CottnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, cottn_status_string(status)))
+
+
+def _load():
+    if not os.path.exists(library_path):
+        raise ImportError(
+            "libcottn.so is not built: run `python -m paper_2409_18747_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(library_path)
+    vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.cottn_workspace_bytes.restype = sz
+    lib.cottn_workspace_bytes.argtypes = [i] * 7
+    lib.cottn_segments.restype = i
+    lib.cottn_segments.argtypes = [i] * 7
+    lib.cottn_tune_segments.restype = None
+    lib.cottn_tune_segments.argtypes = [i]
+    lib.cottn_status_string.restype = ctypes.c_char_p
+    lib.cottn_status_string.argtypes = [i]
+    lib.cottn_fwd_causal.restype = i
+    lib.cottn_fwd_causal.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_causal.restype = i
+    lib.cottn_bwd_causal.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_fwd_bidir.restype = i
+    lib.cottn_fwd_bidir.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_bidir.restype = i
+    lib.cottn_bwd_bidir.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
+    lib.cottn_step.restype = i
+    lib.cottn_step.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, f, vp]
+    lib.cottn_profile_start.restype = i
+    lib.cottn_profile_stop.restype = i
+    lib.cottn_profile_count.restype = i
+    lib.cottn_profile_name.restype = ctypes.c_char_p
+    lib.cottn_profile_name.argtypes = [i]
+    lib.cottn_profile_launches.restype = ctypes.c_long
+    lib.cottn_profile_launches.argtypes = [i]
+    lib.cottn_profile_ms.restype = ctypes.c_double
+    lib.cottn_profile_ms.argtypes = [i]
+    return lib
+
+
+lib = _load()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return COTTN_F32
+    if t.dtype == torch.bfloat16:
+        return COTTN_BF16
+    raise TypeError("tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status, where):
+    if status != 0:
+        raise CottnError(status, where)
+
+
+def cottn_status_string(status: int) -> str:
+    return lib.cottn_status_string(int(status)).decode()
+
+
+def cottn_workspace_bytes(op, B, H, N, d, chunk=0, dtype=COTTN_BF16) -> int:
+    n = lib.cottn_workspace_bytes(op, B, H, N, d, chunk, dtype)
+    if n == ctypes.c_size_t(-1).value:
+        raise CottnError(2, "cottn_workspace_bytes")
+    return n
+
+
+def cottn_segments(op, B, H, N, d, chunk=0, dtype=COTTN_BF16) -> int:
+    return lib.cottn_segments(op, B, H, N, d, chunk, dtype)
+
+
+def cottn_tune_segments(segments: int) -> None:
+    lib.cottn_tune_segments(int(segments))
+
+
+def _workspace(op, B, H, N, d, chunk, dtype, device, workspace):
+    need = cottn_workspace_bytes(op, B, H, N, d, chunk, dtype)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    have = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    return workspace, have
+
+
+def cottn_fwd_causal(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, eps=1e-6,
+                     stream=None):
+    """O = s_h (Qhat Khat^T (.) M) V; returns O (allocated if not given).  `state`, if given,
+    receives sum_j khat_j^T v_j as float32 [B, H, d, d]."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    if O is None:
+        O = torch.empty_like(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    st = lib.cottn_fwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
+                              _ptr(workspace), have, B, H, N, d, chunk, dt, eps, _stream(stream))
+    _check(st, "cottn_fwd_causal")
+    return O
+
+
+def cottn_bwd_causal(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None, chunk=0,
+                     eps=1e-6, stream=None):
+    """Gradients of cottn_fwd_causal wrt raw Q, K, V and s; returns (dQ, dK, dV, ds)."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    st = lib.cottn_bwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
+                              _ptr(dV), _ptr(ds), _ptr(workspace), have, B, H, N, d, chunk, dt,
+                              eps, _stream(stream))
+    _check(st, "cottn_bwd_causal")
+    return dQ, dK, dV, ds
+
+
+def cottn_fwd_bidir(Q, K, V, s, O=None, state=None, workspace=None, eps=1e-6, stream=None):
+    """O = s_h Qhat (Khat^T V); returns O."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    if O is None:
+        O = torch.empty_like(Q)
+    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    st = lib.cottn_fwd_bidir(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
+                             _ptr(workspace), have, B, H, N, d, dt, eps, _stream(stream))
+    _check(st, "cottn_fwd_bidir")
+    return O
+
+
+def cottn_bwd_bidir(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None, eps=1e-6,
+                    stream=None):
+    """Gradients of cottn_fwd_bidir; returns (dQ, dK, dV, ds)."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    st = lib.cottn_bwd_bidir(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
+                             _ptr(dV), _ptr(ds), _ptr(workspace), have, B, H, N, d, dt, eps,
+                             _stream(stream))
+    _check(st, "cottn_bwd_bidir")
+    return dQ, dK, dV, ds
+
+
+def cottn_step(q, k, v, s, state, o=None, eps=1e-6, stream=None):
+    """state += khat^T v (in place); returns o = s_h qhat state.  q, k, v are [B, H, d]."""
+    B, H, d = q.shape
+    dt = _dtype_code(q)
+    if o is None:
+        o = torch.empty_like(q)
+    st = lib.cottn_step(_ptr(q), _ptr(k), _ptr(v), _ptr(s), _ptr(state), _ptr(o), B, H, d, dt,
+                        eps, _stream(stream))
+    _check(st, "cottn_step")
+    return o
+
+
+def profile_start():
+    _check(lib.cottn_profile_start(), "cottn_profile_start")
+
+
+def profile_stop():
+    """Returns {kernel name: (launches, total ms)} gathered since profile_start()."""
+    _check(lib.cottn_profile_stop(), "cottn_profile_stop")
+    return {lib.cottn_profile_name(i).decode(): (lib.cottn_profile_launches(i), lib.cottn_profile_ms(i))
+            for i in range(lib.cottn_profile_count())}

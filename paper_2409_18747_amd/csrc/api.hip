@@ -1,0 +1,303 @@
+// C-ABI entry points of libcottn: argument validation (before anything is enqueued, so it
+// works on a host without a GPU), the host-side choice of the sequence split, dispatch to
+// the per-dtype kernel launchers, and the optional per-kernel event timing.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/cottn.h"
+#include "launch.h"
+#include "workspace.h"
+
+namespace cottn {
+namespace {
+
+int g_tuned_segments = 0;  // <= 0: heuristic
+
+// ---- profiling state -------------------------------------------------------------------
+struct PendingSpan { const char* name; hipEvent_t begin, end; };
+struct KernelTotal { const char* name; long launches; double ms; };
+bool g_profile_on = false;
+std::vector<PendingSpan> g_pending;
+std::vector<KernelTotal> g_totals;
+
+bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+bool dims_ok(int B, int H, int N, int d) {
+  if (B < 1 || H < 1 || N < 0) return false;
+  if (d != 32 && d != 64 && d != 128) return false;
+  // element counts must fit comfortably in 64-bit offsets and the grid in 31 bits
+  if (double(B) * H > 16777216.0) return false;
+  if (double(B) * H * double(N) * d > 9.0e15) return false;
+  return true;
+}
+
+}  // namespace
+
+// Split of one (batch, head) sequence into segments; see workspace.h.
+bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan* plan) {
+  if (dtype != COTTN_F32 && dtype != COTTN_BF16) return false;
+  if (!dims_ok(B, H, N, d)) return false;
+  int C;
+  if (dtype == COTTN_BF16) {
+    C = chunk == 0 ? 64 : chunk;
+    if (C != 64 && C != 128 && C != 256) return false;
+    if (C * d > 16384) return false;
+  } else {
+    C = chunk == 0 ? 32 : chunk;
+    if (C != 32) return false;
+  }
+  const long units = long(B) * H;
+  const long n_chunks = (long(N) + C - 1) / C;
+  long want;
+  if (g_tuned_segments > 0) {
+    want = g_tuned_segments;
+  } else {
+    // enough workgroups to cover the 256 compute units about twice
+    const long target = 512;
+    want = (target + units - 1) / units;
+  }
+  if (want > n_chunks) want = n_chunks;
+  if (want < 1) want = 1;
+  const long chunks_per_seg = n_chunks > 0 ? (n_chunks + want - 1) / want : 1;
+  const long G = n_chunks > 0 ? (n_chunks + chunks_per_seg - 1) / chunks_per_seg : 1;
+  if (units * G > 2147483647L / 4) return false;
+  plan->C = C;
+  plan->G = int(G);
+  plan->seg_rows = int(chunks_per_seg * C);
+  (void)op;
+  return true;
+}
+
+bool profile_on() { return g_profile_on; }
+
+void profile_begin(const char* kernel_name, hipStream_t stream) {
+  PendingSpan sp{kernel_name, nullptr, nullptr};
+  if (hipEventCreate(&sp.begin) != hipSuccess || hipEventCreate(&sp.end) != hipSuccess) return;
+  (void)hipEventRecord(sp.begin, stream);
+  g_pending.push_back(sp);
+}
+
+void profile_end(hipStream_t stream) {
+  if (!g_pending.empty()) (void)hipEventRecord(g_pending.back().end, stream);
+}
+
+namespace {
+
+__global__ void fill_zero_f32(float* p, long n) {
+  const long i = long(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+hipError_t zero_f32(float* p, long n, hipStream_t st) {
+  if (p == nullptr || n <= 0) return hipSuccess;
+  return launch("fill_zero_f32", st, [&] {
+    fill_zero_f32<<<unsigned((n + 255) / 256), 256, 0, st>>>(p, n);
+  });
+}
+
+int check_common(const void* const* ptrs, int n_ptrs, int B, int H, int N, int d, int dtype,
+                 float eps) {
+  for (int i = 0; i < n_ptrs; ++i)
+    if (ptrs[i] == nullptr) return COTTN_E_NULL;
+  if (dtype != COTTN_F32 && dtype != COTTN_BF16) return COTTN_E_DTYPE;
+  if (!dims_ok(B, H, N, d)) return COTTN_E_SHAPE;
+  if (!(eps > 0.f)) return COTTN_E_ARG;
+  for (int i = 0; i < n_ptrs; ++i)
+    if (!is_aligned(ptrs[i], 16)) return COTTN_E_ALIGN;
+  return COTTN_OK;
+}
+
+int check_workspace(const void* ws, size_t have, size_t need) {
+  if (need == 0) return COTTN_OK;
+  if (ws == nullptr || have < need) return COTTN_E_WORKSPACE;
+  if (!is_aligned(ws, 256)) return COTTN_E_ALIGN;
+  return COTTN_OK;
+}
+
+int map_hip(hipError_t e) { return e == hipSuccess ? COTTN_OK : COTTN_E_HIP; }
+
+}  // namespace
+}  // namespace cottn
+
+using namespace cottn;
+
+extern "C" {
+
+size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int dtype) {
+  if (op == COTTN_OP_STEP) {
+    return (dtype == COTTN_F32 || dtype == COTTN_BF16) && dims_ok(B, H, 1, d) ? 0 : size_t(-1);
+  }
+  if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_STEP) return size_t(-1);
+  SeqPlan plan;
+  if (!make_plan(op, B, H, N, d, chunk, dtype, &plan)) return size_t(-1);
+  return workspace_bytes_for(op, B, H, d, plan);
+}
+
+int cottn_segments(int op, int B, int H, int N, int d, int chunk, int dtype) {
+  if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_BWD_BIDIR) return 0;
+  SeqPlan plan;
+  if (!make_plan(op, B, H, N, d, chunk, dtype, &plan)) return 0;
+  return plan.G;
+}
+
+void cottn_tune_segments(int segments) { g_tuned_segments = segments; }
+
+const char* cottn_status_string(int status) {
+  switch (status) {
+    case COTTN_OK: return "ok";
+    case COTTN_E_NULL: return "a required pointer is NULL";
+    case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d in {32,64,128}, "
+                               "chunk in {0,64,128,256} with chunk*d <= 16384 (bf16) or {0,32} (fp32)";
+    case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0) or COTTN_BF16 (1)";
+    case COTTN_E_ALIGN: return "tensor pointers must be 16-byte aligned, the workspace 256-byte aligned";
+    case COTTN_E_WORKSPACE: return "workspace is NULL or smaller than cottn_workspace_bytes()";
+    case COTTN_E_HIP: return "a HIP call failed";
+    case COTTN_E_ARG: return "invalid argument";
+    default: return "unknown status";
+  }
+}
+
+int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s, void* O,
+                     float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                     int d, int chunk, int dtype, float eps, void* hip_stream) {
+  const void* req[] = {Q, K, V, s, O};
+  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
+  SeqPlan plan;
+  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  st = check_workspace(workspace, workspace_bytes,
+                       workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, plan));
+  if (st != COTTN_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (N == 0) return map_hip(zero_f32(state, long(B) * H * d * d, stream));
+  CausalArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.workspace = workspace;
+  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.eps = eps; a.stream = stream;
+  return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : fwd_causal_f32(a));
+}
+
+int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                     void* dQ, void* dK, void* dV, float* ds, void* workspace,
+                     size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                     float eps, void* hip_stream) {
+  const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
+  int st = check_common(req, 9, B, H, N, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  SeqPlan plan;
+  if (!make_plan(COTTN_OP_BWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  st = check_workspace(workspace, workspace_bytes,
+                       workspace_bytes_for(COTTN_OP_BWD_CAUSAL, B, H, d, plan));
+  if (st != COTTN_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (N == 0) return map_hip(zero_f32(ds, H, stream));
+  CausalArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
+  a.workspace = workspace;
+  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.eps = eps; a.stream = stream;
+  return map_hip(dtype == COTTN_BF16 ? bwd_causal_bf16(a) : bwd_causal_f32(a));
+}
+
+int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
+                    float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                    int d, int dtype, float eps, void* hip_stream) {
+  const void* req[] = {Q, K, V, s, O};
+  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
+  SeqPlan plan;
+  if (!make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
+  st = check_workspace(workspace, workspace_bytes,
+                       workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, d, plan));
+  if (st != COTTN_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (N == 0) return map_hip(zero_f32(state, long(B) * H * d * d, stream));
+  CausalArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.workspace = workspace;
+  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.eps = eps; a.stream = stream;
+  return map_hip(dtype == COTTN_BF16 ? fwd_bidir_bf16(a) : fwd_bidir_f32(a));
+}
+
+int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                    void* dQ, void* dK, void* dV, float* ds, void* workspace,
+                    size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                    void* hip_stream) {
+  const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
+  int st = check_common(req, 9, B, H, N, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  SeqPlan plan;
+  if (!make_plan(COTTN_OP_BWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
+  st = check_workspace(workspace, workspace_bytes,
+                       workspace_bytes_for(COTTN_OP_BWD_BIDIR, B, H, d, plan));
+  if (st != COTTN_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (N == 0) return map_hip(zero_f32(ds, H, stream));
+  CausalArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
+  a.workspace = workspace;
+  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.eps = eps; a.stream = stream;
+  return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : bwd_bidir_f32(a));
+}
+
+int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
+               void* o, int B, int H, int d, int dtype, float eps, void* hip_stream) {
+  const void* req[] = {q, k, v, s, state, o};
+  int st = check_common(req, 6, B, H, 1, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  StepArgs a{q, k, v, s, state, o, B, H, d, eps, static_cast<hipStream_t>(hip_stream)};
+  return map_hip(step_any(a, dtype));
+}
+
+int cottn_profile_start(void) {
+  g_pending.clear();
+  g_totals.clear();
+  g_profile_on = true;
+  return COTTN_OK;
+}
+
+int cottn_profile_stop(void) {
+  g_profile_on = false;
+  int status = COTTN_OK;
+  for (const PendingSpan& sp : g_pending) {
+    float ms = 0.f;
+    if (sp.end == nullptr || hipEventSynchronize(sp.end) != hipSuccess ||
+        hipEventElapsedTime(&ms, sp.begin, sp.end) != hipSuccess) {
+      status = COTTN_E_HIP;
+    } else {
+      KernelTotal* slot = nullptr;
+      for (KernelTotal& t : g_totals)
+        if (std::strcmp(t.name, sp.name) == 0) slot = &t;
+      if (slot == nullptr) {
+        g_totals.push_back(KernelTotal{sp.name, 0, 0.0});
+        slot = &g_totals.back();
+      }
+      slot->launches += 1;
+      slot->ms += ms;
+    }
+    if (sp.begin) (void)hipEventDestroy(sp.begin);
+    if (sp.end) (void)hipEventDestroy(sp.end);
+  }
+  g_pending.clear();
+  return status;
+}
+
+int cottn_profile_count(void) { return int(g_totals.size()); }
+const char* cottn_profile_name(int i) {
+  return (i >= 0 && i < int(g_totals.size())) ? g_totals[i].name : "";
+}
+long cottn_profile_launches(int i) {
+  return (i >= 0 && i < int(g_totals.size())) ? g_totals[i].launches : 0;
+}
+double cottn_profile_ms(int i) {
+  return (i >= 0 && i < int(g_totals.size())) ? g_totals[i].ms : 0.0;
+}
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+// One recurrent decode step (Sec. 5, eq. hidden_state_obs) for B*H independent d x d fp32
+// states:  S <- S + kh^T v (in place), then o = s_h * qh S with the updated state.
+//
+// The kernel is a pure stream of the state through the chip (read + write of every state
+// byte per step); all arithmetic is fp32 FMAs on the vector ALU.  One workgroup owns one
+// state: a row of the state is covered by d/4 lanes holding a float4 each, so every wave
+// reads and writes whole contiguous rows; all row loads of a thread are issued before any
+// is consumed to keep many requests in flight.  The column sums of qh[row] * S[row][:] are
+// kept per thread and combined across the row groups through LDS at the end.
+#include "device_common.h"
+#include "launch.h"
+
+namespace cottn {
+namespace {
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
+  static __device__ __forceinline__ float4 load4(const float* p) {
+    return *reinterpret_cast<const float4*>(p);
+  }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float x) { *p = f32_to_bf16(x); }
+  static __device__ __forceinline__ float4 load4(const bf16_t* p) {
+    const uint2 raw = *reinterpret_cast<const uint2*>(p);
+    float4 r;
+    r.x = __builtin_bit_cast(float, raw.x << 16);
+    r.y = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
+    r.z = __builtin_bit_cast(float, raw.y << 16);
+    r.w = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
+    return r;
+  }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_step_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+    const float* __restrict__ s, float* __restrict__ state, T* __restrict__ o, int H, float eps) {
+  constexpr int TPR = D / 4;          // threads per state row
+  constexpr int RPP = 256 / TPR;      // rows per pass
+  constexpr int PASSES = D / RPP;
+  __shared__ float qh[D], kh[D];
+  __shared__ float partial[RPP][D];
+
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  const size_t vbase = size_t(unit) * D;
+
+  // every wave normalises q and k for itself (d <= 128: at most two elements per lane);
+  // wave 0 publishes them
+  {
+    const int l = tid % 64;
+    float q0 = Elem<T>::load(q + vbase + (l % D));
+    float k0 = Elem<T>::load(k + vbase + (l % D));
+    float q1 = 0.f, k1 = 0.f;
+    if (D > 64) {
+      q1 = Elem<T>::load(q + vbase + ((l + 64) % D));
+      k1 = Elem<T>::load(k + vbase + ((l + 64) % D));
+    }
+    const bool own = l < D;  // for d = 32 lanes 32..63 duplicate lanes 0..31
+    float qs = own ? q0 * q0 + q1 * q1 : 0.f;
+    float ks = own ? k0 * k0 + k1 * k1 : 0.f;
+    qs = group_sum<64>(qs);
+    ks = group_sum<64>(ks);
+    const float rq = inv_norm(qs, eps), rk = inv_norm(ks, eps);
+    if (tid < 64 && own) {
+      qh[l] = q0 * rq;
+      kh[l] = k0 * rk;
+      if (D > 64) {
+        qh[l + 64] = q1 * rq;
+        kh[l + 64] = k1 * rk;
+      }
+    }
+  }
+  const int col = (tid % TPR) * 4;
+  const int row_in_pass = tid / TPR;
+  const float4 v4 = Elem<T>::load4(v + vbase + col);
+  float* Su = state + size_t(unit) * D * D;
+
+  float4 rows[PASSES];
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p)
+    rows[p] = *reinterpret_cast<const float4*>(Su + size_t(p * RPP + row_in_pass) * D + col);
+  __syncthreads();
+
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) {
+    const int row = p * RPP + row_in_pass;
+    const float kr = kh[row], qr = qh[row];
+    float4 x = rows[p];
+    x.x += kr * v4.x;
+    x.y += kr * v4.y;
+    x.z += kr * v4.z;
+    x.w += kr * v4.w;
+    *reinterpret_cast<float4*>(Su + size_t(row) * D + col) = x;
+    acc.x += qr * x.x;
+    acc.y += qr * x.y;
+    acc.z += qr * x.z;
+    acc.w += qr * x.w;
+  }
+  *reinterpret_cast<float4*>(&partial[row_in_pass][col]) = acc;
+  __syncthreads();
+  if (tid < D) {
+    float sum = 0.f;
+#pragma unroll
+    for (int rpp = 0; rpp < RPP; ++rpp) sum += partial[rpp][tid];
+    Elem<T>::store(o + vbase + tid, s[unit % H] * sum);
+  }
+}
+
+template <typename T>
+hipError_t run_step(const StepArgs& a) {
+  const int units = a.B * a.H;
+  const T* q = static_cast<const T*>(a.q);
+  const T* k = static_cast<const T*>(a.k);
+  const T* v = static_cast<const T*>(a.v);
+  T* o = static_cast<T*>(a.o);
+  switch (a.d) {
+    case 32:
+      return launch("decode_step_kernel", a.stream, [&] {
+        decode_step_kernel<T, 32><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
+      });
+    case 64:
+      return launch("decode_step_kernel", a.stream, [&] {
+        decode_step_kernel<T, 64><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
+      });
+    case 128:
+      return launch("decode_step_kernel", a.stream, [&] {
+        decode_step_kernel<T, 128><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
+      });
+    default:
+      return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t step_any(const StepArgs& a, int dtype) {
+  return dtype == 0 ? run_step<float>(a) : run_step<bf16_t>(a);
+}
+
+}  // namespace cottn

@@ -1,0 +1,44 @@
+// Host-side description of the sequence split and of the workspace each operation uses.
+// One place computes the sizes so that cottn_workspace_bytes() and the launchers agree.
+#pragma once
+#include <stddef.h>
+
+namespace cottn {
+
+// G segments of seg_rows rows (a whole number of chunks of C rows) per (batch, head).
+struct SeqPlan {
+  int C;
+  int G;
+  int seg_rows;
+};
+
+bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan* plan);
+
+inline size_t round_up_256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Workspace layouts (all fp32):
+//   causal forward   G > 1: [units][G][d][d]   segment totals, turned in place into the state
+//                            at each segment start
+//   causal backward  G > 1: the same array for the forward-time states, a second one for
+//                            the reverse-time states; always: [units][G] partial sums of ds
+//   bidirectional forward : [units][G][d][d]   segment totals, slot 0 becomes the full state
+//   bidirectional backward: [units][G][2][d][d] totals of Kh^T V and Qh^T dO, slot 0 becomes
+//                            the full pair; [units] partial sums of ds
+inline size_t state_array_bytes(int B, int H, int d, int G) {
+  return round_up_256(size_t(B) * H * G * d * d * sizeof(float));
+}
+inline size_t ds_partials_bytes(int B, int H, int G) {
+  return round_up_256(size_t(B) * H * G * sizeof(float));
+}
+
+inline size_t workspace_bytes_for(int op, int B, int H, int d, const SeqPlan& p) {
+  switch (op) {
+    case 0: return p.G > 1 ? state_array_bytes(B, H, d, p.G) : 0;
+    case 1: return (p.G > 1 ? 2 * state_array_bytes(B, H, d, p.G) : 0) + ds_partials_bytes(B, H, p.G);
+    case 2: return state_array_bytes(B, H, d, p.G);
+    case 3: return 2 * state_array_bytes(B, H, d, p.G) + ds_partials_bytes(B, H, 1);
+    default: return 0;
+  }
+}
+
+}  // namespace cottn
