@@ -30,7 +30,7 @@
  *   - Base pointers of tensors must be 16-byte aligned; the workspace 256-byte aligned.
  *   - Supported shapes: d in {32, 64, 128}; B, H, N >= 1 (N == 0 is accepted and does
  *     nothing but define the outputs that do not depend on rows); chunk in {0, 64, 128, 256}
- *     for bf16 (0 = library default, 64) with chunk*d <= 16384, and chunk in {0, 32} for fp32.
+ *     for bf16 (0 = library default, 64; d = 128 supports 64 only), and chunk in {0, 32} for fp32.
  *     N need not be a multiple of chunk.
  *   - Return value: COTTN_OK or a cottn_status error code.  Argument errors are detected
  *     before anything is enqueued (so they can be exercised without a GPU); HIP launch

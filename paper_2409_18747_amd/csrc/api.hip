@@ -45,7 +45,7 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
   if (dtype == COTTN_BF16) {
     C = chunk == 0 ? 64 : chunk;
     if (C != 64 && C != 128 && C != 256) return false;
-    if (C * d > 16384) return false;
+    if (d == 128 && C != 64) return false;
   } else {
     C = chunk == 0 ? 32 : chunk;
     if (C != 32) return false;
@@ -151,7 +151,7 @@ const char* cottn_status_string(int status) {
     case COTTN_OK: return "ok";
     case COTTN_E_NULL: return "a required pointer is NULL";
     case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d in {32,64,128}, "
-                               "chunk in {0,64,128,256} with chunk*d <= 16384 (bf16) or {0,32} (fp32)";
+                               "chunk in {0,64,128,256} (bf16; 64 only when d = 128) or {0,32} (fp32)";
     case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0) or COTTN_BF16 (1)";
     case COTTN_E_ALIGN: return "tensor pointers must be 16-byte aligned, the workspace 256-byte aligned";
     case COTTN_E_WORKSPACE: return "workspace is NULL or smaller than cottn_workspace_bytes()";

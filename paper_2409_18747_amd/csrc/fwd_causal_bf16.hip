@@ -47,7 +47,7 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float eps) {
   using Cfg = FwdCfg<D, C>;
-  using ST = StateTiles<D, Cfg::NW>;
+  using ST = AccTiles<D, Cfg::NW>;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
 
@@ -58,11 +58,11 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
-  f32x4 acc[ST::DVT][ST::DKT];
+  f32x4 acc[ST::NCT][ST::NRT];
 #pragma unroll
-  for (int x = 0; x < ST::DVT; ++x)
+  for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < ST::DKT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int y = 0; y < ST::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   TileStage<D, C, Cfg::NT> kst, vst;
   kst.fetch(Ku, row_begin, row_end);
@@ -79,17 +79,17 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     if (ST::active(w)) {
 #pragma unroll
       for (int p = 0; p < C / 32; ++p) {
-        bf16x8 bv[ST::DVT];
+        bf16x8 bv[ST::NCT];
 #pragma unroll
-        for (int x = 0; x < ST::DVT; ++x)
+        for (int x = 0; x < ST::NCT; ++x)
           bv[x] = lds_col_frag(Vs, Cfg::PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                               16 * ST::dv_tile(w, x), r);
+                               16 * ST::col_tile(w, x), r);
 #pragma unroll
-        for (int y = 0; y < ST::DKT; ++y) {
+        for (int y = 0; y < ST::NRT; ++y) {
           bf16x8 ak = lds_col_frag(Ks, Cfg::PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                                   16 * ST::dk_tile(w, y), r);
+                                   16 * ST::row_tile(w, y), r);
 #pragma unroll
-          for (int x = 0; x < ST::DVT; ++x) acc[x][y] = mma16(ak, bv[x], acc[x][y]);
+          for (int x = 0; x < ST::NCT; ++x) acc[x][y] = mma16(ak, bv[x], acc[x][y]);
         }
       }
     }
@@ -97,12 +97,12 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
   if (ST::active(w)) {
     float* out = seg_state + (size_t(unit) * n_slots + g) * D * D;
 #pragma unroll
-    for (int x = 0; x < ST::DVT; ++x)
+    for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-      for (int y = 0; y < ST::DKT; ++y)
+      for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          out[(16 * ST::dk_tile(w, y) + 4 * q4 + v) * D + 16 * ST::dv_tile(w, x) + r] =
+          out[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] =
               acc[x][y][v];
   }
 }
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_prefix, int H, int N, int G, int seg_rows, float eps) {
   using Cfg = FwdCfg<D, C>;
-  using ST = StateTiles<D, Cfg::NW>;
+  using ST = AccTiles<D, Cfg::NW>;
   constexpr int PITCH = Cfg::PITCH;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
@@ -151,17 +151,17 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
   const int row_end = min(N, row_begin + seg_rows);
 
   // running state in fp32 accumulators, seeded with the segment's prefix
-  f32x4 sacc[ST::DVT][ST::DKT];
+  f32x4 sacc[ST::NCT][ST::NRT];
   const float* init = (seg_prefix != nullptr && g > 0)
                           ? seg_prefix + (size_t(unit) * G + g) * D * D : nullptr;
 #pragma unroll
-  for (int x = 0; x < ST::DVT; ++x)
+  for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < ST::DKT; ++y)
+    for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
       for (int v = 0; v < 4; ++v)
         sacc[x][y][v] = (init != nullptr && ST::active(w))
-            ? init[(16 * ST::dk_tile(w, y) + 4 * q4 + v) * D + 16 * ST::dv_tile(w, x) + r] : 0.f;
+            ? init[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] : 0.f;
 
   TileStage<D, C, Cfg::NT> qst, kst, vst;
   qst.fetch(Qu, row_begin, row_end);
@@ -172,14 +172,14 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
     // ---- publish the state (bf16, transposed) and this chunk's tiles
     if (ST::active(w)) {
 #pragma unroll
-      for (int x = 0; x < ST::DVT; ++x)
+      for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-        for (int y = 0; y < ST::DKT; ++y) {
+        for (int y = 0; y < ST::NRT; ++y) {
           uint2 pk;
           pk.x = pack_bf16(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack_bf16(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(St + (16 * ST::dv_tile(w, x) + r) * PITCH +
-                                    16 * ST::dk_tile(w, y) + 4 * q4) = pk;
+          *reinterpret_cast<uint2*>(St + (16 * ST::col_tile(w, x) + r) * PITCH +
+                                    16 * ST::row_tile(w, y) + 4 * q4) = pk;
         }
     }
     qst.commit_normalised(Qs, eps, nullptr);
@@ -245,17 +245,17 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
     if (ST::active(w)) {
 #pragma unroll
       for (int p = 0; p < C / 32; ++p) {
-        bf16x8 bv[ST::DVT];
+        bf16x8 bv[ST::NCT];
 #pragma unroll
-        for (int x = 0; x < ST::DVT; ++x)
+        for (int x = 0; x < ST::NCT; ++x)
           bv[x] = lds_col_frag(Vs, PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                               16 * ST::dv_tile(w, x), r);
+                               16 * ST::col_tile(w, x), r);
 #pragma unroll
-        for (int y = 0; y < ST::DKT; ++y) {
+        for (int y = 0; y < ST::NRT; ++y) {
           bf16x8 ak = lds_col_frag(Ks, PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                                   16 * ST::dk_tile(w, y), r);
+                                   16 * ST::row_tile(w, y), r);
 #pragma unroll
-          for (int x = 0; x < ST::DVT; ++x) sacc[x][y] = mma16(ak, bv[x], sacc[x][y]);
+          for (int x = 0; x < ST::NCT; ++x) sacc[x][y] = mma16(ak, bv[x], sacc[x][y]);
         }
       }
     }
@@ -283,12 +283,12 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
   if (state_out != nullptr && g == G - 1 && ST::active(w)) {
     float* out = state_out + size_t(unit) * D * D;
 #pragma unroll
-    for (int x = 0; x < ST::DVT; ++x)
+    for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-      for (int y = 0; y < ST::DKT; ++y)
+      for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          out[(16 * ST::dk_tile(w, y) + 4 * q4 + v) * D + 16 * ST::dv_tile(w, x) + r] =
+          out[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] =
               sacc[x][y][v];
   }
 }
@@ -332,7 +332,6 @@ hipError_t fwd_causal_bf16(const CausalArgs& a) {
     case 64128: return run_fwd_causal<64, 128>(a);
     case 64256: return run_fwd_causal<64, 256>(a);
     case 128064: return run_fwd_causal<128, 64>(a);
-    case 128128: return run_fwd_causal<128, 128>(a);
     default: return hipErrorInvalidValue;
   }
 }

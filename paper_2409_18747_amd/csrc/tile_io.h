@@ -67,20 +67,21 @@ struct TileStage {
   }
 };
 
-// Which 16x16 tiles of a D x D state a wave accumulates, for a workgroup of NW waves.
-// The state is cut into (D/16)^2 tiles indexed (key tile, value tile).  A wave keeps one
-// or more whole value-tile columns when there are fewer waves than columns, otherwise the
-// waves that share a column split its key tiles.
+// Which 16x16 tiles of a D x D fp32 accumulator matrix a wave owns, for a workgroup of NW
+// waves.  The matrix is cut into (D/16)^2 tiles indexed (row tile, column tile).  A wave
+// keeps one or more whole tile columns when there are fewer waves than columns (so the
+// column-side operand is loaded once per wave); otherwise the waves that share a tile column
+// split its row tiles.
 template <int D, int NW>
-struct StateTiles {
+struct AccTiles {
   static constexpr int DT = D / 16;
-  static constexpr int DVT = (NW >= DT) ? 1 : DT / NW;      // value tiles per wave
-  static constexpr int WPD = (NW >= DT) ? NW / DT : 1;      // waves per value tile
-  static constexpr int DKT = (WPD >= DT) ? 1 : DT / WPD;    // key tiles per wave
-  __device__ static __forceinline__ bool active(int w) { return (w / DT) * DKT < DT; }
-  __device__ static __forceinline__ int dv_tile(int w, int x) { return (w % DT) + x * NW; }
-  __device__ static __forceinline__ int dk_tile(int w, int y) {
-    return (NW >= DT) ? (w / DT) * DKT + y : y;
+  static constexpr int NCT = (NW >= DT) ? 1 : DT / NW;      // column tiles per wave
+  static constexpr int WPC = (NW >= DT) ? NW / DT : 1;      // waves per tile column
+  static constexpr int NRT = (WPC >= DT) ? 1 : DT / WPC;    // row tiles per wave
+  __device__ static __forceinline__ bool active(int w) { return (w / DT) * NRT < DT; }
+  __device__ static __forceinline__ int col_tile(int w, int x) { return (w % DT) + x * NW; }
+  __device__ static __forceinline__ int row_tile(int w, int y) {
+    return (NW >= DT) ? (w / DT) * NRT + y : y;
   }
 };
 

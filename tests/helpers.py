@@ -34,3 +34,35 @@ def to_device(x, dtype):
 
 def to_host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def ds_terms_rss(oracle, x, causal=True):
+    """Root-sum-square, per head, of the terms P_ij * A_ij whose (signed) sum is ds[h].
+
+    ds is a long sum of terms of both signs; when it happens to cancel, |ds| is far below the
+    size of what was added up and a relative error against |ds| alone measures the
+    cancellation, not the arithmetic.  The root-sum-square of the terms is the magnitude a
+    sum of that many independent terms typically has, and is the floor of the scale the ds
+    error is measured against (see rel_err_ds).  Uses only the oracle's similarity matrix
+    and a plain matmul for A = dO V^T; it is a scale, never an expected value.
+    """
+    Q, K, V, dO = (np.asarray(x[k], dtype=np.float64) for k in ("Q", "K", "V", "dO"))
+    B, H, N, d = Q.shape
+    acc = np.zeros(H)
+    for b in range(B):
+        for h in range(H):
+            P = oracle.similarity(Q[b, h], K[b, h])
+            A = dO[b, h] @ V[b, h].T
+            T = P * A
+            if causal:
+                T = np.tril(T)
+            acc[h] += (T ** 2).sum()
+    return np.sqrt(acc)
+
+
+def rel_err_ds(got, ref, rss):
+    """max_h |got - ref| / max(max_h |ref|, max_h rss_h)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = max(np.abs(ref).max(), float(np.max(rss)))
+    return float(np.abs(got - ref).max() / den) if den > 0 else float(np.abs(got).max())

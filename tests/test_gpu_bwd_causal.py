@@ -1,0 +1,79 @@
+"""GPU parity: cottn_bwd_causal (through the C ABI) against the CPU oracle's brute-force gradients."""
+import numpy as np
+import pytest
+
+from helpers import TOL, ds_terms_rss, rel_err, rel_err_ds, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cottn():
+    import paper_2409_18747_amd.binding as b
+    yield b
+    b.cottn_tune_segments(0)
+
+
+def run_bwd(cottn, oracle, B, H, N, d, dtype, seed, chunk=0, segments=0, scale=1.0, mutate=None):
+    import torch
+    from paper_2409_18747_amd import workloads
+    x = workloads.draw(B, H, N, d, dtype, seed, value_scale=scale)
+    if mutate:
+        mutate(x)
+    Q, K, V, dO = (to_device(x[k], dtype) for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    cottn.cottn_tune_segments(segments)
+    dQ, dK, dV, ds = cottn.cottn_bwd_causal(Q, K, V, s, dO, chunk=chunk)
+    torch.cuda.synchronize()
+    if N <= 1024:
+        ref = oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], causal=True)
+    else:
+        ref = oracle.bwd_recurrent(x["Q"], x["K"], x["V"], x["s"], x["dO"])
+    errs = {}
+    for name, got, want in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        errs[name] = rel_err(to_host(got), want)
+    errs["ds"] = rel_err_ds(to_host(ds), ref[3], ds_terms_rss(oracle, x) if N <= 1024 else 0.0)
+    errs["ds_plain"] = rel_err(to_host(ds), ref[3])
+    print("bwd_causal %s B%d H%d N%d d%d chunk%d seg%d: %s" %
+          (dtype, B, H, N, d, chunk, segments, {k: "%.2e" % v for k, v in errs.items()}), flush=True)
+    for name, e in errs.items():
+        if name != "ds_plain":  # reported only: see helpers.ds_terms_rss
+            assert e <= TOL[dtype], (name, e)
+    return dQ, dK, dV, ds
+
+
+@pytest.mark.parametrize("N", [1, 15, 16, 63, 64, 65, 200, 261])
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_bf16_one_segment(cottn, oracle, N, d):
+    run_bwd(cottn, oracle, 2, 3, N, d, "bf16", seed=200 + N + d, segments=1)
+
+
+@pytest.mark.parametrize("segments", [2, 3, 5, 64])
+@pytest.mark.parametrize("d,N", [(64, 517), (128, 330), (32, 700)])
+def test_bf16_segmented(cottn, oracle, segments, d, N):
+    run_bwd(cottn, oracle, 2, 2, N, d, "bf16", seed=8, segments=segments)
+
+
+@pytest.mark.parametrize("chunk,d", [(128, 32), (128, 64), (256, 32), (256, 64)])
+def test_bf16_chunk_sizes(cottn, oracle, chunk, d):
+    for segments in (1, 3):
+        run_bwd(cottn, oracle, 1, 3, 900, d, "bf16", seed=12, chunk=chunk, segments=segments)
+
+
+def test_bf16_default_plan_gpt_shape(cottn, oracle):
+    run_bwd(cottn, oracle, 2, 12, 1024, 64, "bf16", seed=1, segments=0)
+
+
+def test_bf16_zero_rows_and_determinism(cottn, oracle):
+    import torch
+
+    def mutate(x):
+        x["Q"][:, :, 10] = 0.0
+        x["K"][:, :, 20:23] = 0.0
+        x["V"][:, :, 20:23] = 0.0
+
+    a = run_bwd(cottn, oracle, 1, 2, 150, 64, "bf16", seed=6, segments=2, mutate=mutate)
+    b = run_bwd(cottn, oracle, 1, 2, 150, 64, "bf16", seed=6, segments=2, mutate=mutate)
+    for x, y in zip(a, b):
+        assert torch.isfinite(x.float()).all()
+        assert torch.equal(x, y)
