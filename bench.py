@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the cosine-attention hot path on ONE MI355X.
+
+A step is one causal forward + backward (cottn_fwd_causal + cottn_bwd_causal through the C
+ABI) over one synthetic batch of the GPT-shaped workload  B=8, H=12, N=1024, d=64, bf16
+inputs / fp32 accumulation.  Inputs are resident in HBM before the timed region; the step
+rotates over several independent buffer sets so that the tensors are not served from the
+256 MB last-level cache left warm by the previous step.
+
+Prints ONE JSON line: throughput in tokens/s (tokens = B*N per step), the roofline of the
+dominant kernel (per-kernel durations from HIP events inside the library, a second pass of
+the same steps), and the CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# Algorithmic HBM bytes per token-head (one row of one (batch, head)) for each kernel, in
+# units of d * element_size: the tensors the kernel must read plus those it must write.
+KERNEL_ROW_TENSORS = {
+    "fwd_causal_scan_bf16": 4,      # Q, K, V in; O out
+    "bwd_dq_scan_bf16": 5,          # Q, K, V, dO in; dQ out
+    "bwd_dkdv_scan_bf16": 6,        # Q, K, V, dO in; dK, dV out
+    "fwd_segment_state_bf16": 2,    # K, V in (state totals are d*d per segment, added below)
+    "bwd_segment_states_bf16": 4,   # Q, K, V, dO in
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--buffer-sets", type=int, default=4)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2409_18747_amd.binding as cottn
+    from paper_2409_18747_amd import workloads
+
+    w = workloads.WORKLOADS["cfg2_gpt_causal_fwdbwd_bf16"]
+    B, H, N, d = w.B, w.H, w.N, w.d
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.segments:
+        cottn.cottn_tune_segments(args.segments)
+
+    # buffer sets: the first holds the workload's seeded draw, the others are further draws
+    sets = []
+    for i in range(args.buffer_sets):
+        x = workloads.draw(B, H, N, d, w.dtype, w.seed + 1000 * i, w.value_scale)
+        t = {k: torch.from_numpy(x[k]).to(torch.bfloat16).to(dev) for k in ("Q", "K", "V", "dO")}
+        t["s"] = torch.from_numpy(x["s"]).to(dev)
+        for k in ("O", "dQ", "dK", "dV"):
+            t[k] = torch.empty_like(t["Q"])
+        t["ds"] = torch.empty(H, dtype=torch.float32, device=dev)
+        sets.append(t)
+        if i == 0:
+            host_inputs = x
+    ws_bytes = max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, args.chunk),
+                   cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, args.chunk), 256)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        t = sets[i % len(sets)]
+        cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], t["s"], O=t["O"], workspace=ws,
+                               chunk=args.chunk, stream=stream)
+        cottn.cottn_bwd_causal(t["Q"], t["K"], t["V"], t["s"], t["dO"], dQ=t["dQ"], dK=t["dK"],
+                               dV=t["dV"], ds=t["ds"], workspace=ws, chunk=args.chunk,
+                               stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    tokens_per_s = B * N / (ms_per_step * 1e-3)
+
+    # second pass of the same steps with the library's per-kernel HIP events switched on
+    cottn.profile_start()
+    for i in range(args.steps):
+        step(i)
+    prof = cottn.profile_stop()
+    torch.cuda.synchronize()
+    G_f = cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, args.chunk)
+    G_b = cottn.cottn_segments(cottn.OP_BWD_CAUSAL, B, H, N, d, args.chunk)
+    kernels = {}
+    for name, (launches, total_ms) in prof.items():
+        kernels[name] = {"launches_per_step": launches / args.steps,
+                         "avg_us": 1e3 * total_ms / launches}
+    dom = max(prof, key=lambda n: prof[n][1])
+    rows = B * H * N
+    elem = 2
+    alg_bytes = KERNEL_ROW_TENSORS.get(dom, 0) * d * elem * rows
+    dom_s = prof[dom][1] / prof[dom][0] * 1e-3
+    achieved = alg_bytes / dom_s / 1e9 if alg_bytes else None
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                "traffic": None, "avg_us": dom_s * 1e6, "algorithmic_bytes": alg_bytes}
+    # whole-step view: 11 tensors of B*H*N*d bf16 must cross HBM per fwd+bwd
+    step_bytes = 11 * d * elem * rows
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.fwd_quadratic(host_inputs["Q"], host_inputs["K"], host_inputs["V"], host_inputs["s"])
+        oracle.bwd_quadratic(host_inputs["Q"], host_inputs["K"], host_inputs["V"], host_inputs["s"],
+                             host_inputs["dO"])
+        dt = time.perf_counter() - t0
+        cpu = {"value": B * N / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "one full step of the same workload (B=8,H=12,N=1024,d=64): fp64 "
+                         "quadratic-definition forward + brute-force backward, %.2f s" % dt}
+
+    out = {
+        "metric": "causal cosine-attn fwd+bwd tokens/s (B8 H12 N1024 d64 bf16)",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": B, "H": H, "N": N, "d": d,
+                   "chunk": args.chunk or 64, "segments_fwd": G_f, "segments_bwd": G_b,
+                   "buffer_sets": len(sets), "step": "cottn_fwd_causal + cottn_bwd_causal"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "step_hbm": {"algorithmic_bytes": step_bytes, "achieved_GBs": step_gbs,
+                     "frac_of_peak": step_gbs / HBM_PEAK_GBS},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

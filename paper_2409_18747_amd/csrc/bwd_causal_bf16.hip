@@ -584,11 +584,7 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
           Q, K, V, dO, fwd_states, rev_states, a.N, a.G, a.seg_rows, a.eps);
     });
     if (err != hipSuccess) return err;
-    const long total = long(units) * D * D;
-    err = launch("bwd_state_carry", a.stream, [&] {
-      bwd_state_carry<<<dim3(unsigned((total + 255) / 256), 2), 256, 0, a.stream>>>(
-          fwd_states, rev_states, a.G, D * D, total);
-    });
+    err = launch_bwd_state_carry(fwd_states, rev_states, units, a.G, D * D, a.stream);
     if (err != hipSuccess) return err;
   }
   err = launch("bwd_dq_scan_bf16", a.stream, [&] {
@@ -603,12 +599,25 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
         a.N, a.G, a.seg_rows, a.eps);
   });
   if (err != hipSuccess) return err;
-  return launch("bwd_reduce_ds", a.stream, [&] {
-    bwd_reduce_ds<<<a.H, 256, 0, a.stream>>>(ds_partial, a.ds, a.B, a.H, a.G);
-  });
+  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, a.G, a.stream);
 }
 
 }  // namespace
+
+hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
+                                  hipStream_t st) {
+  const long total = long(units) * elems;
+  return launch("bwd_state_carry", st, [&] {
+    bwd_state_carry<<<dim3(unsigned((total + 255) / 256), 2), 256, 0, st>>>(fwd_tot, rev_tot, G,
+                                                                           elems, total);
+  });
+}
+
+hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st) {
+  return launch("bwd_reduce_ds", st, [&] {
+    bwd_reduce_ds<<<H, 256, 0, st>>>(partial, ds, B, H, G);
+  });
+}
 
 hipError_t bwd_causal_bf16(const CausalArgs& a) {
   switch (a.d * 1000 + a.C) {

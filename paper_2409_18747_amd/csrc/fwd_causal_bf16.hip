@@ -308,10 +308,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
           K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, a.eps);
     });
     if (err != hipSuccess) return err;
-    const long total = long(units) * D * D;
-    err = launch("fwd_state_carry", a.stream, [&] {
-      fwd_state_carry<<<unsigned((total + 255) / 256), 256, 0, a.stream>>>(ws, a.G, D * D, total);
-    });
+    err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
     if (err != hipSuccess) return err;
   }
   return launch("fwd_causal_scan_bf16", a.stream, [&] {
@@ -322,6 +319,13 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 }
 
 }  // namespace
+
+hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {
+  const long total = long(units) * elems;
+  return launch("fwd_state_carry", st, [&] {
+    fwd_state_carry<<<unsigned((total + 255) / 256), 256, 0, st>>>(seg_state, G, elems, total);
+  });
+}
 
 hipError_t fwd_causal_bf16(const CausalArgs& a) {
   switch (a.d * 1000 + a.C) {

@@ -38,6 +38,14 @@ hipError_t fwd_bidir_f32(const CausalArgs& a);
 hipError_t bwd_bidir_f32(const CausalArgs& a);
 hipError_t step_any(const StepArgs& a, int dtype);
 
+// small fp32 state kernels shared by the bf16 and fp32 paths (defined next to their kernels)
+hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st);
+hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
+                                  hipStream_t st);
+hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st);
+hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
+                                int elems, float* state, float* ds_partial, hipStream_t st);
+
 // profiling hooks (api.hip)
 bool profile_on();
 void profile_begin(const char* kernel_name, hipStream_t stream);
