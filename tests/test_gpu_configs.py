@@ -1,0 +1,157 @@
+"""GPU parity at the five benchmark configurations' full sizes, in the default launch
+configuration (the one bench.py times).  Where the whole quadratic definition is affordable it
+is compared element by element; for the long-context and decode configurations the linear-time
+oracle covers every element (or a stated subset of sequences) and the quadratic definition
+covers a sample of rows, each computed on its own, including the last row of each sequence."""
+import numpy as np
+import pytest
+
+from helpers import TOL, rel_err, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cottn():
+    import paper_2409_18747_amd.binding as b
+    b.cottn_tune_segments(0)
+    yield b
+    b.cottn_tune_segments(0)
+
+
+def test_config2_gpt_causal_fwd_bwd_full(cottn, oracle):
+    import torch
+    from paper_2409_18747_amd import workloads
+    w = workloads.WORKLOADS["cfg2_gpt_causal_fwdbwd_bf16"]
+    x = workloads.draw_workload(w)
+    Q, K, V, dO = (to_device(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    O = cottn.cottn_fwd_causal(Q, K, V, s, eps=w.eps)
+    dQ, dK, dV, ds = cottn.cottn_bwd_causal(Q, K, V, s, dO, eps=w.eps)
+    torch.cuda.synchronize()
+    O_ref = oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"], eps=w.eps)
+    refs = oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], eps=w.eps)
+    errs = {"O": rel_err(to_host(O), O_ref)}
+    for name, got, want in zip(("dQ", "dK", "dV", "ds"), (dQ, dK, dV, ds), refs):
+        errs[name] = rel_err(to_host(got), want)
+    print("config 2:", {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= TOL["bf16"], (name, e)
+
+
+def test_config3_bert_bidirectional_fwd_bwd_full(cottn, oracle):
+    import torch
+    from paper_2409_18747_amd import workloads
+    w = workloads.WORKLOADS["cfg3_bert_bidir_fwdbwd_bf16"]
+    x = workloads.draw_workload(w)
+    Q, K, V, dO = (to_device(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    O = cottn.cottn_fwd_bidir(Q, K, V, s, eps=w.eps)
+    dQ, dK, dV, ds = cottn.cottn_bwd_bidir(Q, K, V, s, dO, eps=w.eps)
+    torch.cuda.synchronize()
+    O_ref = oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"], eps=w.eps, causal=False)
+    refs = oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], eps=w.eps, causal=False)
+    errs = {"O": rel_err(to_host(O), O_ref)}
+    for name, got, want in zip(("dQ", "dK", "dV", "ds"), (dQ, dK, dV, ds), refs):
+        errs[name] = rel_err(to_host(got), want)
+    print("config 3:", {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= TOL["bf16"], (name, e)
+
+
+_cfg4_cache = {}
+
+
+def _cfg4_reference(oracle):
+    """Inputs and oracle results of config 4, computed once for the three chunk sizes."""
+    if not _cfg4_cache:
+        from paper_2409_18747_amd import workloads
+        w = workloads.WORKLOADS["cfg4_long_causal_fwdbwd_bf16"]
+        x = workloads.draw_workload(w)
+        O_ref, S_ref = oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"], eps=w.eps)
+        refs = oracle.bwd_recurrent(x["Q"], x["K"], x["V"], x["s"], x["dO"], eps=w.eps)
+        rng = np.random.default_rng(4)
+        rows = [(0, h, int(i)) for h in range(w.H)
+                for i in list(rng.integers(0, w.N, 3)) + [0, w.N - 1]]
+        o_rows = oracle.fwd_rows(x["Q"], x["K"], x["V"], x["s"], rows, eps=w.eps)
+        g_rows = oracle.bwd_rows(x["Q"], x["K"], x["V"], x["s"], x["dO"], rows, eps=w.eps)
+        _cfg4_cache.update(w=w, x=x, O_ref=O_ref, S_ref=S_ref, refs=refs, rows=rows,
+                           o_rows=o_rows, g_rows=g_rows)
+    return _cfg4_cache
+
+
+@pytest.mark.parametrize("chunk", [64, 128, 256])
+def test_config4_long_context_causal_fwd_bwd(cottn, oracle, chunk):
+    import torch
+    c = _cfg4_reference(oracle)
+    w, x = c["w"], c["x"]
+    B, H, N, d = w.B, w.H, w.N, w.d
+    Q, K, V, dO = (to_device(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    state = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    O = cottn.cottn_fwd_causal(Q, K, V, s, state=state, chunk=chunk, eps=w.eps)
+    dQ, dK, dV, ds = cottn.cottn_bwd_causal(Q, K, V, s, dO, chunk=chunk, eps=w.eps)
+    torch.cuda.synchronize()
+    print("config 4 chunk %d: %d segments" %
+          (chunk, cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk)), flush=True)
+    # every element against the linear-time oracle
+    O_ref, S_ref, refs = c["O_ref"], c["S_ref"], c["refs"]
+    got = {"O": to_host(O), "dQ": to_host(dQ), "dK": to_host(dK), "dV": to_host(dV)}
+    errs = {"O": rel_err(got["O"], O_ref), "state": rel_err(to_host(state), S_ref)}
+    for name, want in zip(("dQ", "dK", "dV"), refs[:3]):
+        errs[name] = rel_err(got[name], want)
+    errs["ds"] = rel_err(to_host(ds), refs[3])
+    # sampled rows against the quadratic definition, each row from its own sum
+    rows, o_rows = c["rows"], c["o_rows"]
+    q_rows, k_rows, v_rows = c["g_rows"]
+    pick = lambda a: np.stack([a[b, h, i] for b, h, i in rows])
+    scale = {n: np.abs(ref).max() for n, ref in zip(("O", "dQ", "dK", "dV"), (O_ref,) + refs[:3])}
+    errs["O_rows"] = float(np.abs(pick(got["O"]) - o_rows).max() / scale["O"])
+    errs["dQ_rows"] = float(np.abs(pick(got["dQ"]) - q_rows).max() / scale["dQ"])
+    errs["dK_rows"] = float(np.abs(pick(got["dK"]) - k_rows).max() / scale["dK"])
+    errs["dV_rows"] = float(np.abs(pick(got["dV"]) - v_rows).max() / scale["dV"])
+    print("config 4 chunk %d:" % chunk, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= TOL["bf16"], (name, e)
+
+
+def test_config5_prefill_then_decode_steps(cottn, oracle):
+    """256 sequences x 16 heads, d = 128: causal prefill of 2048 tokens writes the state, then
+    4096 single-token steps.  All 6144 outputs of a fixed subset of sequences are compared with
+    the recurrent oracle run over the whole 6144-token sequence, and sampled rows (incl. the
+    last) with the quadratic causal definition."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    w = workloads.WORKLOADS["cfg5_decode_bf16"]
+    B, H, N1, d, T = w.B, w.H, w.N, w.d, w.extra["steps"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    mk = lambda *shape: torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Q, K, V = mk(B, H, N1, d), mk(B, H, N1, d), mk(B, H, N1, d)
+    qs, ks, vs = mk(T, B, H, d), mk(T, B, H, d), mk(T, B, H, d)
+    s_host = np.random.default_rng(w.seed).uniform(0.5, 1.5, H).astype(np.float32)
+    s = torch.from_numpy(s_host).cuda()
+    state = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    O = cottn.cottn_fwd_causal(Q, K, V, s, state=state, eps=w.eps)
+    outs = torch.empty(T, B, H, d, dtype=torch.bfloat16, device="cuda")
+    for t in range(T):
+        cottn.cottn_step(qs[t], ks[t], vs[t], s, state, o=outs[t], eps=w.eps)
+    torch.cuda.synchronize()
+    seqs = [0, 101, 255]
+    host = lambda t: t.float().cpu().numpy().astype(np.float64)
+    cat = lambda a, b: np.concatenate([host(a[seqs]), host(b[:, seqs]).transpose(1, 2, 0, 3)], axis=2)
+    Qa, Ka, Va = cat(Q, qs), cat(K, ks), cat(V, vs)          # [3, H, 6144, d]
+    O_ref, S_ref = oracle.fwd_recurrent(Qa, Ka, Va, s_host, eps=w.eps)
+    got = cat(O, outs)
+    errs = {"prefill": rel_err(got[:, :, :N1], O_ref[:, :, :N1]),
+            "steps": rel_err(got[:, :, N1:], O_ref[:, :, N1:]),
+            "final_state": rel_err(host(state[seqs]), S_ref)}
+    rng = np.random.default_rng(5)
+    rows = [(b, h, int(i)) for b in range(len(seqs)) for h in (0, 7, 15)
+            for i in list(rng.integers(N1, N1 + T, 2)) + [N1 - 1, N1, N1 + T - 1]]
+    o_rows = oracle.fwd_rows(Qa, Ka, Va, s_host, rows, eps=w.eps)
+    pick = np.stack([got[b, h, i] for b, h, i in rows])
+    errs["rows_vs_quadratic"] = float(np.abs(pick - o_rows).max() / np.abs(O_ref).max())
+    print("config 5:", {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    for name, e in errs.items():
+        assert e <= TOL["bf16"], (name, e)
