@@ -74,15 +74,16 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
 
 bool profile_on() { return g_profile_on; }
 
-void profile_begin(const char* kernel_name, hipStream_t stream) {
+void profile_events(const char* kernel_name, hipEvent_t* begin, hipEvent_t* end) {
   PendingSpan sp{kernel_name, nullptr, nullptr};
-  if (hipEventCreate(&sp.begin) != hipSuccess || hipEventCreate(&sp.end) != hipSuccess) return;
-  (void)hipEventRecord(sp.begin, stream);
+  if (hipEventCreate(&sp.begin) != hipSuccess) return;
+  if (hipEventCreate(&sp.end) != hipSuccess) {
+    (void)hipEventDestroy(sp.begin);
+    return;
+  }
   g_pending.push_back(sp);
-}
-
-void profile_end(hipStream_t stream) {
-  if (!g_pending.empty()) (void)hipEventRecord(g_pending.back().end, stream);
+  *begin = sp.begin;
+  *end = sp.end;
 }
 
 namespace {
@@ -94,9 +95,8 @@ __global__ void fill_zero_f32(float* p, long n) {
 
 hipError_t zero_f32(float* p, long n, hipStream_t st) {
   if (p == nullptr || n <= 0) return hipSuccess;
-  return launch("fill_zero_f32", st, [&] {
-    fill_zero_f32<<<unsigned((n + 255) / 256), 256, 0, st>>>(p, n);
-  });
+  return launch_kernel("fill_zero_f32", fill_zero_f32, dim3(unsigned((n + 255) / 256)), dim3(256),
+                       0, st, p, n);
 }
 
 int check_common(const void* const* ptrs, int n_ptrs, int B, int H, int N, int d, int dtype,

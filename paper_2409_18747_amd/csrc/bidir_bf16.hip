@@ -75,20 +75,24 @@ __global__ __launch_bounds__(C * 4) void bidir_totals_bf16(
     }
     __syncthreads();
     if (AT::active(w)) {
+      bf16x8 by[C / 32][AT::NCT], ax[C / 32][AT::NRT];
 #pragma unroll
       for (int p = 0; p < C / 32; ++p) {
         const int k0 = 32 * p + 8 * q4;
-        bf16x8 by[AT::NCT];
 #pragma unroll
         for (int x = 0; x < AT::NCT; ++x)
-          by[x] = lds_col_frag(Ys, PITCH, k0, k0 + 4, 16 * AT::col_tile(w, x), r);
+          by[p][x] = lds_col_frag(Ys, PITCH, k0, k0 + 4, 16 * AT::col_tile(w, x), r);
 #pragma unroll
-        for (int y = 0; y < AT::NRT; ++y) {
-          const bf16x8 ax = lds_col_frag(Xs, PITCH, k0, k0 + 4, 16 * AT::row_tile(w, y), r);
-#pragma unroll
-          for (int x = 0; x < AT::NCT; ++x) acc[x][y] = mma16(ax, by[x], acc[x][y]);
-        }
+        for (int y = 0; y < AT::NRT; ++y)
+          ax[p][y] = lds_col_frag(Xs, PITCH, k0, k0 + 4, 16 * AT::row_tile(w, y), r);
       }
+      __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
+#pragma unroll
+      for (int p = 0; p < C / 32; ++p)
+#pragma unroll
+        for (int y = 0; y < AT::NRT; ++y)
+#pragma unroll
+          for (int x = 0; x < AT::NCT; ++x) acc[x][y] = mma16(ax[p][y], by[p][x], acc[x][y]);
     }
   }
   if (AT::active(w)) {
@@ -180,13 +184,19 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
     f32x4 oacc[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bf16x8 qf[Cfg::KS], sf[Cfg::KS][Cfg::DT];
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      const bf16x8 qf = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
+      qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
-        oacc[nt] = mma16(qf, lds_row_frag(St + (16 * nt + r) * PITCH + 32 * ks + 8 * q4), oacc[nt]);
+        sf[ks][nt] = lds_row_frag(St + (16 * nt + r) * PITCH + 32 * ks + 8 * q4);
     }
+    __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
+#pragma unroll
+    for (int ks = 0; ks < Cfg::KS; ++ks)
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(qf[ks], sf[ks][nt], oacc[nt]);
     wave_lds_sync();
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt)
@@ -309,14 +319,22 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
       const int off = (16 * w + r) * PITCH + 32 * ks + 8 * q4;
       const bf16x8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off),
                    kf = lds_row_frag(Ks + off);
+      bf16x8 srow[Cfg::DT], grow[Cfg::DT], gcol[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
         const int soff = (16 * nt + r) * PITCH + 32 * ks + 8 * q4;
-        dq[nt] = mma16(gf, lds_row_frag(Sl + soff), dq[nt]);   // dO S^T  (over d_value)
-        dk[nt] = mma16(vf, lds_row_frag(Gl + soff), dk[nt]);   // V G^T   (over d_value)
-        dv[nt] = mma16(kf, lds_col_frag(Gl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4,
-                                        16 * nt, r), dv[nt]);  // Kh G    (over d_key)
+        srow[nt] = lds_row_frag(Sl + soff);
+        grow[nt] = lds_row_frag(Gl + soff);
+        gcol[nt] = lds_col_frag(Gl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       }
+      __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DT; ++nt) {
+        dq[nt] = mma16(gf, srow[nt], dq[nt]);   // dO S^T  (over d_value)
+        dk[nt] = mma16(vf, grow[nt], dk[nt]);   // V G^T   (over d_value)
+        dv[nt] = mma16(kf, gcol[nt], dv[nt]);   // Kh G    (over d_key)
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     // every tile row is private to its wave here: stage the results in place
     normalise_backward_rows<D>(dq, Qs, Gs, rq, scale, r_clamped, w, r, q4);
@@ -353,17 +371,15 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
   const bf16_t* K = static_cast<const bf16_t*>(a.K);
   const bf16_t* V = static_cast<const bf16_t*>(a.V);
   float* totals = static_cast<float*>(a.workspace);
-  hipError_t err = launch("bidir_totals_bf16", a.stream, [&] {
-    bidir_totals_bf16<D, C><<<dim3(units * a.G, 1), Cfg::NT, 0, a.stream>>>(
-        K, V, K, V, totals, 0, a.N, a.G, a.seg_rows, a.eps);
-  });
+  hipError_t err = launch_kernel("bidir_totals_bf16", bidir_totals_bf16<D, C>, dim3(units * a.G, 1),
+                                 dim3(Cfg::NT), 0, a.stream, K, V, K, V, totals, size_t(0), a.N, a.G,
+                                 a.seg_rows, a.eps);
   if (err != hipSuccess) return err;
   err = launch_bidir_combine(totals, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
   if (err != hipSuccess) return err;
-  return launch("fwd_bidir_apply_bf16", a.stream, [&] {
-    fwd_bidir_apply_bf16<D, C><<<units * a.G, Cfg::NT, 0, a.stream>>>(
-        Q, a.s, static_cast<bf16_t*>(a.O), totals, a.H, a.N, a.G, a.seg_rows, a.eps);
-  });
+  return launch_kernel("fwd_bidir_apply_bf16", fwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, Q, a.s, static_cast<bf16_t*>(a.O), totals, a.H,
+                       a.N, a.G, a.seg_rows, a.eps);
 }
 
 template <int D>
@@ -379,29 +395,25 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
   float* totals = reinterpret_cast<float*>(ws);
   const size_t pair_stride = state_array_bytes(a.B, a.H, D, a.G) / sizeof(float);
   float* ds_partial = reinterpret_cast<float*>(ws + 2 * state_array_bytes(a.B, a.H, D, a.G));
-  hipError_t err = launch("bidir_totals_bf16", a.stream, [&] {
-    bidir_totals_bf16<D, C><<<dim3(units * a.G, 2), Cfg::NT, 0, a.stream>>>(
-        K, V, Q, dO, totals, pair_stride, a.N, a.G, a.seg_rows, a.eps);
-  });
+  hipError_t err = launch_kernel("bidir_totals_bf16", bidir_totals_bf16<D, C>, dim3(units * a.G, 2),
+                                 dim3(Cfg::NT), 0, a.stream, K, V, Q, dO, totals, pair_stride, a.N,
+                                 a.G, a.seg_rows, a.eps);
   if (err != hipSuccess) return err;
   err = launch_bidir_combine(totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
                              a.stream);
   if (err != hipSuccess) return err;
-  return launch("bwd_bidir_apply_bf16", a.stream, [&] {
-    bwd_bidir_apply_bf16<D, C><<<units * a.G, Cfg::NT, 0, a.stream>>>(
-        Q, K, V, dO, a.s, static_cast<bf16_t*>(a.dQ), static_cast<bf16_t*>(a.dK),
-        static_cast<bf16_t*>(a.dV), totals, pair_stride, ds_partial, a.ds, a.B, a.H, a.N, a.G,
-        a.seg_rows, a.eps);
-  });
+  return launch_kernel("bwd_bidir_apply_bf16", bwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, Q, K, V, dO, a.s, static_cast<bf16_t*>(a.dQ),
+                       static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), totals, pair_stride,
+                       ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, a.eps);
 }
 
 }  // namespace
 
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st) {
-  return launch("bidir_combine", st, [&] {
-    bidir_combine<<<units, 256, 0, st>>>(totals, pair_stride, n_pairs, G, elems, state, ds_partial);
-  });
+  return launch_kernel("bidir_combine", bidir_combine, dim3(units), dim3(256), 0, st, totals,
+                       pair_stride, n_pairs, G, elems, state, ds_partial);
 }
 
 hipError_t fwd_bidir_bf16(const CausalArgs& a) {

@@ -90,11 +90,29 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   return r;
 }
 
-// Sum over the `width` consecutive lanes (a power of two <= 64) that contain this lane.
+// x of another lane of the same row of 16 lanes, chosen by a DPP control word: no LDS
+// traffic and no extra latency, unlike a general cross-lane permute.
+template <int DPP_CTRL>
+__device__ __forceinline__ float dpp_read(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), DPP_CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the `width` consecutive lanes (a power of two <= 64) that contain this lane; every
+// lane of the group ends with the total.  Up to 16 lanes this is DPP only: swap within
+// pairs, swap pairs within quads, then mirror the 8-lane half-row and the 16-lane row (after
+// the earlier steps every lane of a quad holds the same value, so a mirror pairs each quad
+// with a quad of the other half).
 template <int width>
 __device__ __forceinline__ float group_sum(float x) {
-#pragma unroll
-  for (int m = width >> 1; m > 0; m >>= 1) x += __shfl_xor(x, m, 64);
+  static_assert(width == 1 || width == 2 || width == 4 || width == 8 || width == 16 ||
+                width == 32 || width == 64, "width must be a power of two");
+  if (width >= 2) x += dpp_read<0xB1>(x);    // quad_perm [1,0,3,2]
+  if (width >= 4) x += dpp_read<0x4E>(x);    // quad_perm [2,3,0,1]
+  if (width >= 8) x += dpp_read<0x141>(x);   // row_half_mirror
+  if (width >= 16) x += dpp_read<0x140>(x);  // row_mirror
+  if (width >= 32) x += __shfl_xor(x, 16, 64);
+  if (width >= 64) x += __shfl_xor(x, 32, 64);
   return x;
 }
 

@@ -411,20 +411,18 @@ hipError_t run_fwd(const CausalArgs& a, bool causal) {
   if ((err = allow_lds(segment_totals_f32<D>, lds_tot<D>())) != hipSuccess) return err;
   if ((err = allow_lds(fwd_scan_f32<D>, lds_fwd<D>())) != hipSuccess) return err;
   if (!causal || a.G > 1) {
-    err = launch("segment_totals_f32", a.stream, [&] {
-      segment_totals_f32<D><<<dim3(units * a.G, 1), NT, lds_tot<D>(), a.stream>>>(
-          K, V, K, V, ws, 0, a.N, a.G, a.seg_rows, a.eps, causal ? 1 : 0);
-    });
+    err = launch_kernel("segment_totals_f32", segment_totals_f32<D>, dim3(units * a.G, 1), dim3(NT),
+                        lds_tot<D>(), a.stream, K, V, K, V, ws, size_t(0), a.N, a.G, a.seg_rows,
+                        a.eps, causal ? 1 : 0);
     if (err != hipSuccess) return err;
     err = causal ? launch_fwd_state_carry(ws, units, a.G, D * D, a.stream)
                  : launch_bidir_combine(ws, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
     if (err != hipSuccess) return err;
   }
-  return launch("fwd_scan_f32", a.stream, [&] {
-    fwd_scan_f32<D><<<units * a.G, NT, lds_fwd<D>(), a.stream>>>(
-        Q, K, V, a.s, static_cast<float*>(a.O), causal ? a.state : nullptr,
-        (!causal || a.G > 1) ? ws : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps, causal ? 1 : 0);
-  });
+  return launch_kernel("fwd_scan_f32", fwd_scan_f32<D>, dim3(units * a.G), dim3(NT), lds_fwd<D>(),
+                       a.stream, Q, K, V, a.s, static_cast<float*>(a.O),
+                       causal ? a.state : nullptr, (!causal || a.G > 1) ? ws : nullptr, a.H, a.N,
+                       a.G, a.seg_rows, a.eps, causal ? 1 : 0);
 }
 
 template <int D>
@@ -445,27 +443,24 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
   if ((err = allow_lds(bwd_dq_scan_f32<D>, lds_dq<D>())) != hipSuccess) return err;
   if ((err = allow_lds(bwd_dkdv_scan_f32<D>, lds_dkdv<D>())) != hipSuccess) return err;
   if (have_states) {
-    err = launch("segment_totals_f32", a.stream, [&] {
-      segment_totals_f32<D><<<dim3(units * a.G, 2), NT, lds_tot<D>(), a.stream>>>(
-          K, V, Q, dO, st0, arr / sizeof(float), a.N, a.G, a.seg_rows, a.eps, causal ? 1 : 0);
-    });
+    err = launch_kernel("segment_totals_f32", segment_totals_f32<D>, dim3(units * a.G, 2), dim3(NT),
+                        lds_tot<D>(), a.stream, K, V, Q, dO, st0, arr / sizeof(float), a.N, a.G,
+                        a.seg_rows, a.eps, causal ? 1 : 0);
     if (err != hipSuccess) return err;
     err = causal ? launch_bwd_state_carry(st0, st1, units, a.G, D * D, a.stream)
                  : launch_bidir_combine(st0, arr / sizeof(float), 2, units, a.G, D * D, nullptr,
                                         ds_partial, a.stream);
     if (err != hipSuccess) return err;
   }
-  err = launch("bwd_dq_scan_f32", a.stream, [&] {
-    bwd_dq_scan_f32<D><<<units * a.G, NT, lds_dq<D>(), a.stream>>>(
-        Q, K, V, dO, a.s, static_cast<float*>(a.dQ), st0, causal ? ds_partial : nullptr, a.H, a.N,
-        a.G, a.seg_rows, a.eps, causal ? 1 : 0);
-  });
+  err = launch_kernel("bwd_dq_scan_f32", bwd_dq_scan_f32<D>, dim3(units * a.G), dim3(NT),
+                      lds_dq<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dQ), st0,
+                      causal ? ds_partial : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps,
+                      causal ? 1 : 0);
   if (err != hipSuccess) return err;
-  err = launch("bwd_dkdv_scan_f32", a.stream, [&] {
-    bwd_dkdv_scan_f32<D><<<units * a.G, NT, lds_dkdv<D>(), a.stream>>>(
-        Q, K, V, dO, a.s, static_cast<float*>(a.dK), static_cast<float*>(a.dV), st1, a.H, a.N, a.G,
-        a.seg_rows, a.eps, causal ? 1 : 0);
-  });
+  err = launch_kernel("bwd_dkdv_scan_f32", bwd_dkdv_scan_f32<D>, dim3(units * a.G), dim3(NT),
+                      lds_dkdv<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dK),
+                      static_cast<float*>(a.dV), st1, a.H, a.N, a.G, a.seg_rows, a.eps,
+                      causal ? 1 : 0);
   if (err != hipSuccess) return err;
   // causal: partials per (unit, segment); bidirectional: one share per unit from the combine
   return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : 1, a.stream);

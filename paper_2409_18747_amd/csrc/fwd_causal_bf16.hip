@@ -12,13 +12,26 @@
 // With G = 1 only the scan kernel runs; with one chunk per segment this is the fully
 // chunk-parallel form.
 //
+// Normalisation (Sec. 3.2) without touching Q and K element-wise: with r_i = 1/max(|q_i|,eps)
+// and r_j = 1/max(|k_j|,eps),
+//     O_i = s_h r_i [ sum_{j<=i} (q_i . k_j) (r_j v_j) + q_i S ],   S = sum_j k_j^T (r_j v_j),
+// so the raw Q and K rows are the MFMA operands, V is rescaled by r_j on its way into LDS,
+// and r_i multiplies the finished output row.
+//
 // Work split inside the scan workgroup (C/16 waves): wave w owns query rows 16w..16w+15 of
 // the chunk for the output, and a fixed set of 16x16 tiles of the state for the update.
-// Tiles of normalised Q, K and raw V sit row-major in LDS; operands whose contraction
-// index is the token are read with the transposing LDS read, so no transposed copy is kept.
-// The masked similarity tile is produced as P^T = Kh Qh^T, whose accumulator layout is
-// exactly the A-operand layout of the following P V product (with the token slots
-// permuted the same way on the V side), so P never touches LDS.
+// Tiles sit row-major in LDS; operands whose contraction index is the token are read with
+// the transposing LDS read, so no transposed copy is kept.  The masked similarity tile is
+// produced as P^T = K Q^T, whose accumulator layout is the operand layout the following
+// product needs (with the token slots permuted the same way on the V side), so P never
+// touches LDS; the V fragments read for P V are reused by the state update.  Outputs are
+// accumulated transposed (O^T = V^T P^T + S^T Q^T) so that a lane ends up with 4 consecutive
+// columns of one output row: one row factor per lane and 8-byte staging writes.
+//
+// Scheduling: the kernels are bound by instruction issue and latency, not by MFMA rate, so
+// every group of MFMAs is preceded by all of its LDS reads, issued back to back into distinct
+// registers (a scheduling barrier keeps the compiler from sinking a read next to its use),
+// and the next chunk's tiles are prefetched into registers while the current one is computed.
 #include "device_common.h"
 #include "launch.h"
 #include "tile_io.h"
@@ -32,45 +45,56 @@ struct FwdCfg {
   static constexpr int NT = NW * 64;
   static constexpr int DT = D / 16;
   static constexpr int KS = D / 32;     // k steps of a contraction over the feature dim
+  static constexpr int NP = C / 32;     // pairs of 16-token tiles in a chunk
   static constexpr int PITCH = lds_pitch(D);
   static constexpr int TILE = C * PITCH;            // elements of one [C][D] LDS tile
   static constexpr int STATE = D * PITCH;           // elements of the [D][D] bf16 state copy
+  static constexpr int LDS_BYTES = 2 * (3 * TILE + STATE) + 4 * C;
+  static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
+  // waves per SIMD the register allocation is capped for (two workgroups per compute unit
+  // when LDS allows, never more than the hardware needs for one workgroup)
+  static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
+  static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
 };
 
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
 // grid = units * n_compute workgroups; segment g of a unit writes slot g of the unit's
-// n_slots slots.  The causal forward computes all segments but the last (n_compute =
-// n_slots - 1), the bidirectional forward all of them.
+// n_slots slots (the causal forward computes all segments but the last).
 template <int D, int C>
 __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, float* __restrict__ seg_state,
-    int N, int n_slots, int n_compute, int seg_rows, float eps) {
+    int N, int n_slots, int n_compute, int seg_rows, float inv_eps) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
 
   const int unit = blockIdx.x / n_compute, g = blockIdx.x % n_compute;
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64, r = l % 16, q4 = l / 16;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
+            r = l % 16, q4 = l / 16;
   const bf16_t* Ku = K + size_t(unit) * N * D;
   const bf16_t* Vu = V + size_t(unit) * N * D;
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
+  // acc[x][y] = S tile (key tile row_tile(y), value tile col_tile(x))
   f32x4 acc[ST::NCT][ST::NRT];
 #pragma unroll
   for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
     for (int y = 0; y < ST::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  TileStage<D, C, Cfg::NT> kst, vst;
+  Stage kst, vst;
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
+    float rk[Stage::PASSES];
+    kst.row_rinv(inv_eps, rk);
     __syncthreads();  // previous chunk's reads of Ks/Vs are done
-    kst.commit_normalised(Ks, eps, nullptr);
-    vst.commit_plain(Vs);
+    kst.commit_plain(Ks);
+    vst.commit_scaled(Vs, rk);
     if (row0 + C < row_end) {
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
@@ -78,19 +102,21 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     __syncthreads();
     if (ST::active(w)) {
 #pragma unroll
-      for (int p = 0; p < C / 32; ++p) {
-        bf16x8 bv[ST::NCT];
+      for (int p = 0; p < Cfg::NP; ++p) {
+        const int k0 = 32 * p + 8 * q4;
+        bf16x8 bv[ST::NCT], ak[ST::NRT];
 #pragma unroll
         for (int x = 0; x < ST::NCT; ++x)
-          bv[x] = lds_col_frag(Vs, Cfg::PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                               16 * ST::col_tile(w, x), r);
+          bv[x] = lds_col_frag(Vs, Cfg::PITCH, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
 #pragma unroll
-        for (int y = 0; y < ST::NRT; ++y) {
-          bf16x8 ak = lds_col_frag(Ks, Cfg::PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                                   16 * ST::row_tile(w, y), r);
+        for (int y = 0; y < ST::NRT; ++y)
+          ak[y] = lds_col_frag(Ks, Cfg::PITCH, k0, k0 + 4, 16 * ST::row_tile(w, y), r);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int x = 0; x < ST::NCT; ++x) acc[x][y] = mma16(ak, bv[x], acc[x][y]);
-        }
+        for (int y = 0; y < ST::NRT; ++y)
+#pragma unroll
+          for (int x = 0; x < ST::NCT; ++x) acc[x][y] = mma16(ak[y], bv[x], acc[x][y]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -126,21 +152,29 @@ __global__ __launch_bounds__(256) void fwd_state_carry(float* __restrict__ seg_s
 
 // ---------------------------------------------------------------------------------------
 // Kernel 3: the chunk scan of one segment.
+// The running state is held TRANSPOSED in the accumulators: tile (y, x) of the wave covers
+// value rows 16*row_tile(y).. and key columns 16*col_tile(x)..; element [v] of lane (r, q4)
+// is S[key 16ct + r][value 16rt + 4 q4 + v].  That way a lane holds 4 consecutive values
+// of one key row, which it publishes to the row-major LDS copy Sl[key][value] with one
+// 8-byte write, and the update's row-side operand is the V fragment already read for P V.
 template <int D, int C>
-__global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
+__global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causal_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
-    const float* __restrict__ seg_prefix, int H, int N, int G, int seg_rows, float eps) {
+    const float* __restrict__ seg_prefix, int H, int N, int G, int seg_rows, float inv_eps) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t St[Cfg::STATE];  // [d_value][d_key]
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q rows
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k rows
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
+  __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
+  __shared__ float rq[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64, r = l % 16, q4 = l / 16;
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
+            r = l % 16, q4 = l / 16;
   const size_t ubase = size_t(unit) * N * D;
   const bf16_t* Qu = Q + ubase;
   const bf16_t* Ku = K + ubase;
@@ -150,26 +184,28 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
-  // running state in fp32 accumulators, seeded with the segment's prefix
+  // running state in fp32 accumulators, seeded with the segment's prefix ([d_key][d_value])
   f32x4 sacc[ST::NCT][ST::NRT];
   const float* init = (seg_prefix != nullptr && g > 0)
                           ? seg_prefix + (size_t(unit) * G + g) * D * D : nullptr;
 #pragma unroll
   for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < ST::NRT; ++y)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        sacc[x][y][v] = (init != nullptr && ST::active(w))
-            ? init[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] : 0.f;
+    for (int y = 0; y < ST::NRT; ++y) {
+      f32x4 t = {0.f, 0.f, 0.f, 0.f};
+      if (init != nullptr && ST::active(w))
+        t = *reinterpret_cast<const f32x4*>(init + (16 * ST::col_tile(w, x) + r) * D +
+                                            16 * ST::row_tile(w, y) + 4 * q4);
+      sacc[x][y] = t;
+    }
 
-  TileStage<D, C, Cfg::NT> qst, kst, vst;
+  Stage qst, kst, vst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
 
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    // ---- publish the state (bf16, transposed) and this chunk's tiles
+    // ---- publish the state (bf16) and this chunk's tiles
     if (ST::active(w)) {
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
@@ -178,13 +214,19 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
           uint2 pk;
           pk.x = pack_bf16(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack_bf16(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(St + (16 * ST::col_tile(w, x) + r) * PITCH +
+          *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(w, x) + r) * PITCH +
                                     16 * ST::row_tile(w, y) + 4 * q4) = pk;
         }
     }
-    qst.commit_normalised(Qs, eps, nullptr);
-    kst.commit_normalised(Ks, eps, nullptr);
-    vst.commit_plain(Vs);
+    {
+      float rk[Stage::PASSES], rqv[Stage::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      kst.row_rinv(inv_eps, rk);
+      qst.commit_plain(Qs);
+      qst.store_rinv(rq, rqv);
+      kst.commit_plain(Ks);
+      vst.commit_scaled(Vs, rk);
+    }
     if (row0 + C < row_end) {
       qst.fetch(Qu, row0 + C, row_end);
       kst.fetch(Ku, row0 + C, row_end);
@@ -192,92 +234,87 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
     }
     __syncthreads();
 
-    // ---- output rows 16w..16w+15 of the chunk
-    bf16x8 qf[Cfg::KS];  // Qh rows of this wave: B operand of P^T, A operand of Qh S
+    // ---- inter-chunk part: O^T += S^T Q^T (contraction over d_key = rows of Sl)
+    bf16x8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
       qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
-
+    // oacc[nt][v] = O[query 16w + r][value 16 nt + 4 q4 + v] before the row factor
     f32x4 oacc[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // inter-chunk part: Qh S_prev  (contraction over d_key; St rows are d_value)
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks)
+    for (int ks = 0; ks < Cfg::KS; ++ks) {
+      bf16x8 sf[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
-        oacc[nt] = mma16(qf[ks], lds_row_frag(St + (16 * nt + r) * PITCH + 32 * ks + 8 * q4),
-                         oacc[nt]);
-
-    // intra-chunk part, two key tiles (32 tokens) at a time
+        sf[nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int p = 0; p < Cfg::NW / 2; ++p) {
-      if (2 * p <= w) {  // wave-uniform: key tiles above the diagonal are all masked
-        bf16x8 pf = zero_frag();
+      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(sf[nt], qf[ks], oacc[nt]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- intra-chunk part and state update, two key tiles (32 tokens) at a time
+#pragma unroll
+    for (int p = 0; p < Cfg::NP; ++p) {
+      const bool diag_or_below = 2 * p <= w;  // wave-uniform: else every key is masked
+      // k slot (q4, e) of the P fragment is token 32p + 16*(e/4) + 4*q4 + e%4; V and K are
+      // read down their rows in the same order
+      const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
+      bf16x8 vc[Cfg::DT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DT; ++nt) vc[nt] = lds_col_frag(Vs, PITCH, t0, t1, 16 * nt, r);
+#pragma unroll
+      for (int x = 0; x < ST::NCT; ++x)
+        kcol[x] = lds_col_frag(Ks, PITCH, t0, t1, 16 * ST::col_tile(w, x), r);
+      if (ST::WPC != 1) {
+#pragma unroll
+        for (int y = 0; y < ST::NRT; ++y)
+          vrow[y] = lds_col_frag(Vs, PITCH, t0, t1, 16 * ST::row_tile(w, y), r);
+      }
+      if (diag_or_below) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+          for (int ks = 0; ks < Cfg::KS; ++ks)
+            kr[half][ks] = lds_row_frag(Ks + (16 * (2 * p + half) + r) * PITCH + 32 * ks + 8 * q4);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (diag_or_below) {
+        bf16x8 pf;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const int jt = 2 * p + half;
-          if (jt <= w) {
-            f32x4 pacc = {0.f, 0.f, 0.f, 0.f};
+          f32x4 pacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < Cfg::KS; ++ks)
-              pacc = mma16(lds_row_frag(Ks + (16 * jt + r) * PITCH + 32 * ks + 8 * q4), qf[ks],
-                           pacc);
-            // pacc[v] = P[query 16w + r][key 16jt + 4*q4 + v]; diagonal tile: keep key <= query
+          for (int ks = 0; ks < Cfg::KS; ++ks) pacc = mma16(kr[half][ks], qf[ks], pacc);
+          // pacc[v] = q_(16w + r) . k_(16jt + 4*q4 + v); keep key <= query
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const bool keep = (jt < w) || (4 * q4 + v <= r);
-              pf[4 * half + v] = static_cast<__bf16>(keep ? pacc[v] : 0.f);
-            }
+          for (int v = 0; v < 4; ++v) {
+            const bool keep = (jt < w) || (jt == w && 4 * q4 + v <= r);
+            pf[4 * half + v] = static_cast<__bf16>(keep ? pacc[v] : 0.f);
           }
         }
-        // k slot (q4, e) of pf is token 32p + 16*(e/4) + 4*q4 + e%4: read V the same way
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt)
-          oacc[nt] = mma16(pf, lds_col_frag(Vs, PITCH, 32 * p + 4 * q4, 32 * p + 16 + 4 * q4,
-                                            16 * nt, r),
-                           oacc[nt]);
+        for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(vc[nt], pf, oacc[nt]);
       }
+      // state update S^T += (r v)^T k over these 32 tokens
+      if (ST::active(w)) {
+#pragma unroll
+        for (int y = 0; y < ST::NRT; ++y)
+#pragma unroll
+          for (int x = 0; x < ST::NCT; ++x)
+            sacc[x][y] = mma16(ST::WPC == 1 ? vc[y] : vrow[y], kcol[x], sacc[x][y]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- state update S += Kh^T V over the chunk's tokens
-    if (ST::active(w)) {
-#pragma unroll
-      for (int p = 0; p < C / 32; ++p) {
-        bf16x8 bv[ST::NCT];
-#pragma unroll
-        for (int x = 0; x < ST::NCT; ++x)
-          bv[x] = lds_col_frag(Vs, PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                               16 * ST::col_tile(w, x), r);
-#pragma unroll
-        for (int y = 0; y < ST::NRT; ++y) {
-          bf16x8 ak = lds_col_frag(Ks, PITCH, 32 * p + 8 * q4, 32 * p + 8 * q4 + 4,
-                                   16 * ST::row_tile(w, y), r);
-#pragma unroll
-          for (int x = 0; x < ST::NCT; ++x) sacc[x][y] = mma16(ak, bv[x], sacc[x][y]);
-        }
-      }
-    }
-
-    // ---- store O: through this wave's own (now dead) rows of Qs for 16-byte row writes
+    // ---- O rows: factor s_h r_i, staged through this wave's own (now dead) rows of Qs
+    const float row_factor = scale * rq[16 * w + r];
     wave_lds_sync();
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        Qs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] = f32_to_bf16(scale * oacc[nt][v]);
-    wave_lds_sync();
-    constexpr int PIECES = 16 * D / 8;  // 16-byte pieces in this wave's 16 rows
-#pragma unroll
-    for (int i = l; i < PIECES; i += 64) {
-      const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-      const int row = row0 + 16 * w + lr;
-      if (row < row_end)
-        *reinterpret_cast<uint4*>(Ou + size_t(row) * D + col) =
-            *reinterpret_cast<const uint4*>(Qs + (16 * w + lr) * PITCH + col);
-    }
-    __syncthreads();  // all reads of Ks, Vs, St done before the next chunk overwrites them
+    store_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, Ou, row0 + 16 * w, row_end, l);
+    __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
   }
 
   if (state_out != nullptr && g == G - 1 && ST::active(w)) {
@@ -286,10 +323,8 @@ __global__ __launch_bounds__(C * 4) void fwd_causal_scan_bf16(
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-          out[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] =
-              sacc[x][y][v];
+        *reinterpret_cast<f32x4*>(out + (16 * ST::col_tile(w, x) + r) * D +
+                                  16 * ST::row_tile(w, y) + 4 * q4) = sacc[x][y];
   }
 }
 
@@ -301,30 +336,27 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   const bf16_t* K = static_cast<const bf16_t*>(a.K);
   const bf16_t* V = static_cast<const bf16_t*>(a.V);
   float* ws = static_cast<float*>(a.workspace);  // [units][G][D][D] when G > 1
+  const float inv_eps = 1.0f / a.eps;
   hipError_t err = hipSuccess;
   if (a.G > 1) {
-    err = launch("fwd_segment_state_bf16", a.stream, [&] {
-      fwd_segment_state_bf16<D, C><<<units * (a.G - 1), Cfg::NT, 0, a.stream>>>(
-          K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, a.eps);
-    });
+    err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, C>,
+                        dim3(units * (a.G - 1)), dim3(Cfg::NT), 0, a.stream, K, V, ws, a.N, a.G,
+                        a.G - 1, a.seg_rows, inv_eps);
     if (err != hipSuccess) return err;
     err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
     if (err != hipSuccess) return err;
   }
-  return launch("fwd_causal_scan_bf16", a.stream, [&] {
-    fwd_causal_scan_bf16<D, C><<<units * a.G, Cfg::NT, 0, a.stream>>>(
-        Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state, a.G > 1 ? ws : nullptr, a.H, a.N, a.G,
-        a.seg_rows, a.eps);
-  });
+  return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
+                       a.G > 1 ? ws : nullptr, a.H, a.N, a.G, a.seg_rows, inv_eps);
 }
 
 }  // namespace
 
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {
   const long total = long(units) * elems;
-  return launch("fwd_state_carry", st, [&] {
-    fwd_state_carry<<<unsigned((total + 255) / 256), 256, 0, st>>>(seg_state, G, elems, total);
-  });
+  return launch_kernel("fwd_state_carry", fwd_state_carry, dim3(unsigned((total + 255) / 256)),
+                       dim3(256), 0, st, seg_state, G, elems, total);
 }
 
 hipError_t fwd_causal_bf16(const CausalArgs& a) {

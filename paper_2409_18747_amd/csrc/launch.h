@@ -1,7 +1,8 @@
 // Host-side glue between the C-ABI entry points and the kernel files: argument bundles,
 // the per-dtype launch functions each kernel file defines, and the launch wrapper that
-// optionally brackets a kernel with timing events.
+// optionally attaches timing events to a kernel.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 
@@ -46,20 +47,20 @@ hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st);
 
-// profiling hooks (api.hip)
+// profiling hooks (api.hip): when profiling is on, hands out a fresh pair of events that the
+// launch attaches to the kernel itself, so they time the kernel's own begin and end.
 bool profile_on();
-void profile_begin(const char* kernel_name, hipStream_t stream);
-void profile_end(hipStream_t stream);
+void profile_events(const char* kernel_name, hipEvent_t* begin, hipEvent_t* end);
 
-// Runs `enqueue` (one kernel launch) and returns the launch status.
-template <class F>
-inline hipError_t launch(const char* kernel_name, hipStream_t stream, F&& enqueue) {
-  const bool prof = profile_on();
-  if (prof) profile_begin(kernel_name, stream);
-  enqueue();
-  hipError_t err = hipGetLastError();
-  if (prof) profile_end(stream);
-  return err;
+// Enqueues one kernel on `stream` and returns the launch status.
+template <class... Params, class... Args>
+inline hipError_t launch_kernel(const char* kernel_name, void (*kernel)(Params...), dim3 grid,
+                                dim3 block, size_t dynamic_lds, hipStream_t stream, Args... args) {
+  hipEvent_t begin = nullptr, end = nullptr;
+  if (profile_on()) profile_events(kernel_name, &begin, &end);
+  hipExtLaunchKernelGGL(kernel, grid, block, dynamic_lds, stream, begin, end, 0,
+                        static_cast<Params>(args)...);
+  return hipGetLastError();
 }
 
 }  // namespace cottn

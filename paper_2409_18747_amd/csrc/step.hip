@@ -119,19 +119,17 @@ hipError_t run_step(const StepArgs& a) {
   const T* k = static_cast<const T*>(a.k);
   const T* v = static_cast<const T*>(a.v);
   T* o = static_cast<T*>(a.o);
+  const dim3 grid(units), block(256);
   switch (a.d) {
     case 32:
-      return launch("decode_step_kernel", a.stream, [&] {
-        decode_step_kernel<T, 32><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
-      });
+      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 32>, grid, block, 0, a.stream,
+                           q, k, v, a.s, a.state, o, a.H, a.eps);
     case 64:
-      return launch("decode_step_kernel", a.stream, [&] {
-        decode_step_kernel<T, 64><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
-      });
+      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 64>, grid, block, 0, a.stream,
+                           q, k, v, a.s, a.state, o, a.H, a.eps);
     case 128:
-      return launch("decode_step_kernel", a.stream, [&] {
-        decode_step_kernel<T, 128><<<units, 256, 0, a.stream>>>(q, k, v, a.s, a.state, o, a.H, a.eps);
-      });
+      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 128>, grid, block, 0,
+                           a.stream, q, k, v, a.s, a.state, o, a.H, a.eps);
     default:
       return hipErrorInvalidValue;
   }

@@ -1,6 +1,13 @@
-// Global -> register -> LDS staging of [rows][D] bf16 tiles, with the row L2 normalisation
-// of Sec. 3.2 fused into the register -> LDS step (sum of squares reduced over the lanes
-// that share a row with wavefront shuffles).
+// Global -> register -> LDS staging of [rows][D] bf16 tiles, with the row L2 norm of
+// Sec. 3.2 computed on the way (sum of squares with the packed bf16 dot instruction, reduced
+// over the lanes that share a row with DPP moves).
+//
+// The normalisation x / max(||x||, eps) is never applied to Q and K element by element.
+// With r_i = 1 / max(||q_i||, eps) and r_j likewise for k_j, every product of the method is
+// linear in qh_i = r_i q_i and kh_j = r_j k_j, so the kernels keep the raw rows as MFMA
+// operands and apply r_i to the rows of the result, and fold r_j into the rows of the one
+// operand that is contracted over the token index together with k_j (V in the forward and
+// dQ passes, Q itself in the dK/dV pass).  Only that one tile is rescaled element-wise.
 #pragma once
 #include "device_common.h"
 
@@ -33,27 +40,40 @@ struct TileStage {
     }
   }
 
-  // tile[lr][:] = x / max(||x||, eps) rounded to bf16; rinv[lr] (may be null) = 1/max(||x||, eps)
-  __device__ __forceinline__ void commit_normalised(bf16_t* tile, float eps, float* rinv) const {
+  // rinv[p] = min(1/||row||, inv_eps) = 1 / max(||row||, eps) for the row this lane holds in
+  // pass p (every lane of the row gets the same value).
+  __device__ __forceinline__ void row_rinv(float inv_eps, float* rinv) const {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      float ss = 0.f;
+      const uint32_t w[4] = {regs[p].x, regs[p].y, regs[p].z, regs[p].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16x2 pair = __builtin_bit_cast(bf16x2, w[e]);
+        ss = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, ss, false);
+      }
+      ss = group_sum<LPR>(ss);
+      rinv[p] = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
+    }
+  }
+
+  // out[local row] = rinv of that row (one lane per row writes)
+  __device__ __forceinline__ void store_rinv(float* out, const float* rinv) const {
     const int tid = threadIdx.x;
-    const int col = (tid % LPR) * 8;
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
-      float f[8];
-      unpack8(regs[p], f);
-      float ss = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
-      ss = group_sum<LPR>(ss);
-      const float r = inv_norm(ss, eps);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] *= r;
-      if (lr < C) {
-        *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = pack8(f);
-        if (rinv != nullptr && col == 0) rinv[lr] = r;
-      }
+      if (lr < C && (tid % LPR) == 0) out[lr] = rinv[p];
     }
+  }
+
+  // tile[lr][:] = row / max(||row||, eps) rounded to bf16; rinv_out[lr] (may be null) = that
+  // factor.  For the places that need the normalised rows themselves as an operand.
+  __device__ __forceinline__ void commit_normalised(bf16_t* tile, float eps, float* rinv_out) const {
+    float rinv[PASSES];
+    row_rinv(1.0f / eps, rinv);
+    commit_scaled(tile, rinv);
+    if (rinv_out != nullptr) store_rinv(rinv_out, rinv);
   }
 
   __device__ __forceinline__ void commit_plain(bf16_t* tile) const {
@@ -63,6 +83,21 @@ struct TileStage {
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
       if (lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = regs[p];
+    }
+  }
+
+  // tile[lr][:] = scale[p] * row, rounded to bf16
+  __device__ __forceinline__ void commit_scaled(bf16_t* tile, const float* scale) const {
+    const int tid = threadIdx.x;
+    const int col = (tid % LPR) * 8;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int lr = p * RPP + tid / LPR;
+      float f[8];
+      unpack8(regs[p], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] *= scale[p];
+      if (lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = pack8(f);
     }
   }
 };
@@ -84,5 +119,43 @@ struct AccTiles {
     return (NW >= DT) ? (w / DT) * NRT + y : y;
   }
 };
+
+// Stores a wave's 16-row x D-column result block whose accumulators are laid out
+// TRANSPOSED (acc[nt][v] = result[row r][column 16 nt + 4 q4 + v], i.e. each lane holds 4
+// consecutive columns of one row): scales by the per-lane row factor, rounds to bf16, stages
+// through the wave's own 16 rows of an LDS tile with 8-byte writes, then writes whole
+// 16-byte pieces of rows to global memory.  Rows at or beyond row_end are not written.
+template <int D>
+__device__ __forceinline__ void store_rows_transposed(const f32x4* acc, float row_factor,
+                                                      bf16_t* stage_rows, bf16_t* __restrict__ dst,
+                                                      int first_row, int row_end, int l) {
+  constexpr int DT = D / 16, PITCH = lds_pitch(D);
+  const int r = l % 16, q4 = l / 16;
+#pragma unroll
+  for (int nt = 0; nt < DT; ++nt) {
+    uint2 pk;
+    pk.x = pack_bf16(row_factor * acc[nt][0], row_factor * acc[nt][1]);
+    pk.y = pack_bf16(row_factor * acc[nt][2], row_factor * acc[nt][3]);
+    *reinterpret_cast<uint2*>(stage_rows + r * PITCH + 16 * nt + 4 * q4) = pk;
+  }
+  wave_lds_sync();
+  constexpr int PIECES = 16 * D / 8;  // 16-byte pieces in the wave's 16 rows
+#pragma unroll
+  for (int i = l; i < PIECES; i += 64) {
+    const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
+    const int row = first_row + lr;
+    if (row < row_end)
+      *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) =
+          *reinterpret_cast<const uint4*>(stage_rows + lr * PITCH + col);
+  }
+}
+
+// Sum of x over the four 16-lane rows of the wave (lanes r, r+16, r+32, r+48); every lane
+// gets the total of its column.
+__device__ __forceinline__ float sum_over_lane_rows(float x) {
+  x += __shfl_xor(x, 16, 64);
+  x += __shfl_xor(x, 32, 64);
+  return x;
+}
 
 }  // namespace cottn
