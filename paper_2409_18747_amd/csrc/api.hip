@@ -56,8 +56,9 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
   if (g_tuned_segments > 0) {
     want = g_tuned_segments;
   } else {
-    // enough workgroups to cover the 256 compute units about twice
-    const long target = 512;
+    // about one and a half workgroups per compute unit: measured best for the scan kernels
+    // (more segments shorten the serial chain but add totals to reduce and to add up)
+    const long target = 384;
     want = (target + units - 1) / units;
   }
   if (want > n_chunks) want = n_chunks;

@@ -14,17 +14,28 @@
 //   kernel 3  forward-time scan: dQ of a segment, chunk by chunk, first to last;
 //   kernel 4  reverse-time scan: dK and dV of a segment, chunk by chunk, last to first;
 //   kernel 5  ds[h] from per-workgroup partial sums.
-// The chain rule through x/max(||x||, eps) (dx = r (dxh - xh (xh . dxh)), r = 1/||x||; rows
-// at or below eps: dx = dxh/eps) and the scale s_h are applied in the scan kernels'
-// epilogues, on the fp32 accumulators.  ds_h = sum over rows of qh_i . dqh_i before scaling.
+//
+// Normalisation factors r_i = 1/max(|q_i|, eps), r_j = 1/max(|k_j|, eps) are not applied to
+// Q and K element-wise where a row factor does the same:
+//   dQ pass    V is rescaled to r_j v_j on its way into LDS (then A_ij r_j = dO_i . (r_j v_j)
+//              and S = sum k_j^T (r_j v_j)); Q and K stay raw;
+//              dqh_i = sum_j A'_ij k_j + dO_i S^T;
+//   dK/dV pass Q is rescaled to r_i q_i (it is contracted over the token index in the
+//              reverse state R = sum (r_i q_i)^T dO_i); K and V stay raw;
+//              dv_j = s r_j [ sum_i ((r_i q_i).k_j) dO_i + k_j R ],
+//              dkh_j = sum_i A_ij (r_i q_i) + v_j R^T.
+// The chain rule through x/max(||x||, eps), with t = x . dxh on the raw row:
+//     dx = s r (dxh - x r^2 t)   (rows at or below eps: dx = s r dxh),
+// and ds_h = sum over rows of qh_i . dqh_i = r_i t_i before scaling by s.
 //
 // Inside a chunk the masked A and P tiles are produced directly in the register layout the
-// next product needs as its A operand (A^T = V dO^T for dQ; A and P themselves for dK, dV),
-// so they never pass through LDS; operands contracted over the token index are read from
-// the row-major LDS tiles with the transposing LDS read, and the fragments read for the
-// intra-chunk products are reused as operands of the state updates.  Scheduling follows
-// the same two rules as the forward file: all LDS reads of a group of MFMAs are issued
-// first, and registers are capped for three workgroups per compute unit.
+// next product needs as an operand, so they never pass through LDS; operands contracted
+// over the token index are read from the row-major LDS tiles with the transposing LDS read,
+// and the fragments read for the intra-chunk products are reused by the state updates.
+// Results are accumulated transposed (a lane holds 4 consecutive columns of one result row),
+// which makes every row factor a per-lane scalar and the staging writes 8 bytes wide.
+// Scheduling follows the forward file: all LDS reads of a group of MFMAs are issued first,
+// and the next chunk's tiles are prefetched into registers.
 #include "device_common.h"
 #include "launch.h"
 #include "tile_io.h"
@@ -45,12 +56,15 @@ struct BwdCfg {
   static constexpr int STATE = D * PITCH;
   static constexpr int LDS_BYTES = 2 * (4 * TILE + STATE) + 4 * C + 64;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
-  static constexpr bool PREFETCH = true;
   static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
   static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
 };
 
-// pack a masked accumulator tile into half of an A-operand fragment
+// Up to this many segments per (batch, head) the scan kernels add up the segment totals they
+// need themselves and the carry kernel is not launched.
+constexpr int kMaxSegmentsSummedInScan = 4;
+
+// pack a masked accumulator tile into half of an operand fragment
 __device__ __forceinline__ void put_half(bf16x8& frag, int half, f32x4 acc, bool k0, bool k1,
                                          bool k2, bool k3) {
   frag[4 * half + 0] = static_cast<__bf16>(k0 ? acc[0] : 0.f);
@@ -59,20 +73,51 @@ __device__ __forceinline__ void put_half(bf16x8& frag, int half, f32x4 acc, bool
   frag[4 * half + 3] = static_cast<__bf16>(k3 ? acc[3] : 0.f);
 }
 
+// Chain rule through the row normalisation on a wave's transposed 16 x D block:
+// acc[nt][v] = dxh[row r][column 16 nt + 4 q4 + v].  Reads the raw row x from `x_rows` (the
+// wave's 16 rows of its LDS tile), forms t = x . dxh over the whole row (16 columns per lane,
+// then across the four lane rows) and replaces acc by dxh - x r^2 t (no projection for rows
+// at or below eps).  Returns r t = xh . dxh.
+template <int D>
+__device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_rows, float rinv,
+                                                 float inv_eps, int r, int q4) {
+  constexpr int DT = D / 16, PITCH = lds_pitch(D);
+  float xv[DT][4];
+  float t = 0.f;
+#pragma unroll
+  for (int nt = 0; nt < DT; ++nt) {
+    const uint2 raw = *reinterpret_cast<const uint2*>(x_rows + r * PITCH + 16 * nt + 4 * q4);
+    xv[nt][0] = __builtin_bit_cast(float, raw.x << 16);
+    xv[nt][1] = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
+    xv[nt][2] = __builtin_bit_cast(float, raw.y << 16);
+    xv[nt][3] = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) t += xv[nt][v] * acc[nt][v];
+  }
+  t = sum_over_lane_rows(t);
+  const float c = (rinv == inv_eps) ? 0.f : rinv * rinv * t;
+#pragma unroll
+  for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[nt][v] -= xv[nt][v] * c;
+  return rinv * t;
+}
+
 // ---------------------------------------------------------------------------------------
 // Kernel 1: per-segment totals, both [d_key][d_value]:
-//   fwd_tot[unit][g] = sum_rows kh^T v   (needed by later segments: computed for g < G-1)
-//   rev_tot[unit][g] = sum_rows qh^T dO  (needed by earlier segments: computed for g > 0)
+//   fwd_tot[unit][g] = sum_rows k^T (r_k v)    (needed by later segments: computed for g < G-1)
+//   rev_tot[unit][g] = sum_rows q^T (r_q dO)   (needed by earlier segments: computed for g > 0)
 template <int D, int C>
 __global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, float* __restrict__ fwd_tot, float* __restrict__ rev_tot,
-    int N, int G, int seg_rows, float eps) {
+    int N, int G, int seg_rows, float inv_eps) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[Cfg::TILE];  // Kh or Qh
-  __shared__ __attribute__((aligned(16))) bf16_t Ys[Cfg::TILE];  // V  or dO
+  __shared__ __attribute__((aligned(16))) bf16_t Xs[Cfg::TILE];  // K or Q, raw
+  __shared__ __attribute__((aligned(16))) bf16_t Ys[Cfg::TILE];  // V or dO, times r of the X row
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
@@ -95,13 +140,19 @@ __global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
 #pragma unroll
       for (int y = 0; y < AT::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    TileStage<D, C, Cfg::NT> xst, yst;
+    Stage xst, yst;
+    xst.fetch(X, row_begin, row_end);
+    yst.fetch(Y, row_begin, row_end);
     for (int row0 = row_begin; row0 < row_end; row0 += C) {
-      xst.fetch(X, row0, row_end);
-      yst.fetch(Y, row0, row_end);
+      float rx[Stage::PASSES];
+      xst.row_rinv(inv_eps, rx);
       __syncthreads();
-      xst.commit_normalised(Xs, eps, nullptr);
-      yst.commit_plain(Ys);
+      xst.commit_plain(Xs);
+      yst.commit_scaled(Ys, rx);
+      if (row0 + C < row_end) {
+        xst.fetch(X, row0 + C, row_end);
+        yst.fetch(Y, row0 + C, row_end);
+      }
       __syncthreads();
       if (AT::active(w)) {
 #pragma unroll
@@ -133,6 +184,7 @@ __global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
             out[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r] =
                 acc[x][y][v];
     }
+    __syncthreads();
   }
 }
 
@@ -170,19 +222,20 @@ __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_t
 // columns: element [v] of lane (r, q4) of tile (y, x) is S[16 rt + 4 q4 + v][16 ct + r].  A
 // lane thus holds 4 consecutive keys of one value column and publishes them with one 8-byte
 // write to the transposed LDS copy St[d_value][d_key]; the update's row-side operand is the
-// Kh fragment already read for the intra-chunk product.
+// K fragment already read for the intra-chunk product.
 template <int D, int C>
 __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
-    const float* __restrict__ fwd_prefix, float* __restrict__ ds_partial, int H, int N, int G,
-    int seg_rows, float eps) {
+    const float* __restrict__ fwd_states, float* __restrict__ ds_partial, int H, int N, int G,
+    int seg_rows, float inv_eps, int sum_totals) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
   __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
   __shared__ __attribute__((aligned(16))) bf16_t St[Cfg::STATE];  // state, [d_value][d_key]
   __shared__ float rq[C];
@@ -198,38 +251,39 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   const bf16_t* Gu = dO + ubase;
   bf16_t* dQu = dQ + ubase;
   const float scale = s[unit % H];
-  const float r_clamped = 1.0f / eps;
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
+  // fwd_states holds the carried prefixes (slot g = state at the start of segment g) or, with
+  // sum_totals set, the raw segment totals, which this workgroup then adds up itself
   f32x4 sacc[AT::NCT][AT::NRT];
-  const float* init = (fwd_prefix != nullptr && g > 0)
-                          ? fwd_prefix + (size_t(unit) * G + g) * D * D : nullptr;
 #pragma unroll
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < AT::NRT; ++y)
+    for (int y = 0; y < AT::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (fwd_states != nullptr && g > 0 && AT::active(w)) {
+    const int first = sum_totals ? 0 : g, last = sum_totals ? g - 1 : g;
+    for (int gp = first; gp <= last; ++gp) {
+      const float* src = fwd_states + (size_t(unit) * G + gp) * D * D;
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        sacc[x][y][v] = (init != nullptr && AT::active(w))
-            ? init[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r] : 0.f;
-
-  float ds_lane = 0.f;
-  TileStage<D, C, Cfg::NT> qst, kst, vst, gst;
-  if (Cfg::PREFETCH) {
-    qst.fetch(Qu, row_begin, row_end);
-    kst.fetch(Ku, row_begin, row_end);
-    vst.fetch(Vu, row_begin, row_end);
-    gst.fetch(Gu, row_begin, row_end);
+      for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < AT::NRT; ++y)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            sacc[x][y][v] +=
+                src[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r];
+    }
   }
 
+  float ds_lane = 0.f;
+  Stage qst, kst, vst, gst;
+  qst.fetch(Qu, row_begin, row_end);
+  kst.fetch(Ku, row_begin, row_end);
+  vst.fetch(Vu, row_begin, row_end);
+  gst.fetch(Gu, row_begin, row_end);
+
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    if (!Cfg::PREFETCH) {
-      qst.fetch(Qu, row0, row_end);
-      kst.fetch(Ku, row0, row_end);
-      vst.fetch(Vu, row0, row_end);
-      gst.fetch(Gu, row0, row_end);
-    }
     if (AT::active(w)) {
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
@@ -242,11 +296,17 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
     }
-    qst.commit_normalised(Qs, eps, rq);
-    kst.commit_normalised(Ks, eps, nullptr);
-    vst.commit_plain(Vs);
-    gst.commit_plain(Gs);
-    if (Cfg::PREFETCH && row0 + C < row_end) {
+    {
+      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      kst.row_rinv(inv_eps, rkv);
+      qst.commit_plain(Qs);
+      qst.store_rinv(rq, rqv);
+      kst.commit_plain(Ks);
+      vst.commit_scaled(Vs, rkv);
+      gst.commit_plain(Gs);
+    }
+    if (row0 + C < row_end) {
       qst.fetch(Qu, row0 + C, row_end);
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
@@ -254,11 +314,12 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     }
     __syncthreads();
 
-    // earlier chunks: dO S^T (contraction over d_value = rows of St)
-    bf16x8 gf[Cfg::KS];  // dO rows of this wave
+    // earlier chunks: dqh^T += S dO^T (contraction over d_value = rows of St)
+    bf16x8 gf[Cfg::KS];  // dO rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
       gf[ks] = lds_row_frag(Gs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
+    // dq[nt][v] = dqh[query 16w + r][key feature 16 nt + 4 q4 + v]
     f32x4 dq[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -270,11 +331,12 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
         sf[nt] = lds_col_frag(St, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(gf[ks], sf[nt], dq[nt]);
+      for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(sf[nt], gf[ks], dq[nt]);
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // this chunk: (A (.) M) Kh with A^T = V dO^T, and the state update, 32 tokens at a time
+    // this chunk: dqh^T += K^T (A' (.) M)^T with A'^T = (r v) dO^T, and the state update,
+    // 32 tokens at a time
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_below = 2 * p <= w;
@@ -306,15 +368,15 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
           f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks) t = mma16(vr[half][ks], gf[ks], t);
-          // t[v] = dO_(16w + r) . v_(16jt + 4 q4 + v); keep key <= query
+          // t[v] = dO_(16w + r) . (r v)_(16jt + 4 q4 + v); keep key <= query
           const bool full = jt < w, diag = jt == w;
           put_half(af, half, t, full || (diag && 4 * q4 + 0 <= r), full || (diag && 4 * q4 + 1 <= r),
                    full || (diag && 4 * q4 + 2 <= r), full || (diag && 4 * q4 + 3 <= r));
         }
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(af, kc[nt], dq[nt]);
+        for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(kc[nt], af, dq[nt]);
       }
-      // state update: S += Kh^T V over these 32 tokens
+      // state update: S += k^T (r v) over these 32 tokens
       if (AT::active(w)) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
@@ -325,45 +387,17 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // epilogue: rho_i = qh_i . dqh_i ; dq_i = s r_i (dqh_i - qh_i rho_i)
-    float rho[4] = {0.f, 0.f, 0.f, 0.f};
-    float qv[Cfg::DT][4];
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        qv[nt][v] = bf16_to_f32(Qs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r]);
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) rho[v] += qv[nt][v] * dq[nt][v];
+    // epilogue: normalisation chain rule on the rows, then s r_i and the store through this
+    // wave's own (dead) rows of Gs
+    const float ri = rq[16 * w + r];
+    const float rho = project_out_row<D>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
+    if (q4 == 0) ds_lane += rho;
     wave_lds_sync();  // this wave's reads of its Gs rows (gf) precede the staging writes
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      rho[v] = group_sum<16>(rho[v]);
-      if (r == 0) ds_lane += rho[v];
-      const float ri = rq[16 * w + 4 * q4 + v];
-      const float proj = (ri == r_clamped) ? 0.f : rho[v];
-      const float f = scale * ri;
-#pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt)
-        Gs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] =
-            f32_to_bf16(f * (dq[nt][v] - qv[nt][v] * proj));
-    }
-    wave_lds_sync();
-    constexpr int PIECES = 16 * D / 8;
-#pragma unroll
-    for (int i = l; i < PIECES; i += 64) {
-      const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-      const int row = row0 + 16 * w + lr;
-      if (row < row_end)
-        *reinterpret_cast<uint4*>(dQu + size_t(row) * D + col) =
-            *reinterpret_cast<const uint4*>(Gs + (16 * w + lr) * PITCH + col);
-    }
+    store_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
     __syncthreads();
   }
 
-  // per-workgroup partial of ds: lanes with r == 0 hold the row sums
+  // per-workgroup partial of ds: lanes of the first lane row hold the row sums
   ds_lane = group_sum<64>(ds_lane);
   if (l == 0) ds_wave[w] = ds_lane;
   __syncthreads();
@@ -386,14 +420,16 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dK,
-    bf16_t* __restrict__ dV, const float* __restrict__ rev_suffix, int H, int N, int G,
-    int seg_rows, float eps) {
+    bf16_t* __restrict__ dV, const float* __restrict__ rev_states,
+    const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H, int N, int G,
+    int seg_rows, float inv_eps, int sum_totals) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // r_i q_i
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // raw v
   __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
   __shared__ __attribute__((aligned(16))) bf16_t Rl[Cfg::STATE];  // reverse state, [d_key][d_value]
   __shared__ float rk[C];
@@ -409,27 +445,43 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
   bf16_t* dKu = dK + ubase;
   bf16_t* dVu = dV + ubase;
   const float scale = s[unit % H];
-  const float r_clamped = 1.0f / eps;
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
   const int n_chunks = (row_end - row_begin + C - 1) / C;
 
+  // the first H workgroups also finish ds: ds[h] = sum over batches and segments of the
+  // partial sums the dQ kernel left behind
+  if (int(blockIdx.x) < H && w == 0) {
+    float t = 0.f;
+    const int n = B * G;
+    for (int i = l; i < n; i += 64)
+      t += ds_partial[(size_t(i / G) * H + blockIdx.x) * G + (i % G)];
+    t = group_sum<64>(t);
+    if (l == 0) ds[blockIdx.x] = t;
+  }
+
+  // rev_states holds the carried suffixes (slot g = reverse state at the end of segment g)
+  // or, with sum_totals set, the raw segment totals of the later segments to be added up here
   f32x4 racc[AT::NCT][AT::NRT];
-  const float* init = (rev_suffix != nullptr && g < G - 1)
-                          ? rev_suffix + (size_t(unit) * G + g) * D * D : nullptr;
 #pragma unroll
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < AT::NRT; ++y) {
-      f32x4 t = {0.f, 0.f, 0.f, 0.f};
-      if (init != nullptr && AT::active(w))
-        t = *reinterpret_cast<const f32x4*>(init + (16 * AT::col_tile(w, x) + r) * D +
-                                            16 * AT::row_tile(w, y) + 4 * q4);
-      racc[x][y] = t;
+    for (int y = 0; y < AT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (rev_states != nullptr && g < G - 1 && AT::active(w)) {
+    const int first = sum_totals ? g + 1 : g, last = sum_totals ? G - 1 : g;
+    for (int gp = first; gp <= last; ++gp) {
+      const float* src = rev_states + (size_t(unit) * G + gp) * D * D;
+#pragma unroll
+      for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < AT::NRT; ++y)
+          racc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::col_tile(w, x) + r) * D +
+                                                        16 * AT::row_tile(w, y) + 4 * q4);
     }
+  }
 
-  TileStage<D, C, Cfg::NT> qst, kst, vst, gst;
-  if (Cfg::PREFETCH) {
+  Stage qst, kst, vst, gst;
+  {
     const int first = row_begin + (n_chunks - 1) * C;
     qst.fetch(Qu, first, row_end);
     kst.fetch(Ku, first, row_end);
@@ -439,12 +491,6 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
 
   for (int c = n_chunks - 1; c >= 0; --c) {
     const int row0 = row_begin + c * C;
-    if (!Cfg::PREFETCH) {
-      qst.fetch(Qu, row0, row_end);
-      kst.fetch(Ku, row0, row_end);
-      vst.fetch(Vu, row0, row_end);
-      gst.fetch(Gu, row0, row_end);
-    }
     if (AT::active(w)) {
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
@@ -457,11 +503,17 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
     }
-    qst.commit_normalised(Qs, eps, nullptr);
-    kst.commit_normalised(Ks, eps, rk);
-    vst.commit_plain(Vs);
-    gst.commit_plain(Gs);
-    if (Cfg::PREFETCH && c > 0) {
+    {
+      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      kst.row_rinv(inv_eps, rkv);
+      qst.commit_scaled(Qs, rqv);
+      kst.commit_plain(Ks);
+      kst.store_rinv(rk, rkv);
+      vst.commit_plain(Vs);
+      gst.commit_plain(Gs);
+    }
+    if (c > 0) {
       qst.fetch(Qu, row0 - C, row_end);
       kst.fetch(Ku, row0 - C, row_end);
       vst.fetch(Vu, row0 - C, row_end);
@@ -469,12 +521,13 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     }
     __syncthreads();
 
-    bf16x8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows
+    bf16x8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows (column side)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
       kf[ks] = lds_row_frag(Ks + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
       vf[ks] = lds_row_frag(Vs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
     }
+    // dk[nt][v] = dkh[key 16w + r][feature 16 nt + 4 q4 + v]; dv likewise before s r_j
     f32x4 dk[Cfg::DT], dv[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) {
@@ -482,7 +535,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
       dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // later chunks: dv += kh R (over d_key), dkh += v R^T (over d_value)
+    // later chunks: dv^T += R^T k^T (over d_key), dkh^T += R v^T (over d_value)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
       bf16x8 rcol[Cfg::DT], rrow[Cfg::DT];
@@ -494,8 +547,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
-        dv[nt] = mma16(kf[ks], rcol[nt], dv[nt]);
-        dk[nt] = mma16(vf[ks], rrow[nt], dk[nt]);
+        dv[nt] = mma16(rcol[nt], kf[ks], dv[nt]);
+        dk[nt] = mma16(rrow[nt], vf[ks], dk[nt]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -504,7 +557,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_above = 2 * p + 1 >= w;
-      const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the A slots
+      const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the slots
       bf16x8 gc[Cfg::DT], qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) gc[nt] = lds_col_frag(Gs, PITCH, t0, t1, 16 * nt, r);
@@ -517,7 +570,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
           grow[y] = lds_col_frag(Gs, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       __builtin_amdgcn_sched_barrier(0);
-      // reverse state update: R^T += dO^T Qh over these 32 tokens
+      // reverse state update: R^T += dO^T (r q) over these 32 tokens
       if (AT::active(w)) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
@@ -557,52 +610,20 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
         }
 #pragma unroll
         for (int nt = 0; nt < Cfg::DT; ++nt) {
-          dv[nt] = mma16(pf, gc[nt], dv[nt]);
-          dk[nt] = mma16(af, qc[nt], dk[nt]);
+          dv[nt] = mma16(gc[nt], pf, dv[nt]);
+          dk[nt] = mma16(qc[nt], af, dk[nt]);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // epilogue: dk_j = s r_j (dkh_j - kh_j (kh_j . dkh_j)), dv_j = s dv_j
-    float rho[4] = {0.f, 0.f, 0.f, 0.f};
-    float kv[Cfg::DT][4];
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        kv[nt][v] = bf16_to_f32(Ks[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r]);
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) rho[v] += kv[nt][v] * dk[nt][v];
-    wave_lds_sync();  // own Ks / Vs rows are dead from here on: reuse them as staging
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      rho[v] = group_sum<16>(rho[v]);
-      const float rj = rk[16 * w + 4 * q4 + v];
-      const float proj = (rj == r_clamped) ? 0.f : rho[v];
-      const float f = scale * rj;
-#pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) {
-        Ks[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] =
-            f32_to_bf16(f * (dk[nt][v] - kv[nt][v] * proj));
-        Vs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] = f32_to_bf16(scale * dv[nt][v]);
-      }
-    }
-    wave_lds_sync();
-    constexpr int PIECES = 16 * D / 8;
-#pragma unroll
-    for (int i = l; i < PIECES; i += 64) {
-      const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-      const int row = row0 + 16 * w + lr;
-      if (row < row_end) {
-        *reinterpret_cast<uint4*>(dKu + size_t(row) * D + col) =
-            *reinterpret_cast<const uint4*>(Ks + (16 * w + lr) * PITCH + col);
-        *reinterpret_cast<uint4*>(dVu + size_t(row) * D + col) =
-            *reinterpret_cast<const uint4*>(Vs + (16 * w + lr) * PITCH + col);
-      }
-    }
+    // epilogue: dv_j = s r_j dv; dk_j through the normalisation chain rule; both staged in
+    // this wave's own (dead) rows of Vs and Ks
+    const float rj = rk[16 * w + r];
+    project_out_row<D>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
+    wave_lds_sync();  // own Ks / Vs rows (kf, vf, raw k) were read before the staging writes
+    store_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, dKu, row0 + 16 * w, row_end, l);
+    store_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, dVu, row0 + 16 * w, row_end, l);
     __syncthreads();
   }
 }
@@ -646,23 +667,28 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   }
   float* ds_partial = reinterpret_cast<float*>(ws);
   const dim3 grid(units * a.G), block(Cfg::NT);
+  const float inv_eps = 1.0f / a.eps;
+  // few segments: no carry launch, the scan workgroups add up the totals they need
+  const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   hipError_t err;
   if (a.G > 1) {
     err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, C>, grid, block, 0,
-                        a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G, a.seg_rows, a.eps);
+                        a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G, a.seg_rows, inv_eps);
     if (err != hipSuccess) return err;
-    err = launch_bwd_state_carry(fwd_states, rev_states, units, a.G, D * D, a.stream);
-    if (err != hipSuccess) return err;
+    if (!sum_in_scan) {
+      err = launch_bwd_state_carry(fwd_states, rev_states, units, a.G, D * D, a.stream);
+      if (err != hipSuccess) return err;
+    }
   }
   err = launch_kernel("bwd_dq_scan_bf16", bwd_dq_scan_bf16<D, C>, grid, block, 0, a.stream, Q, K, V,
                       dO, a.s, static_cast<bf16_t*>(a.dQ), fwd_states, ds_partial, a.H, a.N, a.G,
-                      a.seg_rows, a.eps);
+                      a.seg_rows, inv_eps, sum_in_scan ? 1 : 0);
   if (err != hipSuccess) return err;
-  err = launch_kernel("bwd_dkdv_scan_bf16", bwd_dkdv_scan_bf16<D, C>, grid, block, 0, a.stream, Q, K,
-                      V, dO, a.s, static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), rev_states,
-                      a.H, a.N, a.G, a.seg_rows, a.eps);
-  if (err != hipSuccess) return err;
-  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, a.G, a.stream);
+  // the dK/dV kernel also reduces the ds partial sums written by the dQ kernel
+  return launch_kernel("bwd_dkdv_scan_bf16", bwd_dkdv_scan_bf16<D, C>, grid, block, 0, a.stream, Q,
+                       K, V, dO, a.s, static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV),
+                       rev_states, ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, inv_eps,
+                       sum_in_scan ? 1 : 0);
 }
 
 }  // namespace

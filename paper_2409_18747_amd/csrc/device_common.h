@@ -17,6 +17,13 @@ typedef uint16_t bf16_t;  // storage type of bf16 data in global memory and LDS
 
 #define COTTN_LDS __attribute__((address_space(3)))
 
+// Optional in-kernel timeline for tuning builds: a translation unit that defines
+// COTTN_TRACE_POINT(i) before including the kernel sources gets a hook at the phase
+// boundaries of the scan kernels; the library build leaves it empty.
+#ifndef COTTN_TRACE_POINT
+#define COTTN_TRACE_POINT(i)
+#endif
+
 // Row pitch (in elements) of a bf16 LDS tile with `cols` columns: 8 extra elements (16 B)
 // shift consecutive rows by 4 banks, which makes both the 16-byte row reads of 16 rows and
 // the 8-byte transposing reads conflict-free.

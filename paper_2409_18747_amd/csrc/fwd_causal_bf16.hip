@@ -57,6 +57,10 @@ struct FwdCfg {
   static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
 };
 
+// Up to this many segments per (batch, head) the scan kernel adds up the segment totals
+// before its own segment itself and the carry kernel is not launched.
+constexpr int kMaxSegmentsSummedInScan = 4;
+
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
 // grid = units * n_compute workgroups; segment g of a unit writes slot g of the unit's
@@ -161,7 +165,8 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causal_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
-    const float* __restrict__ seg_prefix, int H, int N, int G, int seg_rows, float inv_eps) {
+    const float* __restrict__ seg_states, int H, int N, int G, int seg_rows, float inv_eps,
+    int sum_totals) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -185,19 +190,26 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   const int row_end = min(N, row_begin + seg_rows);
 
   // running state in fp32 accumulators, seeded with the segment's prefix ([d_key][d_value])
+  // seg_states holds either the carried prefixes (slot g = state at the start of segment g)
+  // or, with sum_totals set, the raw segment totals: then the workgroup adds up the totals of
+  // the segments before its own (few segments: cheaper than a separate carry launch).
   f32x4 sacc[ST::NCT][ST::NRT];
-  const float* init = (seg_prefix != nullptr && g > 0)
-                          ? seg_prefix + (size_t(unit) * G + g) * D * D : nullptr;
 #pragma unroll
   for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < ST::NRT; ++y) {
-      f32x4 t = {0.f, 0.f, 0.f, 0.f};
-      if (init != nullptr && ST::active(w))
-        t = *reinterpret_cast<const f32x4*>(init + (16 * ST::col_tile(w, x) + r) * D +
-                                            16 * ST::row_tile(w, y) + 4 * q4);
-      sacc[x][y] = t;
+    for (int y = 0; y < ST::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (seg_states != nullptr && g > 0 && ST::active(w)) {
+    const int first = sum_totals ? 0 : g, last = sum_totals ? g - 1 : g;
+    for (int gp = first; gp <= last; ++gp) {
+      const float* src = seg_states + (size_t(unit) * G + gp) * D * D;
+#pragma unroll
+      for (int x = 0; x < ST::NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < ST::NRT; ++y)
+          sacc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(w, x) + r) * D +
+                                                        16 * ST::row_tile(w, y) + 4 * q4);
     }
+  }
 
   Stage qst, kst, vst;
   qst.fetch(Qu, row_begin, row_end);
@@ -205,6 +217,7 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   vst.fetch(Vu, row_begin, row_end);
 
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
+    COTTN_TRACE_POINT(0);
     // ---- publish the state (bf16) and this chunk's tiles
     if (ST::active(w)) {
 #pragma unroll
@@ -227,12 +240,15 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
       kst.commit_plain(Ks);
       vst.commit_scaled(Vs, rk);
     }
+    COTTN_TRACE_POINT(1);
     if (row0 + C < row_end) {
       qst.fetch(Qu, row0 + C, row_end);
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
     }
+    COTTN_TRACE_POINT(2);
     __syncthreads();
+    COTTN_TRACE_POINT(3);
 
     // ---- inter-chunk part: O^T += S^T Q^T (contraction over d_key = rows of Sl)
     bf16x8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
@@ -255,6 +271,7 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
       __builtin_amdgcn_sched_barrier(0);
     }
 
+    COTTN_TRACE_POINT(4);
     // ---- intra-chunk part and state update, two key tiles (32 tokens) at a time
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
@@ -310,11 +327,13 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
       __builtin_amdgcn_sched_barrier(0);
     }
 
+    COTTN_TRACE_POINT(5);
     // ---- O rows: factor s_h r_i, staged through this wave's own (now dead) rows of Qs
     const float row_factor = scale * rq[16 * w + r];
     wave_lds_sync();
     store_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, Ou, row0 + 16 * w, row_end, l);
     __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
+    COTTN_TRACE_POINT(6);
   }
 
   if (state_out != nullptr && g == G - 1 && ST::active(w)) {
@@ -338,17 +357,22 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   float* ws = static_cast<float*>(a.workspace);  // [units][G][D][D] when G > 1
   const float inv_eps = 1.0f / a.eps;
   hipError_t err = hipSuccess;
+  // few segments: no carry launch, each scan workgroup adds up the totals before its segment
+  const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   if (a.G > 1) {
     err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, C>,
                         dim3(units * (a.G - 1)), dim3(Cfg::NT), 0, a.stream, K, V, ws, a.N, a.G,
                         a.G - 1, a.seg_rows, inv_eps);
     if (err != hipSuccess) return err;
-    err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
-    if (err != hipSuccess) return err;
+    if (!sum_in_scan) {
+      err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
+      if (err != hipSuccess) return err;
+    }
   }
   return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
-                       a.G > 1 ? ws : nullptr, a.H, a.N, a.G, a.seg_rows, inv_eps);
+                       a.G > 1 ? ws : nullptr, a.H, a.N, a.G, a.seg_rows, inv_eps,
+                       sum_in_scan ? 1 : 0);
 }
 
 }  // namespace

@@ -30,12 +30,19 @@ struct TileStage {
   __device__ __forceinline__ void fetch(const bf16_t* __restrict__ base, int row0, int n_rows) {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;
+    const bf16_t* p0 = base + size_t(row0) * D + (tid / LPR) * D + col;
+    if (C % RPP == 0 && row0 + C <= n_rows) {
+      // whole tile in range (workgroup-uniform): plain loads at constant strides
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p)
+        regs[p] = *reinterpret_cast<const uint4*>(p0 + p * RPP * D);
+      return;
+    }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
-      const int row = row0 + lr;
       uint4 v = {0u, 0u, 0u, 0u};
-      if (lr < C && row < n_rows) v = *reinterpret_cast<const uint4*>(base + size_t(row) * D + col);
+      if (lr < C && row0 + lr < n_rows) v = *reinterpret_cast<const uint4*>(p0 + p * RPP * D);
       regs[p] = v;
     }
   }
