@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB a few times before the "
+                         "timed region: the reference dispatch for scaling rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); no multi-GPU figure exists",
@@ -84,6 +87,14 @@ def main():
                                dV=t["dV"], ds=t["ds"], workspace=ws, chunk=args.chunk,
                                stream=stream)
 
+    if args.copy_calibration_mib:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -114,9 +125,14 @@ def main():
     alg_bytes = KERNEL_ROW_TENSORS.get(dom, 0) * d * elem * rows
     dom_s = prof[dom][1] / prof[dom][0] * 1e-3
     achieved = alg_bytes / dom_s / 1e9 if alg_bytes else None
+    # measured HBM bytes per launch of that kernel, from the committed rocprofv3 counter summary
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.json")
+    if os.path.exists(tpath) and not args.chunk and not args.segments:
+        traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dom)
     roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                "traffic": None, "avg_us": dom_s * 1e6, "algorithmic_bytes": alg_bytes}
+                "traffic": traffic, "avg_us": dom_s * 1e6, "algorithmic_bytes": alg_bytes}
     # whole-step view: 11 tensors of B*H*N*d bf16 must cross HBM per fwd+bwd
     step_bytes = 11 * d * elem * rows
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
