@@ -33,6 +33,92 @@ KERNEL_ROW_TENSORS = {
 }
 
 
+def time_calls(torch, fn, iters, warmup):
+    """Average milliseconds of fn(i) over `iters` calls on the current stream."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def other_workloads(torch, cottn, workloads):
+    """The other benchmark configurations, each timed briefly (random bf16 values of the
+    configured shapes; correctness of these shapes is the parity tests' job)."""
+    out = {}
+    dev = torch.device("cuda:0")
+    rnd = lambda *shape: torch.randn(*shape, device=dev).to(torch.bfloat16)
+
+    # decode: 256 sequences x 16 heads, d = 128; one call per token, the fp32 state streams
+    w = workloads.WORKLOADS["cfg5_decode_bf16"]
+    B, H, d = w.B, w.H, w.d
+    state = torch.zeros(B, H, d, d, dtype=torch.float32, device=dev)
+    T = 32
+    q, k, v = rnd(T, B, H, d), rnd(T, B, H, d), rnd(T, B, H, d)
+    o = torch.empty_like(q)
+    s = torch.ones(H, device=dev)
+    ms = time_calls(torch, lambda i: cottn.cottn_step(q[i % T], k[i % T], v[i % T], s, state,
+                                                      o=o[i % T]), 400, 20)
+    byt = 2 * B * H * d * d * 4
+    out["cfg5_decode_step"] = {"us_per_step": ms * 1e3, "tokens_per_s": B / (ms * 1e-3),
+                               "state_bytes_read_plus_written": byt,
+                               "achieved_GBs": byt / ms / 1e6, "frac_of_hbm_peak": byt / ms / 1e6 / HBM_PEAK_GBS}
+    del state, q, k, v, o
+
+    # BERT-shaped bidirectional forward + backward
+    w = workloads.WORKLOADS["cfg3_bert_bidir_fwdbwd_bf16"]
+    B, H, N, d = w.B, w.H, w.N, w.d
+    sets = []
+    for _ in range(2):
+        t = {n: rnd(B, H, N, d) for n in ("Q", "K", "V", "dO")}
+        t.update({n: torch.empty_like(t["Q"]) for n in ("O", "dQ", "dK", "dV")})
+        sets.append(t)
+    s = torch.ones(H, device=dev)
+    ds = torch.empty(H, device=dev)
+    ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_BIDIR, B, H, N, d),
+                         cottn.cottn_workspace_bytes(cottn.OP_BWD_BIDIR, B, H, N, d)),
+                     dtype=torch.uint8, device=dev)
+
+    def bidir(i):
+        t = sets[i % 2]
+        cottn.cottn_fwd_bidir(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=ws)
+        cottn.cottn_bwd_bidir(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"],
+                              dV=t["dV"], ds=ds, workspace=ws)
+    ms = time_calls(torch, bidir, 100, 10)
+    byt = 11 * B * H * N * d * 2
+    out["cfg3_bidir_fwd_bwd"] = {"ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3),
+                                 "algorithmic_GBs": byt / ms / 1e6}
+    del sets, ws
+
+    # long context causal forward + backward, N = 65536
+    w = workloads.WORKLOADS["cfg4_long_causal_fwdbwd_bf16"]
+    B, H, N, d = w.B, w.H, w.N, w.d
+    t = {n: rnd(B, H, N, d) * 0.5 for n in ("Q", "K", "V", "dO")}
+    t.update({n: torch.empty_like(t["Q"]) for n in ("O", "dQ", "dK", "dV")})
+    s = torch.ones(H, device=dev)
+    for chunk in (64, 128, 256):
+        ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
+                             cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, chunk)),
+                         dtype=torch.uint8, device=dev)
+
+        def long_ctx(i):
+            cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=ws, chunk=chunk)
+            cottn.cottn_bwd_causal(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"],
+                                   dV=t["dV"], ds=ds, workspace=ws, chunk=chunk)
+        ms = time_calls(torch, long_ctx, 20, 3)
+        byt = 11 * B * H * N * d * 2
+        out["cfg4_long_context_chunk%d" % chunk] = {
+            "ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3), "algorithmic_GBs": byt / ms / 1e6,
+            "segments": cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
+            "workspace_bytes": ws.numel()}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +128,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the brief timings of the decode, bidirectional and long-context shapes")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB a few times before the "
                          "timed region: the reference dispatch for scaling rocprofv3 byte counters")
@@ -164,6 +252,9 @@ def main():
                      "frac_of_peak": step_gbs / HBM_PEAK_GBS},
         "kernels": kernels,
     }
+    if not args.no_other_workloads and not args.chunk and not args.segments:
+        del sets
+        out["other_workloads"] = other_workloads(torch, cottn, workloads)
     print(json.dumps(out))
     return 0
 
