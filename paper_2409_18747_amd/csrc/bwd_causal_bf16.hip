@@ -126,9 +126,10 @@ __global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
-#pragma unroll 1
-  for (int which = 0; which < 2; ++which) {
-    if (which == 0 ? (g >= G - 1) : (g == 0)) continue;
+  // blockIdx.y selects the pair: 0 = (K, V) forward totals, 1 = (Q, dO) reverse totals
+  {
+    const int which = blockIdx.y;
+    if (which == 0 ? (g >= G - 1) : (g == 0)) return;
     const bf16_t* X = (which == 0 ? K : Q) + ubase;
     const bf16_t* Y = (which == 0 ? V : dO) + ubase;
     float* out = (which == 0 ? fwd_tot : rev_tot) + (size_t(unit) * G + g) * D * D;
@@ -184,7 +185,6 @@ __global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
             out[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r] =
                 acc[x][y][v];
     }
-    __syncthreads();
   }
 }
 
@@ -672,8 +672,22 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   hipError_t err;
   if (a.G > 1) {
-    err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, C>, grid, block, 0,
-                        a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G, a.seg_rows, inv_eps);
+    // The totals kernel is bound by the latency of one global fetch per tile of rows, so it
+    // takes the largest row tile that a segment fills; blockIdx.y picks the operand pair.
+    const dim3 tgrid(units * a.G, 2);
+    constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
+    if (a.seg_rows >= TOP)
+      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, TOP>, tgrid,
+                          dim3(4 * TOP), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N,
+                          a.G, a.seg_rows, inv_eps);
+    else if (a.seg_rows >= 128)
+      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, 128>, tgrid,
+                          dim3(512), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G,
+                          a.seg_rows, inv_eps);
+    else
+      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, 64>, tgrid,
+                          dim3(256), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G,
+                          a.seg_rows, inv_eps);
     if (err != hipSuccess) return err;
     if (!sum_in_scan) {
       err = launch_bwd_state_carry(fwd_states, rev_states, units, a.G, D * D, a.stream);

@@ -360,9 +360,21 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   // few segments: no carry launch, each scan workgroup adds up the totals before its segment
   const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   if (a.G > 1) {
-    err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, C>,
-                        dim3(units * (a.G - 1)), dim3(Cfg::NT), 0, a.stream, K, V, ws, a.N, a.G,
-                        a.G - 1, a.seg_rows, inv_eps);
+    // The totals kernel takes the largest row tile that does not exceed the segment: with
+    // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
+    // paying one memory latency per 64-row chunk.
+    const dim3 grid(units * (a.G - 1));
+    constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
+    if (a.seg_rows >= TOP)
+      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
+                          dim3(4 * TOP), 0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows,
+                          inv_eps);
+    else if (a.seg_rows >= 128)
+      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
+                          0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+    else
+      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256),
+                          0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
     if (err != hipSuccess) return err;
     if (!sum_in_scan) {
       err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
