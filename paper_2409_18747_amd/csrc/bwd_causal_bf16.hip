@@ -261,27 +261,22 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
     for (int y = 0; y < AT::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (fwd_states != nullptr && g > 0 && AT::active(w)) {
-    const int first = sum_totals ? 0 : g, last = sum_totals ? g - 1 : g;
-    for (int gp = first; gp <= last; ++gp) {
-      const float* src = fwd_states + (size_t(unit) * G + gp) * D * D;
-#pragma unroll
-      for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            sacc[x][y][v] +=
-                src[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r];
-    }
-  }
-
+  // the first chunk's rows and the stored states are all requested before anything waits
   float ds_lane = 0.f;
   Stage qst, kst, vst, gst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   gst.fetch(Gu, row_begin, row_end);
+  if (fwd_states != nullptr && g > 0 && AT::active(w)) {
+    const float* src = fwd_states + size_t(unit) * G * D * D;
+    add_stored_states<AT::STATE_BATCH>(
+        sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
+          const float* p = src + size_t(gp) * D * D + (16 * AT::row_tile(w, y) + 4 * q4) * D +
+                           16 * AT::col_tile(w, x) + r;
+          return f32x4{p[0], p[D], p[2 * D], p[3 * D]};
+        });
+  }
 
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     if (AT::active(w)) {
@@ -467,19 +462,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
     for (int y = 0; y < AT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (rev_states != nullptr && g < G - 1 && AT::active(w)) {
-    const int first = sum_totals ? g + 1 : g, last = sum_totals ? G - 1 : g;
-    for (int gp = first; gp <= last; ++gp) {
-      const float* src = rev_states + (size_t(unit) * G + gp) * D * D;
-#pragma unroll
-      for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-          racc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::col_tile(w, x) + r) * D +
-                                                        16 * AT::row_tile(w, y) + 4 * q4);
-    }
-  }
-
+  // the last chunk's rows and the stored states are all requested before anything waits
   Stage qst, kst, vst, gst;
   {
     const int first = row_begin + (n_chunks - 1) * C;
@@ -487,6 +470,15 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     kst.fetch(Ku, first, row_end);
     vst.fetch(Vu, first, row_end);
     gst.fetch(Gu, first, row_end);
+  }
+  if (rev_states != nullptr && g < G - 1 && AT::active(w)) {
+    const float* src = rev_states + size_t(unit) * G * D * D;
+    add_stored_states<AT::STATE_BATCH>(
+        racc, sum_totals ? g + 1 : g, sum_totals ? G - 1 : g, [&](int gp, int x, int y) {
+          return *reinterpret_cast<const f32x4*>(src + size_t(gp) * D * D +
+                                                 (16 * AT::col_tile(w, x) + r) * D +
+                                                 16 * AT::row_tile(w, y) + 4 * q4);
+        });
   }
 
   for (int c = n_chunks - 1; c >= 0; --c) {

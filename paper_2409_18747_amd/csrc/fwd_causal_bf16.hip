@@ -177,6 +177,7 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
   __shared__ float rq[C];
 
+  COTTN_TRACE_POINT(7);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
@@ -198,23 +199,22 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
     for (int y = 0; y < ST::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (seg_states != nullptr && g > 0 && ST::active(w)) {
-    const int first = sum_totals ? 0 : g, last = sum_totals ? g - 1 : g;
-    for (int gp = first; gp <= last; ++gp) {
-      const float* src = seg_states + (size_t(unit) * G + gp) * D * D;
-#pragma unroll
-      for (int x = 0; x < ST::NCT; ++x)
-#pragma unroll
-        for (int y = 0; y < ST::NRT; ++y)
-          sacc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(w, x) + r) * D +
-                                                        16 * ST::row_tile(w, y) + 4 * q4);
-    }
-  }
-
+  // the first chunk's rows and the stored states are all requested before anything waits
   Stage qst, kst, vst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
+  if (seg_states != nullptr && g > 0 && ST::active(w)) {
+    const float* src = seg_states + size_t(unit) * G * D * D + (16 * ST::col_tile(w, 0) + r) * D +
+                       16 * ST::row_tile(w, 0) + 4 * q4;
+    add_stored_states<ST::STATE_BATCH>(
+        sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
+          return *reinterpret_cast<const f32x4*>(
+              src + size_t(gp) * D * D +
+              16 * (ST::col_tile(w, x) - ST::col_tile(w, 0)) * D +
+              16 * (ST::row_tile(w, y) - ST::row_tile(w, 0)));
+        });
+  }
 
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     COTTN_TRACE_POINT(0);

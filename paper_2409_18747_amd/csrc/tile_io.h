@@ -120,12 +120,43 @@ struct AccTiles {
   static constexpr int NCT = (NW >= DT) ? 1 : DT / NW;      // column tiles per wave
   static constexpr int WPC = (NW >= DT) ? NW / DT : 1;      // waves per tile column
   static constexpr int NRT = (WPC >= DT) ? 1 : DT / WPC;    // row tiles per wave
+  // stored states a wave loads at once when it seeds its accumulators (register budget)
+  static constexpr int STATE_BATCH = NCT * NRT <= 4 ? 3 : NCT * NRT <= 8 ? 2 : 1;
   __device__ static __forceinline__ bool active(int w) { return (w / DT) * NRT < DT; }
   __device__ static __forceinline__ int col_tile(int w, int x) { return (w % DT) + x * NW; }
   __device__ static __forceinline__ int row_tile(int w, int y) {
     return (NW >= DT) ? (w / DT) * NRT + y : y;
   }
 };
+
+// acc += the wave's tiles of the stored states first..last, `load(state, x, y)` returning
+// tile (x, y) of one of them.  States are taken BATCH at a time with every load of a batch
+// issued before the first addition, so a batch costs one memory latency, not one per state.
+// Slots of the last batch beyond `last` re-read `last` (an address already in flight) and
+// are discarded.
+template <int BATCH, int NCT, int NRT, class LoadTile>
+__device__ __forceinline__ void add_stored_states(f32x4 (&acc)[NCT][NRT], int first, int last,
+                                                  LoadTile load) {
+  for (int base = first; base <= last; base += BATCH) {
+    f32x4 t[BATCH][NCT][NRT];
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i)
+#pragma unroll
+      for (int x = 0; x < NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < NRT; ++y) t[i][x][y] = load(min(base + i, last), x, y);
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+      const bool keep = base + i <= last;
+#pragma unroll
+      for (int x = 0; x < NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < NRT; ++y)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[x][y][v] += keep ? t[i][x][y][v] : 0.f;
+    }
+  }
+}
 
 // Stores a wave's 16-row x D-column result block whose accumulators are laid out
 // TRANSPOSED (acc[nt][v] = result[row r][column 16 nt + 4 q4 + v], i.e. each lane holds 4
