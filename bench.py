@@ -29,7 +29,6 @@ KERNEL_ROW_TENSORS = {
     "bwd_dq_scan_bf16": 5,          # Q, K, V, dO in; dQ out
     "bwd_dkdv_scan_bf16": 6,        # Q, K, V, dO in; dK, dV out
     "fwd_segment_state_bf16": 2,    # K, V in (state totals are d*d per segment, added below)
-    "bwd_segment_states_bf16": 4,   # Q, K, V, dO in
 }
 
 
@@ -102,20 +101,21 @@ def other_workloads(torch, cottn, workloads):
     t.update({n: torch.empty_like(t["Q"]) for n in ("O", "dQ", "dK", "dV")})
     s = torch.ones(H, device=dev)
     for chunk in (64, 128, 256):
-        ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
-                             cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, chunk)),
+        fwd_ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
+                                 256), dtype=torch.uint8, device=dev)
+        ws = torch.empty(cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, chunk),
                          dtype=torch.uint8, device=dev)
 
         def long_ctx(i):
-            cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=ws, chunk=chunk)
+            cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=fwd_ws, chunk=chunk)
             cottn.cottn_bwd_causal(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"],
-                                   dV=t["dV"], ds=ds, workspace=ws, chunk=chunk)
+                                   dV=t["dV"], ds=ds, workspace=ws, chunk=chunk, fwd_workspace=fwd_ws)
         ms = time_calls(torch, long_ctx, 20, 3)
         byt = 11 * B * H * N * d * 2
         out["cfg4_long_context_chunk%d" % chunk] = {
             "ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3), "algorithmic_GBs": byt / ms / 1e6,
             "segments": cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
-            "workspace_bytes": ws.numel()}
+            "workspace_bytes": ws.numel() + fwd_ws.numel()}
     return out
 
 
@@ -162,18 +162,21 @@ def main():
         sets.append(t)
         if i == 0:
             host_inputs = x
-    ws_bytes = max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, args.chunk),
-                   cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, args.chunk), 256)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    # As in a training step, the backward is handed the forward's workspace: the forward-time
+    # segment states it holds are what the forward saves for the backward.
+    fwd_ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, args.chunk),
+                             256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d, args.chunk),
+                         256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(i):
         t = sets[i % len(sets)]
-        cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], t["s"], O=t["O"], workspace=ws,
+        cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], t["s"], O=t["O"], workspace=fwd_ws,
                                chunk=args.chunk, stream=stream)
         cottn.cottn_bwd_causal(t["Q"], t["K"], t["V"], t["s"], t["dO"], dQ=t["dQ"], dK=t["dK"],
                                dV=t["dV"], ds=t["ds"], workspace=ws, chunk=args.chunk,
-                               stream=stream)
+                               stream=stream, fwd_workspace=fwd_ws)
 
     if args.copy_calibration_mib:
         src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -245,7 +248,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": B, "H": H, "N": N, "d": d,
                    "chunk": args.chunk or 64, "segments_fwd": G_f, "segments_bwd": G_b,
-                   "buffer_sets": len(sets), "step": "cottn_fwd_causal + cottn_bwd_causal"},
+                   "buffer_sets": len(sets), "step": "cottn_fwd_causal + cottn_bwd_causal (given the forward's workspace)"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "step_hbm": {"algorithmic_bytes": step_bytes, "achieved_GBs": step_gbs,

@@ -94,11 +94,18 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
 
 /* Causal backward (Sec. 4, gradient formulas; dK and dV use the cumulative sum that runs
  * backward in time).  Takes the raw Q, K, V of the forward call and dO = dL/dO; writes
- * dQ, dK, dV (same shape and dtype) and ds[H] = dL/ds (overwritten). */
+ * dQ, dK, dV (same shape and dtype) and ds[H] = dL/ds (overwritten).
+ *   fwd_workspace: NULL, or the workspace that a completed cottn_fwd_causal call with the same
+ *   K, V, B, H, N, d, chunk, dtype and eps used, untouched since (device pointer, read only,
+ *   fwd_workspace_bytes as passed there).  It holds the forward-time segment states of
+ *   Kh^T V, which the backward needs again: given them it does not rebuild them from K and V.
+ *   They are taken over only for bfloat16 and when forward and backward split the sequence
+ *   the same way (cottn_segments agrees for both ops); otherwise the argument is ignored.
+ *   Contents that do not come from such a call give wrong gradients, not an error. */
 int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                     void* dQ, void* dK, void* dV, float* ds, void* workspace,
-                     size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
-                     float eps, void* hip_stream);
+                     void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                     int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream);
 
 /* Bidirectional forward (Sec. 4, eq. subQuadCos, right-hand side).
  *   state: NULL, or float[B][H][d][d] out = Kh^T V. */

@@ -41,7 +41,8 @@ def _load():
     lib.cottn_fwd_causal.restype = i
     lib.cottn_fwd_causal.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
     lib.cottn_bwd_causal.restype = i
-    lib.cottn_bwd_causal.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_causal.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i, i, i,
+                                     f, vp]
     lib.cottn_fwd_bidir.restype = i
     lib.cottn_fwd_bidir.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
     lib.cottn_bwd_bidir.restype = i
@@ -133,8 +134,11 @@ def cottn_fwd_causal(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, ep
 
 
 def cottn_bwd_causal(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None, chunk=0,
-                     eps=1e-6, stream=None):
-    """Gradients of cottn_fwd_causal wrt raw Q, K, V and s; returns (dQ, dK, dV, ds)."""
+                     eps=1e-6, stream=None, fwd_workspace=None):
+    """Gradients of cottn_fwd_causal wrt raw Q, K, V and s; returns (dQ, dK, dV, ds).
+
+    fwd_workspace: the workspace tensor the matching cottn_fwd_causal call used (untouched
+    since), or None; see include/cottn.h."""
     B, H, N, d = Q.shape
     dt = _dtype_code(Q)
     dQ = torch.empty_like(Q) if dQ is None else dQ
@@ -142,9 +146,10 @@ def cottn_bwd_causal(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspa
     dV = torch.empty_like(Q) if dV is None else dV
     ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
     workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
     st = lib.cottn_bwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
-                              _ptr(dV), _ptr(ds), _ptr(workspace), have, B, H, N, d, chunk, dt,
-                              eps, _stream(stream))
+                              _ptr(dV), _ptr(ds), _ptr(fwd_workspace), fwd_have, _ptr(workspace),
+                              have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_causal")
     return dQ, dK, dV, ds
 

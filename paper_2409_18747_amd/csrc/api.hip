@@ -184,9 +184,9 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
 }
 
 int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                     void* dQ, void* dK, void* dV, float* ds, void* workspace,
-                     size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
-                     float eps, void* hip_stream) {
+                     void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                     int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
   int st = check_common(req, 9, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
@@ -202,6 +202,18 @@ int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s
   a.workspace = workspace;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
+  // the forward's segment states are taken over only if the forward split the sequence as
+  // the backward does
+  if (fwd_workspace != nullptr && dtype == COTTN_BF16 && plan.G > 1) {
+    SeqPlan fwd_plan;
+    if (make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &fwd_plan) &&
+        fwd_plan.C == plan.C && fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
+      st = check_workspace(fwd_workspace, fwd_workspace_bytes,
+                           workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, fwd_plan));
+      if (st != COTTN_OK) return st;
+      a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
+    }
+  }
   return map_hip(dtype == COTTN_BF16 ? bwd_causal_bf16(a) : bwd_causal_f32(a));
 }
 

@@ -56,13 +56,12 @@ struct BwdCfg {
   static constexpr int STATE = D * PITCH;
   static constexpr int LDS_BYTES = 2 * (4 * TILE + STATE) + 4 * C + 64;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
+  // the dQ kernel adds a staging tile when that does not lower the workgroups per compute unit
+  static constexpr bool DQ_OWN_STAGE =
+      LDS_BYTES + 2 * TILE <= 160 * 1024 && (160 * 1024) / (LDS_BYTES + 2 * TILE) == WG_PER_CU;
   static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
   static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
 };
-
-// Up to this many segments per (batch, head) the scan kernels add up the segment totals they
-// need themselves and the carry kernel is not launched.
-constexpr int kMaxSegmentsSummedInScan = 4;
 
 // pack a masked accumulator tile into half of an operand fragment
 __device__ __forceinline__ void put_half(bf16x8& frag, int half, f32x4 acc, bool k0, bool k1,
@@ -74,11 +73,12 @@ __device__ __forceinline__ void put_half(bf16x8& frag, int half, f32x4 acc, bool
 }
 
 // Chain rule through the row normalisation on a wave's transposed 16 x D block:
-// acc[nt][v] = dxh[row r][column 16 nt + 4 q4 + v].  Reads the raw row x from `x_rows` (the
-// wave's 16 rows of its LDS tile), forms t = x . dxh over the whole row (16 columns per lane,
-// then across the four lane rows) and replaces acc by dxh - x r^2 t (no projection for rows
-// at or below eps).  Returns r t = xh . dxh.
-template <int D>
+// acc[nt][v] = dxh[row r][column 16 nt + 4 q4 + v].  Reads the row from `x_rows` (the wave's
+// 16 rows of its LDS tile), which holds either the raw row x (NORMALISED = false) or
+// xh = r x (true); forms the dot product with dxh over the whole row (16 columns per lane,
+// then across the four lane rows) and replaces acc by dxh - xh (xh . dxh)  (no projection
+// for rows at or below eps).  Returns xh . dxh.
+template <int D, bool NORMALISED>
 __device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_rows, float rinv,
                                                  float inv_eps, int r, int q4) {
   constexpr int DT = D / 16, PITCH = lds_pitch(D);
@@ -95,108 +95,24 @@ __device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_row
     for (int v = 0; v < 4; ++v) t += xv[nt][v] * acc[nt][v];
   }
   t = sum_over_lane_rows(t);
-  const float c = (rinv == inv_eps) ? 0.f : rinv * rinv * t;
+  const float c = (rinv == inv_eps) ? 0.f : (NORMALISED ? t : rinv * rinv * t);
 #pragma unroll
   for (int nt = 0; nt < DT; ++nt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[nt][v] -= xv[nt][v] * c;
-  return rinv * t;
-}
-
-// ---------------------------------------------------------------------------------------
-// Kernel 1: per-segment totals, both [d_key][d_value]:
-//   fwd_tot[unit][g] = sum_rows k^T (r_k v)    (needed by later segments: computed for g < G-1)
-//   rev_tot[unit][g] = sum_rows q^T (r_q dO)   (needed by earlier segments: computed for g > 0)
-template <int D, int C>
-__global__ __launch_bounds__(C * 4) void bwd_segment_states_bf16(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, float* __restrict__ fwd_tot, float* __restrict__ rev_tot,
-    int N, int G, int seg_rows, float inv_eps) {
-  using Cfg = BwdCfg<D, C>;
-  using AT = AccTiles<D, Cfg::NW>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[Cfg::TILE];  // K or Q, raw
-  __shared__ __attribute__((aligned(16))) bf16_t Ys[Cfg::TILE];  // V or dO, times r of the X row
-
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
-            r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
-
-  // blockIdx.y selects the pair: 0 = (K, V) forward totals, 1 = (Q, dO) reverse totals
-  {
-    const int which = blockIdx.y;
-    if (which == 0 ? (g >= G - 1) : (g == 0)) return;
-    const bf16_t* X = (which == 0 ? K : Q) + ubase;
-    const bf16_t* Y = (which == 0 ? V : dO) + ubase;
-    float* out = (which == 0 ? fwd_tot : rev_tot) + (size_t(unit) * G + g) * D * D;
-
-    // acc[x][y]: rows = features of X (row tile y), columns = features of Y (col tile x)
-    f32x4 acc[AT::NCT][AT::NRT];
-#pragma unroll
-    for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-      for (int y = 0; y < AT::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    Stage xst, yst;
-    xst.fetch(X, row_begin, row_end);
-    yst.fetch(Y, row_begin, row_end);
-    for (int row0 = row_begin; row0 < row_end; row0 += C) {
-      float rx[Stage::PASSES];
-      xst.row_rinv(inv_eps, rx);
-      __syncthreads();
-      xst.commit_plain(Xs);
-      yst.commit_scaled(Ys, rx);
-      if (row0 + C < row_end) {
-        xst.fetch(X, row0 + C, row_end);
-        yst.fetch(Y, row0 + C, row_end);
-      }
-      __syncthreads();
-      if (AT::active(w)) {
-#pragma unroll
-        for (int p = 0; p < Cfg::NP; ++p) {
-          const int k0 = 32 * p + 8 * q4;
-          bf16x8 by[AT::NCT], ax[AT::NRT];
-#pragma unroll
-          for (int x = 0; x < AT::NCT; ++x)
-            by[x] = lds_col_frag(Ys, PITCH, k0, k0 + 4, 16 * AT::col_tile(w, x), r);
-#pragma unroll
-          for (int y = 0; y < AT::NRT; ++y)
-            ax[y] = lds_col_frag(Xs, PITCH, k0, k0 + 4, 16 * AT::row_tile(w, y), r);
-          __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
-#pragma unroll
-          for (int y = 0; y < AT::NRT; ++y)
-#pragma unroll
-            for (int x = 0; x < AT::NCT; ++x) acc[x][y] = mma16(ax[y], by[x], acc[x][y]);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-    }
-    if (AT::active(w)) {
-#pragma unroll
-      for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            out[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r] =
-                acc[x][y][v];
-    }
-  }
+  return NORMALISED ? t : rinv * t;
 }
 
 // ---------------------------------------------------------------------------------------
 // Kernel 2: blockIdx.y == 0: slot g <- sum of fwd totals of segments < g;
 //           blockIdx.y == 1: slot g <- sum of rev totals of segments > g.
-// Totals that were never computed (fwd slot G-1, rev slot 0) are not read.
+// Totals that were never computed (fwd slot G-1, rev slot 0) are not read; a null array is
+// skipped.
 __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_tot,
                                                        float* __restrict__ rev_tot, int G,
                                                        int elems_per_state, long total) {
   const long idx = long(blockIdx.x) * 256 + threadIdx.x;
-  if (idx >= total) return;
+  if (idx >= total || (blockIdx.y == 0 ? fwd_tot : rev_tot) == nullptr) return;
   const long unit = idx / elems_per_state, e = idx % elems_per_state;
   float run = 0.f;
   if (blockIdx.y == 0) {
@@ -227,17 +143,22 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
-    const float* __restrict__ fwd_states, float* __restrict__ ds_partial, int H, int N, int G,
-    int seg_rows, float inv_eps, int sum_totals) {
+    const float* __restrict__ fwd_states, float* __restrict__ rev_totals,
+    float* __restrict__ ds_partial, int H, int N, int G, int seg_rows, float inv_eps,
+    int sum_totals) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // qh = r_i q_i
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
   __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
   __shared__ __attribute__((aligned(16))) bf16_t St[Cfg::STATE];  // state, [d_value][d_key]
+  // Every wave reads all rows of all four tiles until the end of a chunk (the reverse total
+  // contracts Qs and Gs over the tokens), so finished dQ rows are staged in a tile of their
+  // own when LDS has room for one; otherwise behind a barrier in the dead dO tile.
+  __shared__ __attribute__((aligned(16))) bf16_t Os[Cfg::DQ_OWN_STAGE ? Cfg::TILE : 8];
   __shared__ float rq[C];
   __shared__ float ds_wave[Cfg::NW];
 
@@ -257,10 +178,18 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   // fwd_states holds the carried prefixes (slot g = state at the start of segment g) or, with
   // sum_totals set, the raw segment totals, which this workgroup then adds up itself
   f32x4 sacc[AT::NCT][AT::NRT];
+  // By-product for the dK/dV kernel: this segment's total of qh^T dO (segments after the
+  // first; earlier segments need it), accumulated in that kernel's layout: element [v] of
+  // lane (r, q4) of tile (y, x) is R[key 16 ct + r][value 16 rt + 4 q4 + v].
+  f32x4 racc[AT::NCT][AT::NRT];
+  const bool with_rev = rev_totals != nullptr && g > 0;
 #pragma unroll
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < AT::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int y = 0; y < AT::NRT; ++y) {
+      sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+      racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
   // the first chunk's rows and the stored states are all requested before anything waits
   float ds_lane = 0.f;
   Stage qst, kst, vst, gst;
@@ -295,7 +224,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
       float rqv[Stage::PASSES], rkv[Stage::PASSES];
       qst.row_rinv(inv_eps, rqv);
       kst.row_rinv(inv_eps, rkv);
-      qst.commit_plain(Qs);
+      qst.commit_scaled(Qs, rqv);
       qst.store_rinv(rq, rqv);
       kst.commit_plain(Ks);
       vst.commit_scaled(Vs, rkv);
@@ -337,6 +266,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
       const bool diag_or_below = 2 * p <= w;
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the A slots
       bf16x8 kc[Cfg::DT], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KS];
+      bf16x8 qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) kc[nt] = lds_col_frag(Ks, PITCH, t0, t1, 16 * nt, r);
 #pragma unroll
@@ -346,6 +276,14 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
           krow[y] = lds_col_frag(Ks, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
+      }
+      if (with_rev && AT::active(w)) {
+#pragma unroll
+        for (int x = 0; x < AT::NCT; ++x)
+          qcol[x] = lds_col_frag(Qs, PITCH, t0, t1, 16 * AT::col_tile(w, x), r);
+#pragma unroll
+        for (int y = 0; y < AT::NRT; ++y)
+          grow[y] = lds_col_frag(Gs, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
@@ -378,18 +316,38 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
 #pragma unroll
           for (int x = 0; x < AT::NCT; ++x)
             sacc[x][y] = mma16(AT::WPC == 1 ? kc[y] : krow[y], vcol[x], sacc[x][y]);
+        // reverse total: R^T += dO^T qh over the same tokens
+        if (with_rev) {
+#pragma unroll
+          for (int y = 0; y < AT::NRT; ++y)
+#pragma unroll
+            for (int x = 0; x < AT::NCT; ++x) racc[x][y] = mma16(grow[y], qcol[x], racc[x][y]);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // epilogue: normalisation chain rule on the rows, then s r_i and the store through this
-    // wave's own (dead) rows of Gs
+    // epilogue: normalisation chain rule on the rows (Qs holds qh), then s r_i and the store
     const float ri = rq[16 * w + r];
-    const float rho = project_out_row<D>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
+    const float rho = project_out_row<D, true>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
     if (q4 == 0) ds_lane += rho;
-    wave_lds_sync();  // this wave's reads of its Gs rows (gf) precede the staging writes
-    store_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
+    if (Cfg::DQ_OWN_STAGE) {
+      store_rows_transposed<D>(dq, scale * ri, Os + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
+    } else {
+      __syncthreads();  // every wave is done with the dO tile
+      store_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
+    }
     __syncthreads();
+  }
+
+  if (with_rev && AT::active(w)) {
+    float* out = rev_totals + (size_t(unit) * G + g) * D * D;
+#pragma unroll
+    for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < AT::NRT; ++y)
+        *reinterpret_cast<f32x4*>(out + (16 * AT::col_tile(w, x) + r) * D +
+                                  16 * AT::row_tile(w, y) + 4 * q4) = racc[x][y];
   }
 
   // per-workgroup partial of ds: lanes of the first lane row hold the row sums
@@ -612,7 +570,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     // epilogue: dv_j = s r_j dv; dk_j through the normalisation chain rule; both staged in
     // this wave's own (dead) rows of Vs and Ks
     const float rj = rk[16 * w + r];
-    project_out_row<D>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
+    project_out_row<D, false>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
     wave_lds_sync();  // own Ks / Vs rows (kf, vf, raw k) were read before the staging writes
     store_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, dKu, row0 + 16 * w, row_end, l);
     store_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, dVu, row0 + 16 * w, row_end, l);
@@ -650,46 +608,41 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   const bf16_t* V = static_cast<const bf16_t*>(a.V);
   const bf16_t* dO = static_cast<const bf16_t*>(a.dO);
   char* ws = static_cast<char*>(a.workspace);
-  float* fwd_states = nullptr;
+  const float* fwd_states = nullptr;
   float* rev_states = nullptr;
-  if (a.G > 1) {
-    fwd_states = reinterpret_cast<float*>(ws);
-    rev_states = reinterpret_cast<float*>(ws + state_array_bytes(a.B, a.H, D, a.G));
-    ws += 2 * state_array_bytes(a.B, a.H, D, a.G);
-  }
-  float* ds_partial = reinterpret_cast<float*>(ws);
   const dim3 grid(units * a.G), block(Cfg::NT);
   const float inv_eps = 1.0f / a.eps;
-  // few segments: no carry launch, the scan workgroups add up the totals they need
+  // few segments: no carry launches, the scan workgroups add up the totals they need
   const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   hipError_t err;
   if (a.G > 1) {
-    // The totals kernel is bound by the latency of one global fetch per tile of rows, so it
-    // takes the largest row tile that a segment fills; blockIdx.y picks the operand pair.
-    const dim3 tgrid(units * a.G, 2);
-    constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
-    if (a.seg_rows >= TOP)
-      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, TOP>, tgrid,
-                          dim3(4 * TOP), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N,
-                          a.G, a.seg_rows, inv_eps);
-    else if (a.seg_rows >= 128)
-      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, 128>, tgrid,
-                          dim3(512), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G,
-                          a.seg_rows, inv_eps);
-    else
-      err = launch_kernel("bwd_segment_states_bf16", bwd_segment_states_bf16<D, 64>, tgrid,
-                          dim3(256), 0, a.stream, Q, K, V, dO, fwd_states, rev_states, a.N, a.G,
-                          a.seg_rows, inv_eps);
-    if (err != hipSuccess) return err;
-    if (!sum_in_scan) {
-      err = launch_bwd_state_carry(fwd_states, rev_states, units, a.G, D * D, a.stream);
+    // Forward-time states: taken over from the forward call when it left them behind (raw
+    // totals or carried prefixes, by the same rule as here), else recomputed from K and V.
+    float* own_fwd = reinterpret_cast<float*>(ws);
+    rev_states = reinterpret_cast<float*>(ws + state_array_bytes(a.B, a.H, D, a.G));
+    ws += 2 * state_array_bytes(a.B, a.H, D, a.G);
+    if (a.saved_fwd_states != nullptr) {
+      fwd_states = a.saved_fwd_states;
+    } else {
+      err = launch_fwd_segment_totals_bf16(a, own_fwd);
       if (err != hipSuccess) return err;
+      if (!sum_in_scan) {
+        err = launch_bwd_state_carry(own_fwd, nullptr, units, a.G, D * D, a.stream);
+        if (err != hipSuccess) return err;
+      }
+      fwd_states = own_fwd;
     }
   }
+  float* ds_partial = reinterpret_cast<float*>(ws);
+  // the dQ scan leaves the reverse-time segment totals (of qh^T dO) behind for the dK/dV scan
   err = launch_kernel("bwd_dq_scan_bf16", bwd_dq_scan_bf16<D, C>, grid, block, 0, a.stream, Q, K, V,
-                      dO, a.s, static_cast<bf16_t*>(a.dQ), fwd_states, ds_partial, a.H, a.N, a.G,
-                      a.seg_rows, inv_eps, sum_in_scan ? 1 : 0);
+                      dO, a.s, static_cast<bf16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
+                      a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0);
   if (err != hipSuccess) return err;
+  if (a.G > 1 && !sum_in_scan) {
+    err = launch_bwd_state_carry(nullptr, rev_states, units, a.G, D * D, a.stream);
+    if (err != hipSuccess) return err;
+  }
   // the dK/dV kernel also reduces the ds partial sums written by the dQ kernel
   return launch_kernel("bwd_dkdv_scan_bf16", bwd_dkdv_scan_bf16<D, C>, grid, block, 0, a.stream, Q,
                        K, V, dO, a.s, static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV),

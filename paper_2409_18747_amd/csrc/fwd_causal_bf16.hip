@@ -57,10 +57,6 @@ struct FwdCfg {
   static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
 };
 
-// Up to this many segments per (batch, head) the scan kernel adds up the segment totals
-// before its own segment itself and the carry kernel is not launched.
-constexpr int kMaxSegmentsSummedInScan = 4;
-
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
 // grid = units * n_compute workgroups; segment g of a unit writes slot g of the unit's
@@ -360,21 +356,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   // few segments: no carry launch, each scan workgroup adds up the totals before its segment
   const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   if (a.G > 1) {
-    // The totals kernel takes the largest row tile that does not exceed the segment: with
-    // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
-    // paying one memory latency per 64-row chunk.
-    const dim3 grid(units * (a.G - 1));
-    constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
-    if (a.seg_rows >= TOP)
-      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
-                          dim3(4 * TOP), 0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows,
-                          inv_eps);
-    else if (a.seg_rows >= 128)
-      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
-                          0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
-    else
-      err = launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256),
-                          0, a.stream, K, V, ws, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+    err = launch_fwd_segment_totals_bf16(a, ws);
     if (err != hipSuccess) return err;
     if (!sum_in_scan) {
       err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
@@ -388,6 +370,36 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 }
 
 }  // namespace
+
+template <int D>
+static hipError_t run_fwd_segment_totals(const CausalArgs& a, float* dst) {
+  const bf16_t* K = static_cast<const bf16_t*>(a.K);
+  const bf16_t* V = static_cast<const bf16_t*>(a.V);
+  const float inv_eps = 1.0f / a.eps;
+  // The totals kernel takes the largest row tile that does not exceed the segment: with
+  // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
+  // paying one memory latency per 64-row chunk.
+  const dim3 grid(a.B * a.H * (a.G - 1));
+  constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
+  if (a.seg_rows >= TOP)
+    return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
+                         dim3(4 * TOP), 0, a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows,
+                         inv_eps);
+  if (a.seg_rows >= 128)
+    return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
+                         0, a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+  return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256), 0,
+                       a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+}
+
+hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst) {
+  switch (a.d) {
+    case 32: return run_fwd_segment_totals<32>(a, dst);
+    case 64: return run_fwd_segment_totals<64>(a, dst);
+    case 128: return run_fwd_segment_totals<128>(a, dst);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {
   const long total = long(units) * elems;

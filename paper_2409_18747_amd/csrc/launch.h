@@ -15,11 +15,20 @@ struct CausalArgs {
   const void* dO;                 // backward only
   void* O; float* state;          // forward only (state may be null)
   void* dQ; void* dK; void* dV; float* ds;  // backward only
+  // backward only: null, or the segment states the forward call with the same split left in
+  // its workspace (then the backward does not recompute them)
+  const float* saved_fwd_states;
   void* workspace;
   int B, H, N, d, C, G, seg_rows;
   float eps;
   hipStream_t stream;
 };
+
+// Up to this many segments per (batch, head) the scan kernels add up the segment totals they
+// need themselves and no carry kernel is launched; above it the state arrays hold prefixes
+// (suffixes for the reverse-time states).  The forward and the backward must agree on it for
+// the backward to take over the forward's saved states.
+constexpr int kMaxSegmentsSummedInScan = 4;
 
 struct StepArgs {
   const void* q; const void* k; const void* v; const float* s; float* state; void* o;
@@ -41,8 +50,12 @@ hipError_t step_any(const StepArgs& a, int dtype);
 
 // small fp32 state kernels shared by the bf16 and fp32 paths (defined next to their kernels)
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st);
+// either array may be null: then only the other one is carried
 hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
                                   hipStream_t st);
+// bf16 segment totals of Kh^T V for all segments but the last, [units][G][d][d] fp32 in `dst`
+// (the first kernel of the causal forward, also used by a backward without saved states)
+hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
 hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st);
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st);

@@ -24,7 +24,7 @@ def lib():
     l.cottn_status_string.restype = ctypes.c_char_p
     vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     l.cottn_fwd_causal.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
-    l.cottn_bwd_causal.argtypes = [vp] * 10 + [sz, i, i, i, i, i, i, f, vp]
+    l.cottn_bwd_causal.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_fwd_bidir.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, i, i, i, i, i, f, vp]
     l.cottn_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp]
@@ -133,10 +133,18 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(p(), p(), p(), p(), p(), None, p(16), need, 1, 1, 128, 64, 0, BF16, eps, None) == E_ALIGN
     lib.cottn_tune_segments(0)
     bwd = lib.cottn_bwd_causal
-    assert bwd(p(), p(), p(), p(), None, p(), p(), p(), p(), p(), 1 << 12, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
-    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), None, p(), 1 << 12, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
-    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_WS
-    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(), 1 << 12, 1, 1, 8, 64, 0, 9, eps, None) == E_DTYPE
+    assert bwd(p(), p(), p(), p(), None, p(), p(), p(), p(), None, 0, p(), 1 << 12, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
+    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), None, None, 0, p(), 1 << 12, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
+    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_WS
+    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 1 << 12, 1, 1, 8, 64, 0, 9, eps, None) == E_DTYPE
+    # a forward workspace that is handed over must be as large and as aligned as the forward
+    # needed it (two segments here); with one segment there is nothing to take over
+    lib.cottn_tune_segments(2)
+    fneed = lib.cottn_workspace_bytes(0, 1, 1, 128, 64, 0, BF16)
+    bneed = lib.cottn_workspace_bytes(1, 1, 1, 128, 64, 0, BF16)
+    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(), fneed - 1, p(), bneed, 1, 1, 128, 64, 0, BF16, eps, None) == E_WS
+    assert bwd(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(16), fneed, p(), bneed, 1, 1, 128, 64, 0, BF16, eps, None) == E_ALIGN
+    lib.cottn_tune_segments(0)
     assert lib.cottn_fwd_bidir(p(), p(), None, p(), p(), None, p(), 1 << 15, 1, 1, 8, 64, BF16, eps, None) == E_NULL
     assert lib.cottn_fwd_bidir(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 64, BF16, eps, None) == E_WS
     assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(), 16, 1, 1, 8, 64, BF16, eps, None) == E_WS

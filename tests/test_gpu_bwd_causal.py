@@ -14,7 +14,8 @@ def cottn():
     b.cottn_tune_segments(0)
 
 
-def run_bwd(cottn, oracle, B, H, N, d, dtype, seed, chunk=0, segments=0, scale=1.0, mutate=None):
+def run_bwd(cottn, oracle, B, H, N, d, dtype, seed, chunk=0, segments=0, scale=1.0, mutate=None,
+            saved=False):
     import torch
     from paper_2409_18747_amd import workloads
     x = workloads.draw(B, H, N, d, dtype, seed, value_scale=scale)
@@ -23,7 +24,14 @@ def run_bwd(cottn, oracle, B, H, N, d, dtype, seed, chunk=0, segments=0, scale=1
     Q, K, V, dO = (to_device(x[k], dtype) for k in ("Q", "K", "V", "dO"))
     s = to_device(x["s"], "f32")
     cottn.cottn_tune_segments(segments)
-    dQ, dK, dV, ds = cottn.cottn_bwd_causal(Q, K, V, s, dO, chunk=chunk)
+    fwd_ws = None
+    if saved:
+        # the backward takes the forward-time segment states over from the forward's workspace
+        code = cottn.COTTN_BF16 if dtype == "bf16" else cottn.COTTN_F32
+        need = cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk, code)
+        fwd_ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        cottn.cottn_fwd_causal(Q, K, V, s, workspace=fwd_ws, chunk=chunk)
+    dQ, dK, dV, ds = cottn.cottn_bwd_causal(Q, K, V, s, dO, chunk=chunk, fwd_workspace=fwd_ws)
     torch.cuda.synchronize()
     if N <= 1024:
         ref = oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], causal=True)
@@ -58,6 +66,22 @@ def test_bf16_segmented(cottn, oracle, segments, d, N):
 def test_bf16_chunk_sizes(cottn, oracle, chunk, d):
     for segments in (1, 3):
         run_bwd(cottn, oracle, 1, 3, 900, d, "bf16", seed=12, chunk=chunk, segments=segments)
+
+
+@pytest.mark.parametrize("segments", [1, 2, 4, 7])
+@pytest.mark.parametrize("d,N", [(64, 517), (128, 330), (32, 700)])
+def test_bf16_states_saved_by_forward(cottn, oracle, segments, d, N):
+    """With the forward's workspace handed over the gradients meet the same bar and equal, bit
+    for bit, those of the backward that rebuilds the states (same kernel, same values)."""
+    import torch
+    a = run_bwd(cottn, oracle, 2, 2, N, d, "bf16", seed=31, segments=segments, saved=True)
+    b = run_bwd(cottn, oracle, 2, 2, N, d, "bf16", seed=31, segments=segments, saved=False)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_f32_ignores_forward_workspace(cottn, oracle):
+    run_bwd(cottn, oracle, 1, 2, 200, 64, "f32", seed=5, segments=3, saved=True)
 
 
 def test_bf16_default_plan_gpt_shape(cottn, oracle):
