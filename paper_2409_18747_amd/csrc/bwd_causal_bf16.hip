@@ -207,6 +207,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
         });
   }
 
+  RowPieces<D> finished;  // dQ rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     if (AT::active(w)) {
 #pragma unroll
@@ -236,6 +239,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
       vst.fetch(Vu, row0 + C, row_end);
       gst.fetch(Gu, row0 + C, row_end);
     }
+    if (row0 > row_begin) store_row_pieces<D>(finished, dQu, row0 - C + 16 * w, row_end, l);
     __syncthreads();
 
     // earlier chunks: dqh^T += S dO^T (contraction over d_value = rows of St)
@@ -332,12 +336,16 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     const float rho = project_out_row<D, true>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
     if (q4 == 0) ds_lane += rho;
     if (Cfg::DQ_OWN_STAGE) {
-      store_rows_transposed<D>(dq, scale * ri, Os + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
+      gather_rows_transposed<D>(dq, scale * ri, Os + 16 * w * PITCH, l, finished);
     } else {
       __syncthreads();  // every wave is done with the dO tile
-      store_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, dQu, row0 + 16 * w, row_end, l);
+      gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, l, finished);
     }
     __syncthreads();
+  }
+  if (row_begin < row_end) {
+    const int last = row_begin + (row_end - row_begin - 1) / C * C;
+    store_row_pieces<D>(finished, dQu, last + 16 * w, row_end, l);
   }
 
   if (with_rev && AT::active(w)) {
@@ -439,6 +447,10 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
         });
   }
 
+  RowPieces<D> done_k, done_v;  // dK and dV rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j)
+    done_k.v[j] = done_v.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int c = n_chunks - 1; c >= 0; --c) {
     const int row0 = row_begin + c * C;
     if (AT::active(w)) {
@@ -468,6 +480,10 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
       kst.fetch(Ku, row0 - C, row_end);
       vst.fetch(Vu, row0 - C, row_end);
       gst.fetch(Gu, row0 - C, row_end);
+    }
+    if (c < n_chunks - 1) {
+      store_row_pieces<D>(done_k, dKu, row0 + C + 16 * w, row_end, l);
+      store_row_pieces<D>(done_v, dVu, row0 + C + 16 * w, row_end, l);
     }
     __syncthreads();
 
@@ -572,9 +588,13 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     const float rj = rk[16 * w + r];
     project_out_row<D, false>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
     wave_lds_sync();  // own Ks / Vs rows (kf, vf, raw k) were read before the staging writes
-    store_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, dKu, row0 + 16 * w, row_end, l);
-    store_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, dVu, row0 + 16 * w, row_end, l);
+    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, l, done_k);
+    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, l, done_v);
     __syncthreads();
+  }
+  if (n_chunks > 0) {
+    store_row_pieces<D>(done_k, dKu, row_begin + 16 * w, row_end, l);
+    store_row_pieces<D>(done_v, dVu, row_begin + 16 * w, row_end, l);
   }
 }
 

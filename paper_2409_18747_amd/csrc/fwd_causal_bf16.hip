@@ -212,6 +212,9 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
         });
   }
 
+  RowPieces<D> finished;  // output rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     COTTN_TRACE_POINT(0);
     // ---- publish the state (bf16) and this chunk's tiles
@@ -242,6 +245,7 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
     }
+    if (row0 > row_begin) store_row_pieces<D>(finished, Ou, row0 - C + 16 * w, row_end, l);
     COTTN_TRACE_POINT(2);
     __syncthreads();
     COTTN_TRACE_POINT(3);
@@ -327,9 +331,13 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
     // ---- O rows: factor s_h r_i, staged through this wave's own (now dead) rows of Qs
     const float row_factor = scale * rq[16 * w + r];
     wave_lds_sync();
-    store_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, Ou, row0 + 16 * w, row_end, l);
+    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, l, finished);
     __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
     COTTN_TRACE_POINT(6);
+  }
+  if (row_begin < row_end) {
+    const int last = row_begin + (row_end - row_begin - 1) / C * C;
+    store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
   }
 
   if (state_out != nullptr && g == G - 1 && ST::active(w)) {

@@ -70,7 +70,7 @@ struct TileStage {
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
-      if (lr < C && (tid % LPR) == 0) out[lr] = rinv[p];
+      if ((C % RPP == 0 || lr < C) && (tid % LPR) == 0) out[lr] = rinv[p];
     }
   }
 
@@ -89,7 +89,7 @@ struct TileStage {
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
-      if (lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = regs[p];
+      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = regs[p];
     }
   }
 
@@ -104,7 +104,7 @@ struct TileStage {
       unpack8(regs[p], f);
 #pragma unroll
       for (int e = 0; e < 8; ++e) f[e] *= scale[p];
-      if (lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = pack8(f);
+      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = pack8(f);
     }
   }
 };
@@ -158,15 +158,25 @@ __device__ __forceinline__ void add_stored_states(f32x4 (&acc)[NCT][NRT], int fi
   }
 }
 
-// Stores a wave's 16-row x D-column result block whose accumulators are laid out
-// TRANSPOSED (acc[nt][v] = result[row r][column 16 nt + 4 q4 + v], i.e. each lane holds 4
-// consecutive columns of one row): scales by the per-lane row factor, rounds to bf16, stages
-// through the wave's own 16 rows of an LDS tile with 8-byte writes, then writes whole
-// 16-byte pieces of rows to global memory.  Rows at or beyond row_end are not written.
+// A wave's finished 16-row x D-column result block as whole 16-byte pieces of rows, one or
+// more per lane, ready for coalesced global stores.
 template <int D>
-__device__ __forceinline__ void store_rows_transposed(const f32x4* acc, float row_factor,
-                                                      bf16_t* stage_rows, bf16_t* __restrict__ dst,
-                                                      int first_row, int row_end, int l) {
+struct RowPieces {
+  static constexpr int PIECES = 16 * D / 8;  // 16-byte pieces in the wave's 16 rows
+  static constexpr int PER_LANE = PIECES / 64;
+  static_assert(PIECES % 64 == 0, "a wave's rows must split evenly over its lanes");
+  uint4 v[PER_LANE];
+};
+
+// Turns a wave's result block whose accumulators are laid out TRANSPOSED (acc[nt][v] =
+// result[row r][column 16 nt + 4 q4 + v], i.e. each lane holds 4 consecutive columns of one
+// row) into row pieces: scales by the per-lane row factor, rounds to bf16, passes the block
+// through the wave's own 16 rows of an LDS tile with 8-byte writes and reads it back as
+// 16-byte pieces.
+template <int D>
+__device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float row_factor,
+                                                       bf16_t* stage_rows, int l,
+                                                       RowPieces<D>& out) {
   constexpr int DT = D / 16, PITCH = lds_pitch(D);
   const int r = l % 16, q4 = l / 16;
 #pragma unroll
@@ -177,15 +187,38 @@ __device__ __forceinline__ void store_rows_transposed(const f32x4* acc, float ro
     *reinterpret_cast<uint2*>(stage_rows + r * PITCH + 16 * nt + 4 * q4) = pk;
   }
   wave_lds_sync();
-  constexpr int PIECES = 16 * D / 8;  // 16-byte pieces in the wave's 16 rows
 #pragma unroll
-  for (int i = l; i < PIECES; i += 64) {
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) {
+    const int i = l + 64 * j;
+    const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
+    out.v[j] = *reinterpret_cast<const uint4*>(stage_rows + lr * PITCH + col);
+  }
+}
+
+// Writes the pieces to rows first_row.. of dst; rows at or beyond row_end are not written.
+// The scan kernels call this one chunk late (after the next chunk's loads have been issued):
+// the wait for those loads at the top of a chunk step is a wait for every outstanding memory
+// operation, and must not find stores that were issued a moment ago.
+template <int D>
+__device__ __forceinline__ void store_row_pieces(const RowPieces<D>& p, bf16_t* __restrict__ dst,
+                                                 int first_row, int row_end, int l) {
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) {
+    const int i = l + 64 * j;
     const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
     const int row = first_row + lr;
-    if (row < row_end)
-      *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) =
-          *reinterpret_cast<const uint4*>(stage_rows + lr * PITCH + col);
+    if (row < row_end) *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) = p.v[j];
   }
+}
+
+// Both at once, for the kernels that do not defer their stores.
+template <int D>
+__device__ __forceinline__ void store_rows_transposed(const f32x4* acc, float row_factor,
+                                                      bf16_t* stage_rows, bf16_t* __restrict__ dst,
+                                                      int first_row, int row_end, int l) {
+  RowPieces<D> p;
+  gather_rows_transposed<D>(acc, row_factor, stage_rows, l, p);
+  store_row_pieces<D>(p, dst, first_row, row_end, l);
 }
 
 // Sum of x over the four 16-lane rows of the wave (lanes r, r+16, r+32, r+48); every lane
