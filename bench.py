@@ -79,20 +79,21 @@ def other_workloads(torch, cottn, workloads):
         sets.append(t)
     s = torch.ones(H, device=dev)
     ds = torch.empty(H, device=dev)
-    ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_BIDIR, B, H, N, d),
-                         cottn.cottn_workspace_bytes(cottn.OP_BWD_BIDIR, B, H, N, d)),
+    fwd_ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_BIDIR, B, H, N, d), 256),
+                         dtype=torch.uint8, device=dev)
+    ws = torch.empty(cottn.cottn_workspace_bytes(cottn.OP_BWD_BIDIR, B, H, N, d),
                      dtype=torch.uint8, device=dev)
 
     def bidir(i):
         t = sets[i % 2]
-        cottn.cottn_fwd_bidir(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=ws)
+        cottn.cottn_fwd_bidir(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=fwd_ws)
         cottn.cottn_bwd_bidir(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"],
-                              dV=t["dV"], ds=ds, workspace=ws)
+                              dV=t["dV"], ds=ds, workspace=ws, fwd_workspace=fwd_ws)
     ms = time_calls(torch, bidir, 100, 10)
     byt = 11 * B * H * N * d * 2
     out["cfg3_bidir_fwd_bwd"] = {"ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3),
                                  "algorithmic_GBs": byt / ms / 1e6}
-    del sets, ws
+    del sets, ws, fwd_ws
 
     # long context causal forward + backward, N = 65536
     w = workloads.WORKLOADS["cfg4_long_causal_fwdbwd_bf16"]

@@ -114,11 +114,15 @@ int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s,
                     int d, int dtype, float eps, void* hip_stream);
 
 /* Bidirectional backward: gradients of cottn_fwd_bidir with respect to raw Q, K, V and s
- * (the gradient formulas of Sec. 4 with the mask M removed). */
+ * (the gradient formulas of Sec. 4 with the mask M removed).
+ *   fwd_workspace: NULL, or the workspace of the matching completed cottn_fwd_bidir call,
+ *   untouched since (same rules as for cottn_bwd_causal): it holds the segment totals of
+ *   Kh^T V, which the backward then does not reduce again.  Taken over for bfloat16 and a
+ *   split into few segments; otherwise ignored. */
 int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                    void* dQ, void* dK, void* dV, float* ds, void* workspace,
-                    size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
-                    void* hip_stream);
+                    void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                    size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                    int H, int N, int d, int dtype, float eps, void* hip_stream);
 
 /* One recurrent decode step for B*H independent states (Sec. 5, eq. hidden_state_obs):
  *   state[b][h] += kh^T v  (in place), then  o[b][h] = s_h * qh state[b][h]

@@ -46,7 +46,8 @@ def _load():
     lib.cottn_fwd_bidir.restype = i
     lib.cottn_fwd_bidir.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
     lib.cottn_bwd_bidir.restype = i
-    lib.cottn_bwd_bidir.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_bidir.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i, i, f,
+                                    vp]
     lib.cottn_step.restype = i
     lib.cottn_step.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, f, vp]
     lib.cottn_profile_start.restype = i
@@ -168,8 +169,9 @@ def cottn_fwd_bidir(Q, K, V, s, O=None, state=None, workspace=None, eps=1e-6, st
 
 
 def cottn_bwd_bidir(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None, eps=1e-6,
-                    stream=None):
-    """Gradients of cottn_fwd_bidir; returns (dQ, dK, dV, ds)."""
+                    stream=None, fwd_workspace=None):
+    """Gradients of cottn_fwd_bidir; returns (dQ, dK, dV, ds).  fwd_workspace: the workspace
+    tensor of the matching cottn_fwd_bidir call (untouched since), or None."""
     B, H, N, d = Q.shape
     dt = _dtype_code(Q)
     dQ = torch.empty_like(Q) if dQ is None else dQ
@@ -177,9 +179,10 @@ def cottn_bwd_bidir(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspac
     dV = torch.empty_like(Q) if dV is None else dV
     ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
     workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
     st = lib.cottn_bwd_bidir(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
-                             _ptr(dV), _ptr(ds), _ptr(workspace), have, B, H, N, d, dt, eps,
-                             _stream(stream))
+                             _ptr(dV), _ptr(ds), _ptr(fwd_workspace), fwd_have, _ptr(workspace),
+                             have, B, H, N, d, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_bidir")
     return dQ, dK, dV, ds
 

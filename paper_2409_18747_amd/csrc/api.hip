@@ -239,9 +239,9 @@ int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s,
 }
 
 int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                    void* dQ, void* dK, void* dV, float* ds, void* workspace,
-                    size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
-                    void* hip_stream) {
+                    void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                    size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                    int H, int N, int d, int dtype, float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
   int st = check_common(req, 9, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
@@ -257,6 +257,16 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
   a.workspace = workspace;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
+  if (fwd_workspace != nullptr && dtype == COTTN_BF16 && plan.G <= kMaxSegmentsSummedInScan) {
+    SeqPlan fwd_plan;
+    if (make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &fwd_plan) && fwd_plan.C == plan.C &&
+        fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
+      st = check_workspace(fwd_workspace, fwd_workspace_bytes,
+                           workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, d, fwd_plan));
+      if (st != COTTN_OK) return st;
+      a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
+    }
+  }
   return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : bwd_bidir_f32(a));
 }
 

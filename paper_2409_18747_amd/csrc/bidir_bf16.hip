@@ -8,12 +8,21 @@
 //     dQh = s dO S^T,   dKh = s V G^T,   dV = s Kh G,   ds = <S, G> (Frobenius product),
 // followed by the chain rule through the row normalisation.
 //
-// Three launches per call:
-//   totals   each workgroup reduces N(X)^T Y over one segment of rows (split over the
-//            sequence because B*H alone does not fill the chip);
-//   combine  sums the segment totals per (batch, head) into slot 0 (and into `state`);
-//            in the backward it also forms the per-(b,h) share of ds in fp32;
-//   apply    streams the rows once more and multiplies them with the d x d totals.
+// Launches per call:
+//   totals   the segment-totals kernel of the causal forward reduces N(X)^T Y over one
+//            segment of rows per workgroup (split over the sequence because B*H alone may
+//            not fill the chip), for (X, Y) = (K, V) and, in the backward, (Q, dO);
+//   combine  only with many segments, or in a backward that was not handed the forward's
+//            totals: sums the segment totals per (batch, head) into slot 0 and forms the
+//            per-(b,h) share of ds;
+//   apply    streams the rows once more and multiplies them with the d x d matrices; with
+//            few segments it adds up the segment totals itself while staging them.
+// A backward that is handed the forward's workspace does not reduce Kh^T V again, and its
+// totals kernel forms <S, G_segment> on the fly, so it is two launches.
+//
+// The apply kernels follow the scheme of the causal kernels: raw rows as MFMA operands,
+// normalisation factors on result rows, results accumulated transposed and staged through
+// the wave's own (dead) tile rows, stores one chunk late.
 #include "device_common.h"
 #include "launch.h"
 #include "tile_io.h"
@@ -32,80 +41,6 @@ struct BiCfg {
   static constexpr int TILE = C * PITCH;
   static constexpr int STATE = D * PITCH;
 };
-
-// totals[pair][unit][g] = sum over the rows of segment g of N(X)^T Y, stored [feature of X]
-// [feature of Y] in fp32.  pair = blockIdx.y selects (X, Y) = (K, V) or (Q, dO).
-template <int D, int C>
-__global__ __launch_bounds__(C * 4) void bidir_totals_bf16(
-    const bf16_t* __restrict__ X0, const bf16_t* __restrict__ Y0, const bf16_t* __restrict__ X1,
-    const bf16_t* __restrict__ Y1, float* __restrict__ totals, size_t pair_stride, int N, int G,
-    int seg_rows, float eps) {
-  using Cfg = BiCfg<D, C>;
-  using AT = AccTiles<D, Cfg::NW>;
-  constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Ys[Cfg::TILE];
-
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
-  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
-            r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* X = (blockIdx.y == 0 ? X0 : X1) + ubase;
-  const bf16_t* Y = (blockIdx.y == 0 ? Y0 : Y1) + ubase;
-  float* out = totals + blockIdx.y * pair_stride + (size_t(unit) * G + g) * D * D;
-  const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
-
-  f32x4 acc[AT::NCT][AT::NRT];
-#pragma unroll
-  for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-    for (int y = 0; y < AT::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  TileStage<D, C, Cfg::NT> xst, yst;
-  xst.fetch(X, row_begin, row_end);
-  yst.fetch(Y, row_begin, row_end);
-  for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    __syncthreads();
-    xst.commit_normalised(Xs, eps, nullptr);
-    yst.commit_plain(Ys);
-    if (row0 + C < row_end) {
-      xst.fetch(X, row0 + C, row_end);
-      yst.fetch(Y, row0 + C, row_end);
-    }
-    __syncthreads();
-    if (AT::active(w)) {
-      bf16x8 by[C / 32][AT::NCT], ax[C / 32][AT::NRT];
-#pragma unroll
-      for (int p = 0; p < C / 32; ++p) {
-        const int k0 = 32 * p + 8 * q4;
-#pragma unroll
-        for (int x = 0; x < AT::NCT; ++x)
-          by[p][x] = lds_col_frag(Ys, PITCH, k0, k0 + 4, 16 * AT::col_tile(w, x), r);
-#pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-          ax[p][y] = lds_col_frag(Xs, PITCH, k0, k0 + 4, 16 * AT::row_tile(w, y), r);
-      }
-      __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
-#pragma unroll
-      for (int p = 0; p < C / 32; ++p)
-#pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-#pragma unroll
-          for (int x = 0; x < AT::NCT; ++x) acc[x][y] = mma16(ax[p][y], by[p][x], acc[x][y]);
-    }
-  }
-  if (AT::active(w)) {
-#pragma unroll
-    for (int x = 0; x < AT::NCT; ++x)
-#pragma unroll
-      for (int y = 0; y < AT::NRT; ++y)
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-          out[(16 * AT::row_tile(w, y) + 4 * q4 + v) * D + 16 * AT::col_tile(w, x) + r] =
-              acc[x][y][v];
-  }
-}
 
 // One workgroup per (batch, head): slot 0 of each pair <- sum over g of the slots; `state`
 // (may be null) receives pair 0; with n_pairs == 2, ds_partial[unit] = sum_e S[e] * G[e].
@@ -141,27 +76,41 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
   }
 }
 
-// Copy a [D][D] fp32 matrix M (global) into LDS as bf16, either as is (dst[a][b] = M[a][b])
-// or transposed (dst[b][a] = M[a][b]).
-template <int D, int NT, bool TRANSPOSE>
-__device__ __forceinline__ void stage_matrix(bf16_t* dst, const float* __restrict__ M) {
+// dst (LDS, bf16, row-major [D][D] with the tile pitch) <- sum of the first n_sum of the
+// [D][D] fp32 matrices at src; the fp32 sum also goes to `copy` when that is not null.
+template <int D, int NT>
+__device__ __forceinline__ void stage_summed_matrix(bf16_t* dst, const float* __restrict__ src,
+                                                    int n_sum, float* __restrict__ copy) {
   constexpr int PITCH = lds_pitch(D);
-  for (int e = threadIdx.x; e < D * D; e += NT) {
-    const int a = e / D, b = e % D;
-    const bf16_t x = f32_to_bf16(M[e]);
-    if (TRANSPOSE) dst[b * PITCH + a] = x; else dst[a * PITCH + b] = x;
+  for (int e = 4 * threadIdx.x; e < D * D; e += 4 * NT) {
+    f32x4 a = *reinterpret_cast<const f32x4*>(src + e);
+    for (int j = 1; j < n_sum; ++j) {
+      const f32x4 b = *reinterpret_cast<const f32x4*>(src + size_t(j) * D * D + e);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) a[v] += b[v];
+    }
+    if (copy != nullptr) *reinterpret_cast<f32x4*>(copy + e) = a;
+    uint2 pk;
+    pk.x = pack_bf16(a[0], a[1]);
+    pk.y = pack_bf16(a[2], a[3]);
+    *reinterpret_cast<uint2*>(dst + (e / D) * PITCH + e % D) = pk;
   }
 }
 
-// O rows of one segment: O = s Qh S.
+// O rows of one segment: O_i = s r_i (q_i S), accumulated as O^T = S^T Q^T.  `totals` holds
+// n_sum stored matrices per unit at a stride of `slots` matrices; the workgroup of segment 0
+// writes their sum to `state` when that is asked for.
 template <int D, int C>
 __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
     const bf16_t* __restrict__ Q, const float* __restrict__ s, bf16_t* __restrict__ O,
-    const float* __restrict__ totals, int H, int N, int G, int seg_rows, float eps) {
+    const float* __restrict__ totals, int slots, int n_sum, float* __restrict__ state, int H, int N,
+    int G, int seg_rows, float inv_eps) {
   using Cfg = BiCfg<D, C>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t St[Cfg::STATE];  // [d_value][d_key]
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // [d_key][d_value]
+  __shared__ float rq[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
@@ -173,14 +122,26 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
-  TileStage<D, C, Cfg::NT> qst;
+  Stage qst;
   qst.fetch(Qu, row_begin, row_end);
-  stage_matrix<D, Cfg::NT, true>(St, totals + size_t(unit) * G * D * D);
+  stage_summed_matrix<D, Cfg::NT>(Sl, totals + size_t(unit) * slots * D * D, n_sum,
+                                  (state != nullptr && g == 0) ? state + size_t(unit) * D * D
+                                                               : nullptr);
 
+  RowPieces<D> finished;  // output rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    qst.commit_normalised(Qs, eps, nullptr);
+    {
+      float rqv[Stage::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      qst.commit_plain(Qs);
+      qst.store_rinv(rq, rqv);
+    }
     if (row0 + C < row_end) qst.fetch(Qu, row0 + C, row_end);
+    if (row0 > row_begin) store_row_pieces<D>(finished, Ou, row0 - C + 16 * w, row_end, l);
     __syncthreads();
+    // oacc[nt][v] = (q S)[query 16w + r][value 16 nt + 4 q4 + v]
     f32x4 oacc[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -190,77 +151,41 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
       qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
-        sf[ks][nt] = lds_row_frag(St + (16 * nt + r) * PITCH + 32 * ks + 8 * q4);
+        sf[ks][nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
     }
     __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(qf[ks], sf[ks][nt], oacc[nt]);
-    wave_lds_sync();
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        Qs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] = f32_to_bf16(scale * oacc[nt][v]);
-    wave_lds_sync();
-    constexpr int PIECES = 16 * D / 8;
-#pragma unroll
-    for (int i = l; i < PIECES; i += 64) {
-      const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-      const int row = row0 + 16 * w + lr;
-      if (row < row_end)
-        *reinterpret_cast<uint4*>(Ou + size_t(row) * D + col) =
-            *reinterpret_cast<const uint4*>(Qs + (16 * w + lr) * PITCH + col);
-    }
+      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(sf[ks][nt], qf[ks], oacc[nt]);
+    __builtin_amdgcn_sched_barrier(0);
+    const float row_factor = scale * rq[16 * w + r];
+    wave_lds_sync();  // this wave's reads of its Qs rows precede the staging writes
+    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, l, finished);
     __syncthreads();
   }
-}
-
-// row-wise chain rule through the normalisation on a wave's 16 x D accumulator block:
-// out = f_row * (acc - xh * (xh . acc)), written as bf16 into `stage` (the wave's own rows
-// of a dead LDS tile); xh is read from `xs` (same rows).  Returns per-lane (xh . acc) sums.
-template <int D>
-__device__ __forceinline__ void normalise_backward_rows(const f32x4* acc, const bf16_t* xs,
-                                                        bf16_t* stage, const float* rinv,
-                                                        float scale, float r_clamped, int w,
-                                                        int r, int q4) {
-  constexpr int DT = D / 16, PITCH = lds_pitch(D);
-  float rho[4] = {0.f, 0.f, 0.f, 0.f};
-  float xv[DT][4];
-#pragma unroll
-  for (int nt = 0; nt < DT; ++nt)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      xv[nt][v] = bf16_to_f32(xs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r]);
-      rho[v] += xv[nt][v] * acc[nt][v];
-    }
-  wave_lds_sync();
-#pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    rho[v] = group_sum<16>(rho[v]);
-    const float ri = rinv[16 * w + 4 * q4 + v];
-    const float proj = (ri == r_clamped) ? 0.f : rho[v];
-    const float f = scale * ri;
-#pragma unroll
-    for (int nt = 0; nt < DT; ++nt)
-      stage[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] =
-          f32_to_bf16(f * (acc[nt][v] - xv[nt][v] * proj));
+  if (row_begin < row_end) {
+    const int last = row_begin + (row_end - row_begin - 1) / C * C;
+    store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
   }
 }
 
-// dQ, dK, dV rows of one segment; the first H workgroups also finish ds.
+// dQ, dK, dV rows of one segment; the first H workgroups also finish ds from the n_ds
+// partial sums per (batch, head).  All products are accumulated transposed:
+//   dqh^T = S dO^T (over d_value),  dkh^T = G V^T (over d_value),  (k G)^T = G^T k^T (over
+//   d_key), then dq_i = s r_i (dqh_i - qh_i (qh_i . dqh_i)), dk_j likewise, dv_j = s r_j (k_j G).
 template <int D, int C>
 __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
-    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const float* __restrict__ totals,
-    size_t pair_stride, const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H,
-    int N, int G, int seg_rows, float eps) {
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const float* __restrict__ s_totals,
+    const float* __restrict__ g_totals, int slots, int n_sum, const float* __restrict__ ds_partial,
+    int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps) {
   using Cfg = BiCfg<D, C>;
+  using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
   __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // Kh^T V,  [d_key][d_value]
@@ -275,38 +200,60 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
   const bf16_t* Ku = K + ubase;
   const bf16_t* Vu = V + ubase;
   const bf16_t* Gu = dO + ubase;
+  bf16_t* dQu = dQ + ubase;
+  bf16_t* dKu = dK + ubase;
+  bf16_t* dVu = dV + ubase;
   const float scale = s[unit % H];
-  const float r_clamped = 1.0f / eps;
   const int row_begin = g * seg_rows;
   const int row_end = min(N, row_begin + seg_rows);
 
-  if (int(blockIdx.x) < H && tid == 0) {  // ds[h] = sum over batches of the per-(b,h) shares
-    float t = 0.f;
-    for (int b = 0; b < B; ++b) t += ds_partial[size_t(b) * H + blockIdx.x];
-    ds[blockIdx.x] = t;
-  }
-
-  TileStage<D, C, Cfg::NT> qst, kst, vst, gst;
+  Stage qst, kst, vst, gst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   gst.fetch(Gu, row_begin, row_end);
-  stage_matrix<D, Cfg::NT, false>(Sl, totals + size_t(unit) * G * D * D);
-  stage_matrix<D, Cfg::NT, false>(Gl, totals + pair_stride + size_t(unit) * G * D * D);
 
+  if (int(blockIdx.x) < H && w == 0) {  // ds[h] = sum of the shares of all batches
+    float t = 0.f;
+    const int n = B * n_ds;
+    for (int i = l; i < n; i += 64)
+      t += ds_partial[(size_t(i / n_ds) * H + blockIdx.x) * n_ds + (i % n_ds)];
+    t = group_sum<64>(t);
+    if (l == 0) ds[blockIdx.x] = t;
+  }
+  stage_summed_matrix<D, Cfg::NT>(Sl, s_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
+  stage_summed_matrix<D, Cfg::NT>(Gl, g_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
+
+  RowPieces<D> done_q, done_k, done_v;  // rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j)
+    done_q.v[j] = done_k.v[j] = done_v.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    qst.commit_normalised(Qs, eps, rq);
-    kst.commit_normalised(Ks, eps, rk);
-    vst.commit_plain(Vs);
-    gst.commit_plain(Gs);
+    {
+      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      kst.row_rinv(inv_eps, rkv);
+      qst.commit_plain(Qs);
+      qst.store_rinv(rq, rqv);
+      kst.commit_plain(Ks);
+      kst.store_rinv(rk, rkv);
+      vst.commit_plain(Vs);
+      gst.commit_plain(Gs);
+    }
     if (row0 + C < row_end) {
       qst.fetch(Qu, row0 + C, row_end);
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
       gst.fetch(Gu, row0 + C, row_end);
     }
+    if (row0 > row_begin) {
+      store_row_pieces<D>(done_q, dQu, row0 - C + 16 * w, row_end, l);
+      store_row_pieces<D>(done_k, dKu, row0 - C + 16 * w, row_end, l);
+      store_row_pieces<D>(done_v, dVu, row0 - C + 16 * w, row_end, l);
+    }
     __syncthreads();
 
+    // d*[nt][v] = result[row 16w + r][feature 16 nt + 4 q4 + v]
     f32x4 dq[Cfg::DT], dk[Cfg::DT], dv[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) {
@@ -330,36 +277,37 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
       __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
-        dq[nt] = mma16(gf, srow[nt], dq[nt]);   // dO S^T  (over d_value)
-        dk[nt] = mma16(vf, grow[nt], dk[nt]);   // V G^T   (over d_value)
-        dv[nt] = mma16(kf, gcol[nt], dv[nt]);   // Kh G    (over d_key)
+        dq[nt] = mma16(srow[nt], gf, dq[nt]);   // S dO^T   (over d_value)
+        dk[nt] = mma16(grow[nt], vf, dk[nt]);   // G V^T    (over d_value)
+        dv[nt] = mma16(gcol[nt], kf, dv[nt]);   // G^T k^T  (over d_key)
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    // every tile row is private to its wave here: stage the results in place
-    normalise_backward_rows<D>(dq, Qs, Gs, rq, scale, r_clamped, w, r, q4);
-    normalise_backward_rows<D>(dk, Ks, Ks, rk, scale, r_clamped, w, r, q4);
-#pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        Vs[(16 * w + 4 * q4 + v) * PITCH + 16 * nt + r] = f32_to_bf16(scale * dv[nt][v]);
-    wave_lds_sync();
-    constexpr int PIECES = 16 * D / 8;
-#pragma unroll
-    for (int i = l; i < PIECES; i += 64) {
-      const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-      const int row = row0 + 16 * w + lr;
-      if (row < row_end) {
-        const size_t goff = ubase + size_t(row) * D + col;
-        const int loff = (16 * w + lr) * PITCH + col;
-        *reinterpret_cast<uint4*>(dQ + goff) = *reinterpret_cast<const uint4*>(Gs + loff);
-        *reinterpret_cast<uint4*>(dK + goff) = *reinterpret_cast<const uint4*>(Ks + loff);
-        *reinterpret_cast<uint4*>(dV + goff) = *reinterpret_cast<const uint4*>(Vs + loff);
-      }
-    }
+    // every tile row is private to its wave here: chain rule on the raw rows, then the
+    // results are staged in place (dO rows for dQ, K rows for dK, V rows for dV)
+    const float ri = rq[16 * w + r], rj = rk[16 * w + r];
+    project_out_row<D, false>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
+    project_out_row<D, false>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
+    wave_lds_sync();  // own rows of Gs, Ks, Vs were read before the staging writes
+    gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, l, done_q);
+    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, l, done_k);
+    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, l, done_v);
     __syncthreads();
   }
+  if (row_begin < row_end) {
+    const int last = row_begin + (row_end - row_begin - 1) / C * C;
+    store_row_pieces<D>(done_q, dQu, last + 16 * w, row_end, l);
+    store_row_pieces<D>(done_k, dKu, last + 16 * w, row_end, l);
+    store_row_pieces<D>(done_v, dVu, last + 16 * w, row_end, l);
+  }
+}
+
+SegmentTotalsArgs totals_args(const CausalArgs& a, const void* X, const void* Y, float* dst) {
+  SegmentTotalsArgs t{};
+  t.X = X; t.Y = Y; t.dst = dst;
+  t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G;
+  t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
+  return t;
 }
 
 template <int D>
@@ -367,19 +315,19 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
   constexpr int C = 64;
   using Cfg = BiCfg<D, C>;
   const int units = a.B * a.H;
-  const bf16_t* Q = static_cast<const bf16_t*>(a.Q);
-  const bf16_t* K = static_cast<const bf16_t*>(a.K);
-  const bf16_t* V = static_cast<const bf16_t*>(a.V);
   float* totals = static_cast<float*>(a.workspace);
-  hipError_t err = launch_kernel("bidir_totals_bf16", bidir_totals_bf16<D, C>, dim3(units * a.G, 1),
-                                 dim3(Cfg::NT), 0, a.stream, K, V, K, V, totals, size_t(0), a.N, a.G,
-                                 a.seg_rows, a.eps);
+  hipError_t err = launch_segment_totals_bf16(totals_args(a, a.K, a.V, totals));
   if (err != hipSuccess) return err;
-  err = launch_bidir_combine(totals, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
-  if (err != hipSuccess) return err;
+  // few segments: the apply workgroups add the totals up themselves (and write `state`)
+  const bool sum_in_apply = a.G <= kMaxSegmentsSummedInScan;
+  if (!sum_in_apply) {
+    err = launch_bidir_combine(totals, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
+    if (err != hipSuccess) return err;
+  }
   return launch_kernel("fwd_bidir_apply_bf16", fwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, Q, a.s, static_cast<bf16_t*>(a.O), totals, a.H,
-                       a.N, a.G, a.seg_rows, a.eps);
+                       dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q), a.s,
+                       static_cast<bf16_t*>(a.O), totals, a.G, sum_in_apply ? a.G : 1,
+                       sum_in_apply ? a.state : nullptr, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps);
 }
 
 template <int D>
@@ -387,25 +335,40 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
   constexpr int C = 64;
   using Cfg = BiCfg<D, C>;
   const int units = a.B * a.H;
-  const bf16_t* Q = static_cast<const bf16_t*>(a.Q);
-  const bf16_t* K = static_cast<const bf16_t*>(a.K);
-  const bf16_t* V = static_cast<const bf16_t*>(a.V);
-  const bf16_t* dO = static_cast<const bf16_t*>(a.dO);
   char* ws = static_cast<char*>(a.workspace);
-  float* totals = reinterpret_cast<float*>(ws);
+  float* s_totals = reinterpret_cast<float*>(ws);
   const size_t pair_stride = state_array_bytes(a.B, a.H, D, a.G) / sizeof(float);
+  float* g_totals = s_totals + pair_stride;
   float* ds_partial = reinterpret_cast<float*>(ws + 2 * state_array_bytes(a.B, a.H, D, a.G));
-  hipError_t err = launch_kernel("bidir_totals_bf16", bidir_totals_bf16<D, C>, dim3(units * a.G, 2),
-                                 dim3(Cfg::NT), 0, a.stream, K, V, Q, dO, totals, pair_stride, a.N,
-                                 a.G, a.seg_rows, a.eps);
-  if (err != hipSuccess) return err;
-  err = launch_bidir_combine(totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
-                             a.stream);
-  if (err != hipSuccess) return err;
+  const bool few = a.G <= kMaxSegmentsSummedInScan;
+  hipError_t err;
+  const float* s_src = s_totals;
+  int n_sum = 1, n_ds = 1;
+  if (few && a.saved_fwd_states != nullptr) {
+    // the forward left the segment totals of Kh^T V behind: only Qh^T dO is reduced here, and
+    // the same kernel forms the share <S, G_segment> of ds
+    SegmentTotalsArgs t = totals_args(a, a.Q, a.dO, g_totals);
+    t.dot_with = a.saved_fwd_states; t.dot_slots = a.G; t.dot_out = ds_partial;
+    err = launch_segment_totals_bf16(t);
+    if (err != hipSuccess) return err;
+    s_src = a.saved_fwd_states;
+    n_sum = a.G;
+    n_ds = a.G;
+  } else {
+    err = launch_segment_totals_bf16(totals_args(a, a.K, a.V, s_totals));
+    if (err != hipSuccess) return err;
+    err = launch_segment_totals_bf16(totals_args(a, a.Q, a.dO, g_totals));
+    if (err != hipSuccess) return err;
+    err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
+                               a.stream);
+    if (err != hipSuccess) return err;
+  }
   return launch_kernel("bwd_bidir_apply_bf16", bwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, Q, K, V, dO, a.s, static_cast<bf16_t*>(a.dQ),
-                       static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), totals, pair_stride,
-                       ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, a.eps);
+                       dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q),
+                       static_cast<const bf16_t*>(a.K), static_cast<const bf16_t*>(a.V),
+                       static_cast<const bf16_t*>(a.dO), a.s, static_cast<bf16_t*>(a.dQ),
+                       static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), s_src, g_totals, a.G,
+                       n_sum, ds_partial, n_ds, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps);
 }
 
 }  // namespace

@@ -60,16 +60,21 @@ struct FwdCfg {
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
 // grid = units * n_compute workgroups; segment g of a unit writes slot g of the unit's
-// n_slots slots (the causal forward computes all segments but the last).
+// n_slots slots (the causal forward computes all segments but the last).  The bidirectional
+// path uses it for Kh^T V and, with (K, V) := (Q, dO), for Qh^T dO; there, given the stored
+// segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
+// also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
 template <int D, int C>
 __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, float* __restrict__ seg_state,
-    int N, int n_slots, int n_compute, int seg_rows, float inv_eps) {
+    int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
+    const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
+  __shared__ float dot_wave[Cfg::NW];
 
   const int unit = blockIdx.x / n_compute, g = blockIdx.x % n_compute;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
@@ -130,6 +135,32 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
         for (int v = 0; v < 4; ++v)
           out[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] =
               acc[x][y][v];
+  }
+  if (dot_with != nullptr) {  // workgroup-uniform
+    float dot = 0.f;
+    if (ST::active(w)) {
+      const float* other = dot_with + size_t(unit) * dot_slots * D * D;
+#pragma unroll
+      for (int x = 0; x < ST::NCT; ++x)
+#pragma unroll
+        for (int y = 0; y < ST::NRT; ++y)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int e = (16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r;
+            float o = 0.f;
+            for (int j = 0; j < dot_slots; ++j) o += other[size_t(j) * D * D + e];
+            dot += acc[x][y][v] * o;
+          }
+    }
+    dot = group_sum<64>(dot);
+    if (l == 0) dot_wave[w] = dot;
+    __syncthreads();
+    if (tid == 0) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < Cfg::NW; ++i) t += dot_wave[i];
+      dot_out[size_t(unit) * n_slots + g] = t;
+    }
   }
 }
 
@@ -380,33 +411,43 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 }  // namespace
 
 template <int D>
-static hipError_t run_fwd_segment_totals(const CausalArgs& a, float* dst) {
-  const bf16_t* K = static_cast<const bf16_t*>(a.K);
-  const bf16_t* V = static_cast<const bf16_t*>(a.V);
-  const float inv_eps = 1.0f / a.eps;
+static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
+  const bf16_t* X = static_cast<const bf16_t*>(t.X);
+  const bf16_t* Y = static_cast<const bf16_t*>(t.Y);
+  const float inv_eps = 1.0f / t.eps;
   // The totals kernel takes the largest row tile that does not exceed the segment: with
   // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
   // paying one memory latency per 64-row chunk.
-  const dim3 grid(a.B * a.H * (a.G - 1));
+  const dim3 grid(t.units * t.n_compute);
   constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
-  if (a.seg_rows >= TOP)
+  if (t.seg_rows >= TOP)
     return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
-                         dim3(4 * TOP), 0, a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows,
-                         inv_eps);
-  if (a.seg_rows >= 128)
+                         dim3(4 * TOP), 0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows,
+                         inv_eps, t.dot_with, t.dot_slots, t.dot_out);
+  if (t.seg_rows >= 128)
     return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
-                         0, a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+                         0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
+                         t.dot_with, t.dot_slots, t.dot_out);
   return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256), 0,
-                       a.stream, K, V, dst, a.N, a.G, a.G - 1, a.seg_rows, inv_eps);
+                       t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
+                       t.dot_slots, t.dot_out);
+}
+
+hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t) {
+  switch (t.d) {
+    case 32: return run_segment_totals<32>(t);
+    case 64: return run_segment_totals<64>(t);
+    case 128: return run_segment_totals<128>(t);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst) {
-  switch (a.d) {
-    case 32: return run_fwd_segment_totals<32>(a, dst);
-    case 64: return run_fwd_segment_totals<64>(a, dst);
-    case 128: return run_fwd_segment_totals<128>(a, dst);
-    default: return hipErrorInvalidValue;
-  }
+  SegmentTotalsArgs t{};
+  t.X = a.K; t.Y = a.V; t.dst = dst;
+  t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G - 1;
+  t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
+  return launch_segment_totals_bf16(t);
 }
 
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {

@@ -56,6 +56,19 @@ hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int
 // bf16 segment totals of Kh^T V for all segments but the last, [units][G][d][d] fp32 in `dst`
 // (the first kernel of the causal forward, also used by a backward without saved states)
 hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
+
+// The same kernel in general: dst[unit][g] = sum over the rows of segment g of N(X)^T Y for
+// g < n_compute (G slots per unit).  With dot_with (stored totals of another d x d matrix,
+// dot_slots slots per unit, added up by the kernel) it also writes
+// dot_out[unit][g] = <dst[unit][g], that matrix>.
+struct SegmentTotalsArgs {
+  const void* X; const void* Y; float* dst;
+  int units, N, d, G, n_compute, seg_rows;
+  float eps;
+  const float* dot_with; int dot_slots; float* dot_out;
+  hipStream_t stream;
+};
+hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t);
 hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st);
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st);

@@ -229,4 +229,35 @@ __device__ __forceinline__ float sum_over_lane_rows(float x) {
   return x;
 }
 
+// Chain rule through the row normalisation on a wave's transposed 16 x D block:
+// acc[nt][v] = dxh[row r][column 16 nt + 4 q4 + v].  Reads the row from `x_rows` (the wave's
+// 16 rows of its LDS tile), which holds either the raw row x (NORMALISED = false) or
+// xh = r x (true); forms the dot product with dxh over the whole row (16 columns per lane,
+// then across the four lane rows) and replaces acc by dxh - xh (xh . dxh)  (no projection
+// for rows at or below eps).  Returns xh . dxh.
+template <int D, bool NORMALISED>
+__device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_rows, float rinv,
+                                                 float inv_eps, int r, int q4) {
+  constexpr int DT = D / 16, PITCH = lds_pitch(D);
+  float xv[DT][4];
+  float t = 0.f;
+#pragma unroll
+  for (int nt = 0; nt < DT; ++nt) {
+    const uint2 raw = *reinterpret_cast<const uint2*>(x_rows + r * PITCH + 16 * nt + 4 * q4);
+    xv[nt][0] = __builtin_bit_cast(float, raw.x << 16);
+    xv[nt][1] = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
+    xv[nt][2] = __builtin_bit_cast(float, raw.y << 16);
+    xv[nt][3] = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) t += xv[nt][v] * acc[nt][v];
+  }
+  t = sum_over_lane_rows(t);
+  const float c = (rinv == inv_eps) ? 0.f : (NORMALISED ? t : rinv * rinv * t);
+#pragma unroll
+  for (int nt = 0; nt < DT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[nt][v] -= xv[nt][v] * c;
+  return NORMALISED ? t : rinv * t;
+}
+
 }  // namespace cottn

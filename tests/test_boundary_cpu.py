@@ -26,7 +26,7 @@ def lib():
     l.cottn_fwd_causal.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_bwd_causal.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_fwd_bidir.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, f, vp]
-    l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, i, i, i, i, i, f, vp]
+    l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp]
     yield l
     l.cottn_tune_segments(0)
@@ -147,8 +147,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     lib.cottn_tune_segments(0)
     assert lib.cottn_fwd_bidir(p(), p(), None, p(), p(), None, p(), 1 << 15, 1, 1, 8, 64, BF16, eps, None) == E_NULL
     assert lib.cottn_fwd_bidir(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 64, BF16, eps, None) == E_WS
-    assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(), 16, 1, 1, 8, 64, BF16, eps, None) == E_WS
-    assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), p(), 1 << 15, 1, 1, 8, 96, BF16, eps, None) == E_SHAPE
+    assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 16, 1, 1, 8, 64, BF16, eps, None) == E_WS
+    assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 1 << 15, 1, 1, 8, 96, BF16, eps, None) == E_SHAPE
     step = lib.cottn_step
     assert step(p(), p(), p(), p(), None, p(), 1, 1, 64, BF16, eps, None) == E_NULL
     assert step(p(), p(), p(), p(), p(), p(), 1, 1, 100, BF16, eps, None) == E_SHAPE
