@@ -60,6 +60,9 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
     // (more segments shorten the serial chain but add totals to reduce and to add up)
     const long target = 384;
     want = (target + units - 1) / units;
+    // long serial chains (16 chunks or more per segment) are bound by the memory path, not by
+    // the prologue: there two workgroups on every compute unit measured best
+    if (n_chunks >= 16 * want) want = (512 + units - 1) / units;
   }
   if (want > n_chunks) want = n_chunks;
   if (want < 1) want = 1;

@@ -60,7 +60,9 @@ struct BwdCfg {
   static constexpr bool DQ_OWN_STAGE =
       LDS_BYTES + 2 * TILE <= 160 * 1024 && (160 * 1024) / (LDS_BYTES + 2 * TILE) == WG_PER_CU;
   static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
-  static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
+  // never budget registers for more than two waves per SIMD unless one workgroup alone needs
+  // it: spilling costs more than the second workgroup of a large chunk gains
+  static constexpr int WAVES_PER_EU = NW / 4 > 2 ? NW / 4 : (WAVES_RAW > 2 ? 2 : WAVES_RAW);
 };
 
 // pack a masked accumulator tile into half of an operand fragment

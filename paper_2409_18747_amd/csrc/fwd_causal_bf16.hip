@@ -54,7 +54,9 @@ struct FwdCfg {
   // waves per SIMD the register allocation is capped for (two workgroups per compute unit
   // when LDS allows, never more than the hardware needs for one workgroup)
   static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
-  static constexpr int WAVES_PER_EU = WAVES_RAW > 4 ? 4 : WAVES_RAW;
+  // never budget registers for more than two waves per SIMD unless one workgroup alone needs
+  // it: spilling costs more than the second workgroup of a large chunk gains
+  static constexpr int WAVES_PER_EU = NW / 4 > 2 ? NW / 4 : (WAVES_RAW > 2 ? 2 : WAVES_RAW);
 };
 
 // ---------------------------------------------------------------------------------------
