@@ -21,6 +21,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+
+def flop_rates(token_heads, d, chunk, seconds, bidirectional=False):
+    """Algorithmic flops of linear attention (14 d^2 per token-head for causal fwd+bwd, 12 d^2
+    bidirectional) and those a chunked MFMA design executes (14 (C + d) d; the bidirectional
+    path has no chunk-quadratic part), as rates and as fractions of the bf16 MFMA peak."""
+    alg = (12 if bidirectional else 14) * d * d * token_heads
+    exe = alg if bidirectional else 14 * (chunk + d) * d * token_heads
+    return {"algorithmic_TFLOPs": alg / seconds / 1e12, "executed_TFLOPs": exe / seconds / 1e12,
+            "executed_frac_of_mfma_peak": exe / seconds / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
 # Algorithmic HBM bytes per token-head (one row of one (batch, head)) for each kernel, in
 # units of d * element_size: the tensors the kernel must read plus those it must write.
@@ -92,7 +103,9 @@ def other_workloads(torch, cottn, workloads):
     ms = time_calls(torch, bidir, 100, 10)
     byt = 11 * B * H * N * d * 2
     out["cfg3_bidir_fwd_bwd"] = {"ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3),
-                                 "algorithmic_GBs": byt / ms / 1e6}
+                                 "algorithmic_GBs": byt / ms / 1e6,
+                                 "frac_of_hbm_peak": byt / ms / 1e6 / HBM_PEAK_GBS,
+                                 "flops": flop_rates(B * H * N, d, 64, ms * 1e-3, True)}
     del sets, ws, fwd_ws
 
     # long context causal forward + backward, N = 65536
@@ -115,6 +128,8 @@ def other_workloads(torch, cottn, workloads):
         byt = 11 * B * H * N * d * 2
         out["cfg4_long_context_chunk%d" % chunk] = {
             "ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3), "algorithmic_GBs": byt / ms / 1e6,
+            "frac_of_hbm_peak": byt / ms / 1e6 / HBM_PEAK_GBS,
+            "flops": flop_rates(B * H * N, d, chunk, ms * 1e-3),
             "segments": cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
             "workspace_bytes": ws.numel() + fwd_ws.numel()}
     return out
@@ -254,6 +269,7 @@ def main():
         "cpu_baseline": cpu,
         "step_hbm": {"algorithmic_bytes": step_bytes, "achieved_GBs": step_gbs,
                      "frac_of_peak": step_gbs / HBM_PEAK_GBS},
+        "step_flops": flop_rates(rows, d, args.chunk or 64, ms_per_step * 1e-3),
         "kernels": kernels,
     }
     if not args.no_other_workloads and not args.chunk and not args.segments:
