@@ -131,7 +131,8 @@ int cottn_step(const void* q, const void* k, const void* v, const float* s, floa
                void* o, int B, int H, int d, int dtype, float eps, void* hip_stream);
 
 /* Per-kernel timing for benchmarks.  After cottn_profile_start(), every kernel the library
- * launches is bracketed by two HIP events on its stream; cottn_profile_stop() waits for
+ * launches carries two HIP events of its own (attached to the dispatch, so they mark the
+ * kernel's begin and end, not the gaps between launches); cottn_profile_stop() waits for
  * those events, adds each kernel's elapsed time to a per-kernel-name total and stops
  * recording.  The three getters read the totals gathered by the last start/stop pair:
  * cottn_profile_count() distinct kernel names, and for 0 <= i < count its name (static
