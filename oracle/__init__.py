@@ -158,3 +158,20 @@ def bwd_rows(Q, K, V, s, dO, rows, eps=1e-6, causal=True):
     _load().oracle_bwd_rows(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q), ctypes.c_double(eps),
                             ctypes.c_int(1 if causal else 0), rp, n, _p(dQ), _p(dK), _p(dV))
     return dQ, dK, dV
+
+
+def scale_from_m(m, n):
+    """The paper's stabiliser (Sec. 3.3): the similarity is divided by n^sigma(m_h), with n the
+    sequence length and m_h a learned scalar per head, i.e. s_h = n^(-sigma(m_h))."""
+    m = _f64(m)
+    sig = 1.0 / (1.0 + np.exp(-m))
+    return np.power(float(n), -sig)
+
+
+def scale_backward(m, n, ds):
+    """dL/dm_h from dL/ds_h through s_h = n^(-sigma(m_h)):
+    ds_h/dm_h = -ln(n) sigma(m_h) (1 - sigma(m_h)) n^(-sigma(m_h))."""
+    m = _f64(m)
+    ds = _f64(ds)
+    sig = 1.0 / (1.0 + np.exp(-m))
+    return ds * (-np.log(float(n))) * sig * (1.0 - sig) * np.power(float(n), -sig)

@@ -333,3 +333,45 @@ def test_threads_do_not_change_results(oracle):
     for x, y in zip(a, b):
         np.testing.assert_array_equal(x, y)
     assert oracle.num_threads() >= 1
+
+
+# ---- the stabiliser of Sec. 3.3: s_h = n^(-sigma(m_h)) -------------------------------------
+def test_stabiliser_closed_forms(oracle):
+    # m = 0 gives sigma = 1/2, i.e. division by sqrt(n) (the paper initialises m at 0.5, between
+    # no scaling and division by n); n = 1 never scales; m -> +inf divides by n, -inf by 1
+    np.testing.assert_allclose(oracle.scale_from_m([0.0], 1024), [1.0 / 32.0], rtol=1e-15)
+    np.testing.assert_allclose(oracle.scale_from_m([-3.0, 0.5, 7.0], 1), [1.0, 1.0, 1.0], rtol=0)
+    np.testing.assert_allclose(oracle.scale_from_m([40.0], 512), [1.0 / 512.0], rtol=1e-12)
+    np.testing.assert_allclose(oracle.scale_from_m([-40.0], 512), [1.0], rtol=1e-12)
+    # the paper's initial value: sigma(0.5) = 0.62245933..., so s = n^-0.62245933...
+    np.testing.assert_allclose(oracle.scale_from_m([0.5], 100.0),
+                               [np.exp(-np.log(100.0) / (1.0 + np.exp(-0.5)))], rtol=1e-15)
+    # monotone: a larger m scales more strongly; a longer sequence scales more strongly
+    s = oracle.scale_from_m(np.linspace(-4, 4, 17), 300)
+    assert np.all(np.diff(s) < 0)
+    assert oracle.scale_from_m([0.3], 2000)[0] < oracle.scale_from_m([0.3], 200)[0]
+
+
+def test_stabiliser_gradient_finite_differences(oracle):
+    m = np.array([-1.3, 0.0, 0.5, 2.2])
+    ds = np.array([0.7, -1.1, 2.0, 0.3])
+    for n in (2, 77, 4096):
+        h = 1e-6
+        fd = (oracle.scale_from_m(m + h, n) - oracle.scale_from_m(m - h, n)) / (2 * h)
+        np.testing.assert_allclose(oracle.scale_backward(m, n, ds), ds * fd, rtol=1e-8, atol=1e-12)
+    np.testing.assert_array_equal(oracle.scale_backward(m, 1, ds), np.zeros(4))  # ln 1 = 0
+
+
+def test_stabiliser_through_attention(oracle):
+    # the whole chain: L = sum(dO * O(s(m))) differentiated with respect to m by central
+    # differences equals the oracle's ds pushed through scale_backward
+    Q, K, V, dO, _ = rand_inputs(60, 2, 3, 12, 4)
+    m = np.array([0.5, -0.8, 1.7])
+    n = Q.shape[2]
+    loss = lambda mm: float((dO * oracle.fwd_quadratic(Q, K, V, oracle.scale_from_m(mm, n))).sum())
+    ds = oracle.bwd_quadratic(Q, K, V, oracle.scale_from_m(m, n), dO)[3]
+    dm = oracle.scale_backward(m, n, ds)
+    for h_idx in range(3):
+        e = np.zeros(3); e[h_idx] = 1e-6
+        fd = (loss(m + e) - loss(m - e)) / 2e-6
+        np.testing.assert_allclose(dm[h_idx], fd, rtol=1e-6, atol=1e-9)
