@@ -130,6 +130,19 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
 int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
                void* o, int B, int H, int d, int dtype, float eps, void* hip_stream);
 
+/* The learned stabiliser of Sec. 3.3 (eq. cosine2): scores are divided by n^sigma(m_h), n the
+ * sequence length, m_h a learned scalar per head (the paper starts it at 0.5).  The entry
+ * points above take the factor itself; these map between the two.  m, s, ds, dm: float[H]
+ * device pointers; n >= 1.
+ *   cottn_scale_from_m:   s[h]  = n^(-sigma(m[h]))
+ *   cottn_scale_backward: dm[h] = ds[h] * ds_h/dm_h
+ *                               = ds[h] * (-ln n) sigma(m[h]) (1 - sigma(m[h])) n^(-sigma(m[h]))
+ * Outputs are overwritten.  Errors: COTTN_E_NULL, COTTN_E_SHAPE (H < 1), COTTN_E_ARG (n < 1 or
+ * not finite), COTTN_E_ALIGN (pointers not 4-byte aligned), COTTN_E_HIP. */
+int cottn_scale_from_m(const float* m, float* s, int H, float n, void* hip_stream);
+int cottn_scale_backward(const float* m, const float* ds, float* dm, int H, float n,
+                         void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  After cottn_profile_start(), every kernel the library
  * launches carries two HIP events of its own (attached to the dispatch, so they mark the
  * kernel's begin and end, not the gaps between launches); cottn_profile_stop() waits for

@@ -50,6 +50,10 @@ def _load():
                                     vp]
     lib.cottn_step.restype = i
     lib.cottn_step.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, f, vp]
+    lib.cottn_scale_from_m.restype = i
+    lib.cottn_scale_from_m.argtypes = [fp, fp, i, f, vp]
+    lib.cottn_scale_backward.restype = i
+    lib.cottn_scale_backward.argtypes = [fp, fp, fp, i, f, vp]
     lib.cottn_profile_start.restype = i
     lib.cottn_profile_stop.restype = i
     lib.cottn_profile_count.restype = i
@@ -197,6 +201,23 @@ def cottn_step(q, k, v, s, state, o=None, eps=1e-6, stream=None):
                         eps, _stream(stream))
     _check(st, "cottn_step")
     return o
+
+
+def cottn_scale_from_m(m, n, s=None, stream=None):
+    """s[h] = n^(-sigmoid(m[h])): the stabiliser of Sec. 3.3 as the factor the attention calls take."""
+    H = m.numel()
+    s = torch.empty(H, dtype=torch.float32, device=m.device) if s is None else s
+    _check(lib.cottn_scale_from_m(_ptr(m), _ptr(s), H, float(n), _stream(stream)), "cottn_scale_from_m")
+    return s
+
+
+def cottn_scale_backward(m, n, ds, dm=None, stream=None):
+    """dm[h] = ds[h] * ds_h/dm_h for s_h = n^(-sigmoid(m_h))."""
+    H = m.numel()
+    dm = torch.empty(H, dtype=torch.float32, device=m.device) if dm is None else dm
+    _check(lib.cottn_scale_backward(_ptr(m), _ptr(ds), _ptr(dm), H, float(n), _stream(stream)),
+           "cottn_scale_backward")
+    return dm
 
 
 def profile_start():

@@ -273,6 +273,23 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
   return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : bwd_bidir_f32(a));
 }
 
+int cottn_scale_from_m(const float* m, float* s, int H, float n, void* hip_stream) {
+  if (m == nullptr || s == nullptr) return COTTN_E_NULL;
+  if (H < 1) return COTTN_E_SHAPE;
+  if (!(n >= 1.0f) || !(n <= 3.0e38f)) return COTTN_E_ARG;
+  if (!is_aligned(m, 4) || !is_aligned(s, 4)) return COTTN_E_ALIGN;
+  return map_hip(launch_scale_from_m(m, s, H, n, static_cast<hipStream_t>(hip_stream)));
+}
+
+int cottn_scale_backward(const float* m, const float* ds, float* dm, int H, float n,
+                         void* hip_stream) {
+  if (m == nullptr || ds == nullptr || dm == nullptr) return COTTN_E_NULL;
+  if (H < 1) return COTTN_E_SHAPE;
+  if (!(n >= 1.0f) || !(n <= 3.0e38f)) return COTTN_E_ARG;
+  if (!is_aligned(m, 4) || !is_aligned(ds, 4) || !is_aligned(dm, 4)) return COTTN_E_ALIGN;
+  return map_hip(launch_scale_backward(m, ds, dm, H, n, static_cast<hipStream_t>(hip_stream)));
+}
+
 int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
                void* o, int B, int H, int d, int dtype, float eps, void* hip_stream) {
   const void* req[] = {q, k, v, s, state, o};

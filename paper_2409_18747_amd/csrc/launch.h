@@ -73,6 +73,11 @@ hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st);
 
+// the stabiliser map of Sec. 3.3 and its gradient (scale.hip)
+hipError_t launch_scale_from_m(const float* m, float* s, int H, float n, hipStream_t st);
+hipError_t launch_scale_backward(const float* m, const float* ds, float* dm, int H, float n,
+                                 hipStream_t st);
+
 // profiling hooks (api.hip): when profiling is on, hands out a fresh pair of events that the
 // launch attaches to the kernel itself, so they time the kernel's own begin and end.
 bool profile_on();
