@@ -92,6 +92,18 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
                      float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                      int d, int chunk, int dtype, float eps, void* hip_stream);
 
+/* The same for a sequence that continues an earlier one (a long prompt fed in pieces, Sec. 5:
+ * the hidden state carries everything the later tokens need from the earlier ones).
+ *   state_in: float[B][H][d][d] in, the state after the tokens before this piece (what an
+ *   earlier call left in `state`, or cottn_step's state); O_i = s qh_i (state_in + sum_{j<=i}
+ *   kh_j^T v_j) and `state` (may be NULL) receives state_in + the sum over this piece.
+ *   state_in and state must not be the same buffer (COTTN_E_ARG): workgroups read the one
+ *   while others write the other.  N = 0 copies state_in to state. */
+int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
+                                const float* state_in, void* O, float* state, void* workspace,
+                                size_t workspace_bytes, int B, int H, int N, int d, int chunk,
+                                int dtype, float eps, void* hip_stream);
+
 /* Causal backward (Sec. 4, gradient formulas; dK and dV use the cumulative sum that runs
  * backward in time).  Takes the raw Q, K, V of the forward call and dO = dL/dO; writes
  * dQ, dK, dV (same shape and dtype) and ds[H] = dL/ds (overwritten).

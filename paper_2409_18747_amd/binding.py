@@ -40,6 +40,9 @@ def _load():
     lib.cottn_status_string.argtypes = [i]
     lib.cottn_fwd_causal.restype = i
     lib.cottn_fwd_causal.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_fwd_causal_from_state.restype = i
+    lib.cottn_fwd_causal_from_state.argtypes = [vp, vp, vp, fp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f,
+                                                vp]
     lib.cottn_bwd_causal.restype = i
     lib.cottn_bwd_causal.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i, i, i,
                                      f, vp]
@@ -135,6 +138,22 @@ def cottn_fwd_causal(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, ep
     st = lib.cottn_fwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
                               _ptr(workspace), have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_fwd_causal")
+    return O
+
+
+def cottn_fwd_causal_from_state(Q, K, V, s, state_in, O=None, state=None, workspace=None, chunk=0,
+                                eps=1e-6, stream=None):
+    """cottn_fwd_causal for a piece of a longer sequence: starts from `state_in` (float32
+    [B, H, d, d]) and leaves the state after the piece in `state` (a different tensor)."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    if O is None:
+        O = torch.empty_like(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    st = lib.cottn_fwd_causal_from_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(state_in), _ptr(O),
+                                         _ptr(state), _ptr(workspace), have, B, H, N, d, chunk, dt,
+                                         eps, _stream(stream))
+    _check(st, "cottn_fwd_causal_from_state")
     return O
 
 

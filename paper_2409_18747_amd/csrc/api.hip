@@ -165,25 +165,60 @@ const char* cottn_status_string(int status) {
   }
 }
 
-int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s, void* O,
-                     float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
-                     int d, int chunk, int dtype, float eps, void* hip_stream) {
+namespace {
+
+__global__ void copy_f32(const float* __restrict__ src, float* __restrict__ dst, long n) {
+  const long i = long(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s,
+                   const float* state_in, void* O, float* state, void* workspace,
+                   size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                   float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, O};
   int st = check_common(req, 5, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
   if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
+  if (state_in != nullptr && !is_aligned(state_in, 16)) return COTTN_E_ALIGN;
+  if (state_in != nullptr && state_in == state) return COTTN_E_ARG;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
                        workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (N == 0) return map_hip(zero_f32(state, long(B) * H * d * d, stream));
+  if (N == 0) {
+    const long n = long(B) * H * d * d;
+    if (state == nullptr) return COTTN_OK;
+    if (state_in == nullptr) return map_hip(zero_f32(state, n, stream));
+    return map_hip(launch_kernel("copy_f32", copy_f32, dim3(unsigned((n + 255) / 256)), dim3(256), 0,
+                                 stream, state_in, state, n));
+  }
   CausalArgs a{};
-  a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.workspace = workspace;
+  a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.state_in = state_in;
+  a.workspace = workspace;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : fwd_causal_f32(a));
+}
+
+}  // namespace
+
+int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s, void* O,
+                     float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                     int d, int chunk, int dtype, float eps, void* hip_stream) {
+  return fwd_causal_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, d, chunk,
+                        dtype, eps, hip_stream);
+}
+
+int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
+                                const float* state_in, void* O, float* state, void* workspace,
+                                size_t workspace_bytes, int B, int H, int N, int d, int chunk,
+                                int dtype, float eps, void* hip_stream) {
+  if (state_in == nullptr) return COTTN_E_NULL;
+  return fwd_causal_any(Q, K, V, s, state_in, O, state, workspace, workspace_bytes, B, H, N, d,
+                        chunk, dtype, eps, hip_stream);
 }
 
 int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,

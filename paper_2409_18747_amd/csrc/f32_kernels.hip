@@ -128,6 +128,14 @@ __device__ __forceinline__ void state_load(float* M, const float* __restrict__ s
   constexpr int P = FCfg<D>::P;
   for (int e = threadIdx.x; e < D * D; e += NT) M[(e / D) * P + (e % D)] = src ? src[e] : 0.f;
 }
+// the same with a second (optional) matrix added: M = src + more
+template <int D>
+__device__ __forceinline__ void state_load2(float* M, const float* __restrict__ src,
+                                            const float* __restrict__ more) {
+  constexpr int P = FCfg<D>::P;
+  for (int e = threadIdx.x; e < D * D; e += NT)
+    M[(e / D) * P + (e % D)] = (src ? src[e] : 0.f) + (more ? more[e] : 0.f);
+}
 template <int D>
 __device__ __forceinline__ void state_store(float* __restrict__ dst, const float* M) {
   constexpr int P = FCfg<D>::P;
@@ -179,7 +187,8 @@ template <int D>
 __global__ __launch_bounds__(NT) void fwd_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ s, float* __restrict__ O, float* __restrict__ state_out,
-    const float* __restrict__ states, int H, int N, int G, int seg_rows, float eps, int causal) {
+    const float* __restrict__ states, const float* __restrict__ state_in, int H, int N, int G,
+    int seg_rows, float eps, int causal) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -197,7 +206,8 @@ __global__ __launch_bounds__(NT) void fwd_scan_f32(
   const float* init = nullptr;
   if (!causal) init = states + size_t(unit) * G * D * D;
   else if (states != nullptr && g > 0) init = states + (size_t(unit) * G + g) * D * D;
-  state_load<D>(S, init);
+  // the state the sequence starts from (causal only) is part of every segment's start state
+  state_load2<D>(S, init, state_in ? state_in + size_t(unit) * D * D : nullptr);
   for (int row0 = row_begin; row0 < row_end; row0 += CR) {
     __syncthreads();
     load_rows<D>(qs, Q + ubase, row0, row_end, true, eps, nullptr);
@@ -421,8 +431,9 @@ hipError_t run_fwd(const CausalArgs& a, bool causal) {
   }
   return launch_kernel("fwd_scan_f32", fwd_scan_f32<D>, dim3(units * a.G), dim3(NT), lds_fwd<D>(),
                        a.stream, Q, K, V, a.s, static_cast<float*>(a.O),
-                       causal ? a.state : nullptr, (!causal || a.G > 1) ? ws : nullptr, a.H, a.N,
-                       a.G, a.seg_rows, a.eps, causal ? 1 : 0);
+                       causal ? a.state : nullptr, (!causal || a.G > 1) ? ws : nullptr,
+                       causal ? a.state_in : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps,
+                       causal ? 1 : 0);
 }
 
 template <int D>

@@ -194,8 +194,8 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causal_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
-    const float* __restrict__ seg_states, int H, int N, int G, int seg_rows, float inv_eps,
-    int sum_totals) {
+    const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
+    int seg_rows, float inv_eps, int sum_totals) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -233,6 +233,17 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
+  // the state the sequence starts from (chunked prefill) belongs to every segment's start state
+  f32x4 start[ST::NCT][ST::NRT];
+  if (state_in != nullptr && ST::active(w)) {
+    const float* src = state_in + size_t(unit) * D * D;
+#pragma unroll
+    for (int x = 0; x < ST::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < ST::NRT; ++y)
+        start[x][y] = *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(w, x) + r) * D +
+                                                      16 * ST::row_tile(w, y) + 4 * q4);
+  }
   if (seg_states != nullptr && g > 0 && ST::active(w)) {
     const float* src = seg_states + size_t(unit) * G * D * D + (16 * ST::col_tile(w, 0) + r) * D +
                        16 * ST::row_tile(w, 0) + 4 * q4;
@@ -243,6 +254,15 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
               16 * (ST::col_tile(w, x) - ST::col_tile(w, 0)) * D +
               16 * (ST::row_tile(w, y) - ST::row_tile(w, 0)));
         });
+  }
+
+  if (state_in != nullptr && ST::active(w)) {
+#pragma unroll
+    for (int x = 0; x < ST::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < ST::NRT; ++y)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sacc[x][y][v] += start[x][y][v];
   }
 
   RowPieces<D> finished;  // output rows of the previous chunk, stored one chunk late
@@ -406,7 +426,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   }
   return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
-                       a.G > 1 ? ws : nullptr, a.H, a.N, a.G, a.seg_rows, inv_eps,
+                       a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0);
 }
 

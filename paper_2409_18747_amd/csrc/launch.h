@@ -14,6 +14,7 @@ struct CausalArgs {
   const void* Q; const void* K; const void* V; const float* s;
   const void* dO;                 // backward only
   void* O; float* state;          // forward only (state may be null)
+  const float* state_in;          // causal forward only: null, or the state the sequence starts from
   void* dQ; void* dK; void* dV; float* ds;  // backward only
   // backward only: null, or the segment states the forward call with the same split left in
   // its workspace (then the backward does not recompute them)

@@ -28,6 +28,7 @@ def lib():
     l.cottn_fwd_bidir.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp]
+    l.cottn_fwd_causal_from_state.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m.argtypes = [vp, vp, i, f, vp]
     l.cottn_scale_backward.argtypes = [vp, vp, vp, i, f, vp]
     yield l
@@ -44,7 +45,7 @@ def test_header_declares_the_entry_points():
     names = declared_functions()
     for required in ("cottn_fwd_causal", "cottn_bwd_causal", "cottn_fwd_bidir", "cottn_bwd_bidir",
                      "cottn_step", "cottn_workspace_bytes", "cottn_status_string",
-                     "cottn_scale_from_m", "cottn_scale_backward"):
+                     "cottn_scale_from_m", "cottn_scale_backward", "cottn_fwd_causal_from_state"):
         assert required in names
 
 
@@ -152,6 +153,12 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.cottn_fwd_bidir(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 64, BF16, eps, None) == E_WS
     assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 16, 1, 1, 8, 64, BF16, eps, None) == E_WS
     assert lib.cottn_bwd_bidir(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 1 << 15, 1, 1, 8, 96, BF16, eps, None) == E_SHAPE
+    cont = lib.cottn_fwd_causal_from_state
+    st_buf = p()
+    assert cont(p(), p(), p(), p(), None, p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
+    assert cont(p(), p(), p(), p(), p(4), p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ALIGN
+    assert cont(p(), p(), p(), p(), st_buf, p(), st_buf, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ARG
+    assert cont(p(), p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 48, 0, BF16, eps, None) == E_SHAPE
     assert lib.cottn_scale_from_m(p(), None, 4, 128.0, None) == E_NULL
     assert lib.cottn_scale_from_m(p(), p(), 0, 128.0, None) == E_SHAPE
     assert lib.cottn_scale_from_m(p(), p(), 4, 0.5, None) == E_ARG

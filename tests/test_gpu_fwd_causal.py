@@ -82,3 +82,79 @@ def test_bf16_zero_rows_and_determinism(cottn, oracle):
     ref = oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"])
     assert rel_err(to_host(O1), ref) <= TOL["bf16"]
     assert np.all(to_host(O1)[:, :, 10] == 0.0)
+
+
+@pytest.mark.parametrize("dtype,d,cuts,segments", [
+    ("bf16", 64, (0, 300, 301, 700, 1000), 0),
+    ("bf16", 64, (0, 517, 1100), 3),
+    ("bf16", 128, (0, 64, 330), 2),
+    ("bf16", 32, (0, 1, 200, 450), 0),
+    ("f32", 32, (0, 100, 260), 0),
+    ("f32", 64, (0, 33, 150), 3),
+])
+def test_sequence_fed_in_pieces(cottn, oracle, dtype, d, cuts, segments):
+    """A sequence fed piece by piece through cottn_fwd_causal_from_state gives the rows and the
+    final state of one pass over the whole sequence (Sec. 5: the state carries all the later
+    tokens need)."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    B, H, N = 2, 3, cuts[-1]
+    x = workloads.draw(B, H, N, d, dtype, 91, with_dO=False)
+    s = to_device(x["s"], "f32")
+    cottn.cottn_tune_segments(segments)
+    ref, S_ref = oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"])
+    state = torch.zeros(B, H, d, d, dtype=torch.float32, device="cuda")
+    outs = []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        Q, K, V = (to_device(x[k][:, :, a:b], dtype) for k in "QKV")
+        nxt = torch.full_like(state, float("nan"))
+        if a == 0:
+            O = cottn.cottn_fwd_causal(Q, K, V, s, state=nxt)
+        else:
+            O = cottn.cottn_fwd_causal_from_state(Q, K, V, s, state, state=nxt)
+        state = nxt
+        outs.append(to_host(O))
+    torch.cuda.synchronize()
+    got = np.concatenate(outs, axis=2)
+    e, es = rel_err(got, ref), rel_err(to_host(state), S_ref)
+    print("pieces %s d%d cuts %s: rel %.3e state %.3e" % (dtype, d, cuts, e, es), flush=True)
+    assert e <= TOL[dtype] and es <= TOL[dtype]
+
+
+def test_prefill_from_decode_state(cottn, oracle):
+    """The state of a few cottn_step calls continues into a multi-token piece."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    B, H, d, n_steps, N = 2, 2, 64, 5, 200
+    x = workloads.draw(B, H, n_steps + N, d, "bf16", 92, with_dO=False)
+    s = to_device(x["s"], "f32")
+    state = torch.zeros(B, H, d, d, dtype=torch.float32, device="cuda")
+    for t in range(n_steps):
+        q, k, v = (to_device(x[n][:, :, t], "bf16") for n in "QKV")
+        cottn.cottn_step(q, k, v, s, state)
+    Q, K, V = (to_device(x[n][:, :, n_steps:], "bf16") for n in "QKV")
+    O = cottn.cottn_fwd_causal_from_state(Q, K, V, s, state)
+    torch.cuda.synchronize()
+    ref, _ = oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"])
+    assert rel_err(to_host(O), ref[:, :, n_steps:]) <= TOL["bf16"]
+
+
+def test_empty_piece_copies_the_state(cottn):
+    """N = 0 through the C ABI itself (the tensor-based binding has no pointer for an empty
+    tensor): the state passes through unchanged."""
+    import ctypes
+    import torch
+    B, H, d = 2, 3, 64
+    dummy = torch.zeros(16, dtype=torch.bfloat16, device="cuda")
+    s = torch.ones(H, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    state_in = torch.randn(B, H, d, d, device="cuda", generator=g)
+    state = torch.full_like(state_in, float("nan"))
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    st = cottn.lib.cottn_fwd_causal_from_state(ptr(dummy), ptr(dummy), ptr(dummy), ptr(s), ptr(state_in),
+                                               ptr(dummy), ptr(state), None, 0, B, H, 0, d, 0,
+                                               cottn.COTTN_BF16, 1e-6,
+                                               ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    assert st == 0
+    assert torch.equal(state, state_in)
