@@ -42,37 +42,32 @@ struct BiCfg {
   static constexpr int STATE = D * PITCH;
 };
 
-// One workgroup per (batch, head): slot 0 of each pair <- sum over g of the slots; `state`
-// (may be null) receives pair 0; with n_pairs == 2, ds_partial[unit] = sum_e S[e] * G[e].
+// Slot 0 of each pair <- sum over g of the slots, one matrix element per thread (grid:
+// elems/256 workgroups per (batch, head)); `state` (may be null) receives pair 0; with
+// n_pairs == 2 every workgroup leaves sum_e S[e] * G[e] over its 256 elements in
+// ds_partial[unit][blockIdx.x], i.e. elems/256 partial sums per (batch, head).
 __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals, size_t pair_stride,
                                                      int n_pairs, int G, int elems,
                                                      float* __restrict__ state,
                                                      float* __restrict__ ds_partial) {
-  __shared__ float red[256];
-  const int unit = blockIdx.x;
+  __shared__ float red[4];
+  const int unit = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
   float* p0 = totals + size_t(unit) * G * elems;
   float* p1 = p0 + pair_stride;
-  float prod = 0.f;
-  for (int e = threadIdx.x; e < elems; e += 256) {
-    float a = 0.f;
-    for (int g = 0; g < G; ++g) a += p0[size_t(g) * elems + e];
-    p0[e] = a;
-    if (state != nullptr) state[size_t(unit) * elems + e] = a;
-    if (n_pairs == 2) {
-      float b = 0.f;
-      for (int g = 0; g < G; ++g) b += p1[size_t(g) * elems + e];
-      p1[e] = b;
-      prod += a * b;
-    }
-  }
+  float a = 0.f;
+  for (int g = 0; g < G; ++g) a += p0[size_t(g) * elems + e];
+  p0[e] = a;
+  if (state != nullptr) state[size_t(unit) * elems + e] = a;
   if (n_pairs == 2) {
-    red[threadIdx.x] = prod;
+    float b = 0.f;
+    for (int g = 0; g < G; ++g) b += p1[size_t(g) * elems + e];
+    p1[e] = b;
+    const float prod = group_sum<64>(a * b);
+    if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = prod;
     __syncthreads();
-    for (int stride = 128; stride > 0; stride >>= 1) {
-      if (int(threadIdx.x) < stride) red[threadIdx.x] += red[threadIdx.x + stride];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) ds_partial[unit] = red[0];
+    if (threadIdx.x == 0)
+      ds_partial[size_t(unit) * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
 
@@ -362,6 +357,7 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
     err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
                                a.stream);
     if (err != hipSuccess) return err;
+    n_ds = D * D / 256;  // the combine kernel's partial sums per (batch, head)
   }
   return launch_kernel("bwd_bidir_apply_bf16", bwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q),
@@ -375,8 +371,8 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
 
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st) {
-  return launch_kernel("bidir_combine", bidir_combine, dim3(units), dim3(256), 0, st, totals,
-                       pair_stride, n_pairs, G, elems, state, ds_partial);
+  return launch_kernel("bidir_combine", bidir_combine, dim3(elems / 256, units), dim3(256), 0, st,
+                       totals, pair_stride, n_pairs, G, elems, state, ds_partial);
 }
 
 hipError_t fwd_bidir_bf16(const CausalArgs& a) {

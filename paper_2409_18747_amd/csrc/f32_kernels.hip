@@ -473,8 +473,8 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
                       static_cast<float*>(a.dV), st1, a.H, a.N, a.G, a.seg_rows, a.eps,
                       causal ? 1 : 0);
   if (err != hipSuccess) return err;
-  // causal: partials per (unit, segment); bidirectional: one share per unit from the combine
-  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : 1, a.stream);
+  // causal: partials per (unit, segment); bidirectional: d*d/256 per unit from the combine
+  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : D * D / 256, a.stream);
 }
 
 template <class F>

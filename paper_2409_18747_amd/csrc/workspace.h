@@ -23,8 +23,9 @@ inline size_t round_up_256(size_t x) { return (x + 255) & ~size_t(255); }
 //                            the reverse-time states; always: [units][G] partial sums of ds
 //   bidirectional forward : [units][G][d][d]   segment totals, slot 0 becomes the full state
 //   bidirectional backward: [units][G][2][d][d] totals of Kh^T V and Qh^T dO, slot 0 becomes
-//                            the full pair when the combine kernel runs; [units][G] partial
-//                            sums of ds
+//                            the full pair when the combine kernel runs; per unit max(G,
+//                            d*d/256) partial sums of ds (the totals kernel leaves G, the
+//                            combine kernel d*d/256)
 inline size_t state_array_bytes(int B, int H, int d, int G) {
   return round_up_256(size_t(B) * H * G * d * d * sizeof(float));
 }
@@ -37,7 +38,8 @@ inline size_t workspace_bytes_for(int op, int B, int H, int d, const SeqPlan& p)
     case 0: return p.G > 1 ? state_array_bytes(B, H, d, p.G) : 0;
     case 1: return (p.G > 1 ? 2 * state_array_bytes(B, H, d, p.G) : 0) + ds_partials_bytes(B, H, p.G);
     case 2: return state_array_bytes(B, H, d, p.G);
-    case 3: return 2 * state_array_bytes(B, H, d, p.G) + ds_partials_bytes(B, H, p.G);
+    case 3: return 2 * state_array_bytes(B, H, d, p.G) +
+                   ds_partials_bytes(B, H, p.G > d * d / 256 ? p.G : d * d / 256);
     default: return 0;
   }
 }
