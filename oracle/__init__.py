@@ -175,3 +175,53 @@ def scale_backward(m, n, ds):
     ds = _f64(ds)
     sig = 1.0 / (1.0 + np.exp(-m))
     return ds * (-np.log(float(n))) * sig * (1.0 - sig) * np.power(float(n), -sig)
+
+
+# ---- padded batches ---------------------------------------------------------------------------
+# Sequences of different lengths share one [B, H, N, d] tensor; rows at or beyond seq_len[b]
+# do not exist (Sec. 4: padding is masked by zeroing rows).  The oracle simply runs each
+# sequence on its own rows; rows that do not exist are zero in every output.  s is [B, H]
+# (the stabiliser of Sec. 3.3 depends on each sequence's own length) and so is ds.
+
+
+def fwd_varlen(Q, K, V, s, seq_len, eps=1e-6, causal=True):
+    """Returns (O, state): O zero on rows that do not exist; state [B, H, d, d] over the rows that do."""
+    Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
+    B, H, N, d = Q.shape
+    O = np.zeros_like(Q)
+    S = np.zeros((B, H, d, d))
+    for b in range(B):
+        n = int(min(N, max(0, seq_len[b])))
+        if n == 0:
+            continue
+        sl = (slice(b, b + 1), slice(None), slice(0, n))
+        O[sl] = fwd_quadratic(Q[sl], K[sl], V[sl], s[b], eps=eps, causal=causal)
+        S[b] = state_total(K[sl], V[sl], eps=eps)[0]
+    return O, S
+
+
+def bwd_varlen(Q, K, V, s, dO, seq_len, eps=1e-6, causal=True):
+    """Returns (dQ, dK, dV, ds) with ds [B, H]; gradients are zero on rows that do not exist."""
+    Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
+    B, H, N, d = Q.shape
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(Q)
+    ds = np.zeros((B, H))
+    for b in range(B):
+        n = int(min(N, max(0, seq_len[b])))
+        if n == 0:
+            continue
+        sl = (slice(b, b + 1), slice(None), slice(0, n))
+        dQ[sl], dK[sl], dV[sl], ds[b] = bwd_quadratic(Q[sl], K[sl], V[sl], s[b], dO[sl], eps=eps,
+                                                      causal=causal)
+    return dQ, dK, dV, ds
+
+
+def scale_from_m_varlen(m, seq_len):
+    """s[b, h] = max(seq_len[b], 1)^(-sigma(m[h]))."""
+    return np.stack([scale_from_m(m, max(int(n), 1)) for n in seq_len])
+
+
+def scale_backward_varlen(m, seq_len, ds):
+    """dm[h] = sum over b of ds[b, h] * d s[b, h] / d m[h]."""
+    ds = _f64(ds)
+    return sum(scale_backward(m, max(int(n), 1), ds[b]) for b, n in enumerate(seq_len))

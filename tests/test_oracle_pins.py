@@ -375,3 +375,82 @@ def test_stabiliser_through_attention(oracle):
         e = np.zeros(3); e[h_idx] = 1e-6
         fd = (loss(m + e) - loss(m - e)) / 2e-6
         np.testing.assert_allclose(dm[h_idx], fd, rtol=1e-6, atol=1e-9)
+
+
+# ---- padded batches (rows at or beyond seq_len[b] do not exist) ----------------------------
+def test_padded_batch_reduces_to_fixed_length(oracle):
+    Q, K, V, dO, s = rand_inputs(70, 3, 2, 10, 4)
+    sb = np.tile(s, (3, 1))
+    for causal in (True, False):
+        O, S = oracle.fwd_varlen(Q, K, V, sb, [10, 10, 10], causal=causal)
+        np.testing.assert_allclose(O, oracle.fwd_quadratic(Q, K, V, s, causal=causal), atol=1e-13)
+        np.testing.assert_allclose(S, oracle.state_total(K, V), atol=1e-13)
+        g = oracle.bwd_varlen(Q, K, V, sb, dO, [10, 10, 10], causal=causal)
+        ref = oracle.bwd_quadratic(Q, K, V, s, dO, causal=causal)
+        for a, b in zip(g[:3], ref[:3]):
+            np.testing.assert_allclose(a, b, atol=1e-12)
+        np.testing.assert_allclose(g[3].sum(0), ref[3], atol=1e-12)  # ds[b][h] summed over b
+
+
+def test_padded_batch_equals_zeroed_rows(oracle):
+    # Sec. 4: "masking" a bidirectional sequence is zeroing its padded rows: with K, V zeroed
+    # there the rows that exist see exactly the shorter sequence, whatever Q holds in the padding
+    Q, K, V, dO, s = rand_inputs(71, 2, 3, 12, 4)
+    lens = [7, 12]
+    sb = np.stack([s, s * 1.3])
+    O, _ = oracle.fwd_varlen(Q, K, V, sb, lens, causal=False)
+    Kz, Vz = K.copy(), V.copy()
+    Kz[0, :, 7:] = 0.0
+    Vz[0, :, 7:] = 0.0
+    for b in range(2):
+        ref = oracle.fwd_quadratic(Q[b:b + 1], Kz[b:b + 1], Vz[b:b + 1], sb[b], causal=False)
+        np.testing.assert_allclose(O[b, :, :lens[b]], ref[0, :, :lens[b]], atol=1e-13)
+    assert np.all(O[0, :, 7:] == 0.0)
+    # causal: rows that exist never see later rows, so garbage in the padding changes nothing
+    Qg, Kg, Vg = Q.copy(), K.copy(), V.copy()
+    for X in (Qg, Kg, Vg):
+        X[0, :, 7:] = 1e3
+    Oc, Sc = oracle.fwd_varlen(Q, K, V, sb, lens, causal=True)
+    Og, Sg = oracle.fwd_varlen(Qg, Kg, Vg, sb, lens, causal=True)
+    np.testing.assert_array_equal(Oc, Og)
+    np.testing.assert_array_equal(Sc, Sg)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_padded_batch_gradients_finite_differences(oracle, causal):
+    Q, K, V, dO, s = rand_inputs(72, 2, 2, 6, 3)
+    lens = [4, 6]
+    sb = np.stack([s, s * 0.7])
+    loss = lambda q, k, v, ss: float((dO * oracle.fwd_varlen(q, k, v, ss, lens, causal=causal)[0]).sum())
+    dQ, dK, dV, ds = oracle.bwd_varlen(Q, K, V, sb, dO, lens, causal=causal)
+    h = 1e-6
+    for (b, hd, i, c) in [(0, 0, 1, 2), (0, 1, 3, 0), (1, 0, 5, 1), (0, 1, 5, 1)]:  # last: padding
+        for X, dX, which in ((Q, dQ, 0), (K, dK, 1), (V, dV, 2)):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[b, hd, i, c] += h
+            Xm[b, hd, i, c] -= h
+            args = lambda Y: [Y if w == which else Z for w, Z in enumerate((Q, K, V))]
+            fd = (loss(*args(Xp), sb) - loss(*args(Xm), sb)) / (2 * h)
+            np.testing.assert_allclose(dX[b, hd, i, c], fd, rtol=1e-6, atol=1e-8)
+    for (b, hd) in [(0, 0), (1, 1)]:
+        sp, sm = sb.copy(), sb.copy()
+        sp[b, hd] += h
+        sm[b, hd] -= h
+        np.testing.assert_allclose(ds[b, hd], (loss(Q, K, V, sp) - loss(Q, K, V, sm)) / (2 * h),
+                                   rtol=1e-6, atol=1e-8)
+
+
+def test_padded_batch_stabiliser(oracle):
+    m = np.array([0.5, -1.0, 2.0])
+    lens = [1, 17, 0, 300]
+    s = oracle.scale_from_m_varlen(m, lens)
+    assert s.shape == (4, 3)
+    np.testing.assert_array_equal(s[0], np.ones(3))          # n = 1
+    np.testing.assert_array_equal(s[2], np.ones(3))          # an empty sequence counts as n = 1
+    np.testing.assert_allclose(s[3], oracle.scale_from_m(m, 300), rtol=0)
+    ds = np.arange(12, dtype=np.float64).reshape(4, 3) - 5.0
+    h = 1e-6
+    fd = np.array([((oracle.scale_from_m_varlen(m + h * e, lens) -
+                     oracle.scale_from_m_varlen(m - h * e, lens)) * ds).sum() / (2 * h)
+                   for e in np.eye(3)])
+    np.testing.assert_allclose(oracle.scale_backward_varlen(m, lens, ds), fd, rtol=1e-7)
