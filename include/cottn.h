@@ -136,6 +136,33 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
                     int H, int N, int d, int dtype, float eps, void* hip_stream);
 
+/* Padded batches: sequences of different lengths in one [B][H][N][d] tensor (Sec. 4 notes that
+ * padding is masked by zeroing rows).  seq_len: int[B] device pointer, 0 <= seq_len[b] <= N
+ * (values outside are clamped).  Rows at or beyond seq_len[b] do not exist: they are not read,
+ * take part in no sum, and those rows of O, dQ, dK, dV are written as zeros.  Because the
+ * stabiliser of Sec. 3.3 depends on each sequence's own length, the scale is one value per
+ * (batch, head) here: s is float[B][H] and ds is float[B][H].  Everything else (state,
+ * workspaces, fwd_workspace, errors) is as for the functions without the suffix;
+ * cottn_workspace_bytes is the same. */
+int cottn_fwd_causal_varlen(const void* Q, const void* K, const void* V, const float* s,
+                            const int* seq_len, void* O, float* state, void* workspace,
+                            size_t workspace_bytes, int B, int H, int N, int d, int chunk,
+                            int dtype, float eps, void* hip_stream);
+int cottn_bwd_causal_varlen(const void* Q, const void* K, const void* V, const float* s,
+                            const int* seq_len, const void* dO, void* dQ, void* dK, void* dV,
+                            float* ds, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                            void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                            int chunk, int dtype, float eps, void* hip_stream);
+int cottn_fwd_bidir_varlen(const void* Q, const void* K, const void* V, const float* s,
+                           const int* seq_len, void* O, float* state, void* workspace,
+                           size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                           void* hip_stream);
+int cottn_bwd_bidir_varlen(const void* Q, const void* K, const void* V, const float* s,
+                           const int* seq_len, const void* dO, void* dQ, void* dK, void* dV,
+                           float* ds, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                           void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                           int dtype, float eps, void* hip_stream);
+
 /* One recurrent decode step for B*H independent states (Sec. 5, eq. hidden_state_obs):
  *   state[b][h] += kh^T v  (in place), then  o[b][h] = s_h * qh state[b][h]
  * (the state is read AFTER the update).  q, k, v, o are [B][H][d] in `dtype`. */
@@ -154,6 +181,12 @@ int cottn_step(const void* q, const void* k, const void* v, const float* s, floa
 int cottn_scale_from_m(const float* m, float* s, int H, float n, void* hip_stream);
 int cottn_scale_backward(const float* m, const float* ds, float* dm, int H, float n,
                          void* hip_stream);
+/* The same for a padded batch: n is each sequence's own length (a length below 1 counts as 1).
+ *   s[b][h] = seq_len[b]^(-sigma(m[h]));   dm[h] = sum over b of ds[b][h] * ds_bh/dm_h. */
+int cottn_scale_from_m_varlen(const float* m, const int* seq_len, float* s, int B, int H,
+                              void* hip_stream);
+int cottn_scale_backward_varlen(const float* m, const int* seq_len, const float* ds, float* dm,
+                                int B, int H, void* hip_stream);
 
 /* Per-kernel timing for benchmarks.  After cottn_profile_start(), every kernel the library
  * launches carries two HIP events of its own (attached to the dispatch, so they mark the

@@ -51,6 +51,21 @@ def _load():
     lib.cottn_bwd_bidir.restype = i
     lib.cottn_bwd_bidir.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i, i, f,
                                     vp]
+    ip = ctypes.c_void_p
+    lib.cottn_fwd_causal_varlen.restype = i
+    lib.cottn_fwd_causal_varlen.argtypes = [vp, vp, vp, fp, ip, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_causal_varlen.restype = i
+    lib.cottn_bwd_causal_varlen.argtypes = [vp, vp, vp, fp, ip, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i,
+                                            i, i, i, i, f, vp]
+    lib.cottn_fwd_bidir_varlen.restype = i
+    lib.cottn_fwd_bidir_varlen.argtypes = [vp, vp, vp, fp, ip, vp, fp, vp, sz, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_bidir_varlen.restype = i
+    lib.cottn_bwd_bidir_varlen.argtypes = [vp, vp, vp, fp, ip, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i,
+                                           i, i, i, f, vp]
+    lib.cottn_scale_from_m_varlen.restype = i
+    lib.cottn_scale_from_m_varlen.argtypes = [fp, ip, fp, i, i, vp]
+    lib.cottn_scale_backward_varlen.restype = i
+    lib.cottn_scale_backward_varlen.argtypes = [fp, ip, fp, fp, i, i, vp]
     lib.cottn_step.restype = i
     lib.cottn_step.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, f, vp]
     lib.cottn_scale_from_m.restype = i
@@ -208,6 +223,103 @@ def cottn_bwd_bidir(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspac
                              have, B, H, N, d, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_bidir")
     return dQ, dK, dV, ds
+
+
+def _check_lengths(seq_len, B):
+    if seq_len.dtype != torch.int32 or seq_len.numel() != B:
+        raise TypeError("seq_len must be an int32 tensor of B elements")
+
+
+def cottn_fwd_causal_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=None, chunk=0,
+                            eps=1e-6, stream=None):
+    """cottn_fwd_causal for a padded batch: seq_len int32 [B], s float32 [B, H]."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    _check_lengths(seq_len, B)
+    if O is None:
+        O = torch.empty_like(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    st = lib.cottn_fwd_causal_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(O),
+                                     _ptr(state), _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
+                                     _stream(stream))
+    _check(st, "cottn_fwd_causal_varlen")
+    return O
+
+
+def cottn_bwd_causal_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, ds=None,
+                            workspace=None, chunk=0, eps=1e-6, stream=None, fwd_workspace=None):
+    """cottn_bwd_causal for a padded batch; returns (dQ, dK, dV, ds) with ds float32 [B, H]."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    _check_lengths(seq_len, B)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(B, H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    st = lib.cottn_bwd_causal_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(dO),
+                                     _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
+                                     fwd_have, _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
+                                     _stream(stream))
+    _check(st, "cottn_bwd_causal_varlen")
+    return dQ, dK, dV, ds
+
+
+def cottn_fwd_bidir_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=None, eps=1e-6,
+                           stream=None):
+    """cottn_fwd_bidir for a padded batch: seq_len int32 [B], s float32 [B, H]."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    _check_lengths(seq_len, B)
+    if O is None:
+        O = torch.empty_like(Q)
+    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    st = lib.cottn_fwd_bidir_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(O),
+                                    _ptr(state), _ptr(workspace), have, B, H, N, d, dt, eps,
+                                    _stream(stream))
+    _check(st, "cottn_fwd_bidir_varlen")
+    return O
+
+
+def cottn_bwd_bidir_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, ds=None,
+                           workspace=None, eps=1e-6, stream=None, fwd_workspace=None):
+    """cottn_bwd_bidir for a padded batch; returns (dQ, dK, dV, ds) with ds float32 [B, H]."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    _check_lengths(seq_len, B)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(B, H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    st = lib.cottn_bwd_bidir_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(dO),
+                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
+                                    fwd_have, _ptr(workspace), have, B, H, N, d, dt, eps,
+                                    _stream(stream))
+    _check(st, "cottn_bwd_bidir_varlen")
+    return dQ, dK, dV, ds
+
+
+def cottn_scale_from_m_varlen(m, seq_len, s=None, stream=None):
+    """s[b, h] = seq_len[b]^(-sigmoid(m[h]))."""
+    B, H = seq_len.numel(), m.numel()
+    _check_lengths(seq_len, B)
+    s = torch.empty(B, H, dtype=torch.float32, device=m.device) if s is None else s
+    _check(lib.cottn_scale_from_m_varlen(_ptr(m), _ptr(seq_len), _ptr(s), B, H, _stream(stream)),
+           "cottn_scale_from_m_varlen")
+    return s
+
+
+def cottn_scale_backward_varlen(m, seq_len, ds, dm=None, stream=None):
+    """dm[h] = sum_b ds[b, h] * d s[b, h] / d m[h]."""
+    B, H = seq_len.numel(), m.numel()
+    _check_lengths(seq_len, B)
+    dm = torch.empty(H, dtype=torch.float32, device=m.device) if dm is None else dm
+    _check(lib.cottn_scale_backward_varlen(_ptr(m), _ptr(seq_len), _ptr(ds), _ptr(dm), B, H,
+                                           _stream(stream)), "cottn_scale_backward_varlen")
+    return dm
 
 
 def cottn_step(q, k, v, s, state, o=None, eps=1e-6, stream=None):

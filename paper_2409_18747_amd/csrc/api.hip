@@ -172,7 +172,12 @@ __global__ void copy_f32(const float* __restrict__ src, float* __restrict__ dst,
   if (i < n) dst[i] = src[i];
 }
 
-int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s,
+// seq_len != null in the *_any functions: a padded batch, with s and ds per (batch, head)
+int check_lengths(const int* seq_len) {
+  return seq_len == nullptr || is_aligned(seq_len, 4) ? COTTN_OK : COTTN_E_ALIGN;
+}
+
+int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
                    const float* state_in, void* O, float* state, void* workspace,
                    size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
                    float eps, void* hip_stream) {
@@ -182,6 +187,7 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s,
   if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
   if (state_in != nullptr && !is_aligned(state_in, 16)) return COTTN_E_ALIGN;
   if (state_in != nullptr && state_in == state) return COTTN_E_ARG;
+  if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
@@ -197,7 +203,7 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s,
   }
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.state_in = state_in;
-  a.workspace = workspace;
+  a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : fwd_causal_f32(a));
@@ -208,8 +214,8 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s,
 int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s, void* O,
                      float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                      int d, int chunk, int dtype, float eps, void* hip_stream) {
-  return fwd_causal_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, d, chunk,
-                        dtype, eps, hip_stream);
+  return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, workspace, workspace_bytes, B, H, N,
+                        d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
@@ -217,27 +223,31 @@ int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, con
                                 size_t workspace_bytes, int B, int H, int N, int d, int chunk,
                                 int dtype, float eps, void* hip_stream) {
   if (state_in == nullptr) return COTTN_E_NULL;
-  return fwd_causal_any(Q, K, V, s, state_in, O, state, workspace, workspace_bytes, B, H, N, d,
-                        chunk, dtype, eps, hip_stream);
+  return fwd_causal_any(Q, K, V, s, nullptr, state_in, O, state, workspace, workspace_bytes, B, H, N,
+                        d, chunk, dtype, eps, hip_stream);
 }
 
-int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                     void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
-                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
-                     int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream) {
+namespace {
+
+int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
+                   const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                   const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                   size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                   float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
   int st = check_common(req, 9, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
+  if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_BWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
                        workspace_bytes_for(COTTN_OP_BWD_CAUSAL, B, H, d, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (N == 0) return map_hip(zero_f32(ds, H, stream));
+  if (N == 0) return map_hip(zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream));
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
-  a.workspace = workspace;
+  a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   // the forward's segment states are taken over only if the forward split the sequence as
@@ -255,13 +265,14 @@ int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s
   return map_hip(dtype == COTTN_BF16 ? bwd_causal_bf16(a) : bwd_causal_f32(a));
 }
 
-int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
-                    float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
-                    int d, int dtype, float eps, void* hip_stream) {
+int fwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
+                  void* O, float* state, void* workspace, size_t workspace_bytes, int B, int H,
+                  int N, int d, int dtype, float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, O};
   int st = check_common(req, 5, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
   if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
+  if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
@@ -271,28 +282,31 @@ int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s,
   if (N == 0) return map_hip(zero_f32(state, long(B) * H * d * d, stream));
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.workspace = workspace;
+  a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   return map_hip(dtype == COTTN_BF16 ? fwd_bidir_bf16(a) : fwd_bidir_f32(a));
 }
 
-int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
-                    void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
-                    size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
-                    int H, int N, int d, int dtype, float eps, void* hip_stream) {
+int bwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
+                  const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                  const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                  size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                  void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
   int st = check_common(req, 9, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
+  if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_BWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
                        workspace_bytes_for(COTTN_OP_BWD_BIDIR, B, H, d, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (N == 0) return map_hip(zero_f32(ds, H, stream));
+  if (N == 0) return map_hip(zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream));
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
-  a.workspace = workspace;
+  a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   if (fwd_workspace != nullptr && dtype == COTTN_BF16 && plan.G <= kMaxSegmentsSummedInScan) {
@@ -306,6 +320,70 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
     }
   }
   return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : bwd_bidir_f32(a));
+}
+
+}  // namespace
+
+int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                     void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                     int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream) {
+  return bwd_causal_any(Q, K, V, s, nullptr, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+                        workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
+                    float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                    int d, int dtype, float eps, void* hip_stream) {
+  return fwd_bidir_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, d, dtype,
+                       eps, hip_stream);
+}
+
+int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s, const void* dO,
+                    void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
+                    size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
+                    int H, int N, int d, int dtype, float eps, void* hip_stream) {
+  return bwd_bidir_any(Q, K, V, s, nullptr, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+                       workspace, workspace_bytes, B, H, N, d, dtype, eps, hip_stream);
+}
+
+// ---- padded batches: seq_len[B] rows exist per sequence; s and ds are [B][H] -------------------
+int cottn_fwd_causal_varlen(const void* Q, const void* K, const void* V, const float* s,
+                            const int* seq_len, void* O, float* state, void* workspace,
+                            size_t workspace_bytes, int B, int H, int N, int d, int chunk,
+                            int dtype, float eps, void* hip_stream) {
+  if (seq_len == nullptr) return COTTN_E_NULL;
+  return fwd_causal_any(Q, K, V, s, seq_len, nullptr, O, state, workspace, workspace_bytes, B, H, N,
+                        d, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_bwd_causal_varlen(const void* Q, const void* K, const void* V, const float* s,
+                            const int* seq_len, const void* dO, void* dQ, void* dK, void* dV,
+                            float* ds, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                            void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                            int chunk, int dtype, float eps, void* hip_stream) {
+  if (seq_len == nullptr) return COTTN_E_NULL;
+  return bwd_causal_any(Q, K, V, s, seq_len, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+                        workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_fwd_bidir_varlen(const void* Q, const void* K, const void* V, const float* s,
+                           const int* seq_len, void* O, float* state, void* workspace,
+                           size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                           void* hip_stream) {
+  if (seq_len == nullptr) return COTTN_E_NULL;
+  return fwd_bidir_any(Q, K, V, s, seq_len, O, state, workspace, workspace_bytes, B, H, N, d, dtype,
+                       eps, hip_stream);
+}
+
+int cottn_bwd_bidir_varlen(const void* Q, const void* K, const void* V, const float* s,
+                           const int* seq_len, const void* dO, void* dQ, void* dK, void* dV,
+                           float* ds, const void* fwd_workspace, size_t fwd_workspace_bytes,
+                           void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                           int dtype, float eps, void* hip_stream) {
+  if (seq_len == nullptr) return COTTN_E_NULL;
+  return bwd_bidir_any(Q, K, V, s, seq_len, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+                       workspace, workspace_bytes, B, H, N, d, dtype, eps, hip_stream);
 }
 
 int cottn_scale_from_m(const float* m, float* s, int H, float n, void* hip_stream) {
@@ -323,6 +401,25 @@ int cottn_scale_backward(const float* m, const float* ds, float* dm, int H, floa
   if (!(n >= 1.0f) || !(n <= 3.0e38f)) return COTTN_E_ARG;
   if (!is_aligned(m, 4) || !is_aligned(ds, 4) || !is_aligned(dm, 4)) return COTTN_E_ALIGN;
   return map_hip(launch_scale_backward(m, ds, dm, H, n, static_cast<hipStream_t>(hip_stream)));
+}
+
+int cottn_scale_from_m_varlen(const float* m, const int* seq_len, float* s, int B, int H,
+                              void* hip_stream) {
+  if (m == nullptr || seq_len == nullptr || s == nullptr) return COTTN_E_NULL;
+  if (B < 1 || H < 1 || double(B) * H > 16777216.0) return COTTN_E_SHAPE;
+  if (!is_aligned(m, 4) || !is_aligned(seq_len, 4) || !is_aligned(s, 4)) return COTTN_E_ALIGN;
+  return map_hip(launch_scale_from_m_varlen(m, seq_len, s, B, H,
+                                            static_cast<hipStream_t>(hip_stream)));
+}
+
+int cottn_scale_backward_varlen(const float* m, const int* seq_len, const float* ds, float* dm,
+                                int B, int H, void* hip_stream) {
+  if (m == nullptr || seq_len == nullptr || ds == nullptr || dm == nullptr) return COTTN_E_NULL;
+  if (B < 1 || H < 1 || double(B) * H > 16777216.0) return COTTN_E_SHAPE;
+  if (!is_aligned(m, 4) || !is_aligned(seq_len, 4) || !is_aligned(ds, 4) || !is_aligned(dm, 4))
+    return COTTN_E_ALIGN;
+  return map_hip(launch_scale_backward_varlen(m, seq_len, ds, dm, B, H,
+                                              static_cast<hipStream_t>(hip_stream)));
 }
 
 int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,

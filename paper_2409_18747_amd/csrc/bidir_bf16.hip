@@ -99,7 +99,7 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
     const bf16_t* __restrict__ Q, const float* __restrict__ s, bf16_t* __restrict__ O,
     const float* __restrict__ totals, int slots, int n_sum, float* __restrict__ state, int H, int N,
-    int G, int seg_rows, float inv_eps) {
+    int G, int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
@@ -113,9 +113,10 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
   const size_t ubase = size_t(unit) * N * D;
   const bf16_t* Qu = Q + ubase;
   bf16_t* Ou = O + ubase;
-  const float scale = s[unit % H];
+  const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
   Stage qst;
   qst.fetch(Qu, row_begin, row_end);
@@ -163,6 +164,7 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
     store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
   }
+  if (seq_len != nullptr) zero_rows_bf16<D>(Ou, row_end, seg_end);  // rows that do not exist
 }
 
 // dQ, dK, dV rows of one segment; the first H workgroups also finish ds from the n_ds
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const float* __restrict__ s_totals,
     const float* __restrict__ g_totals, int slots, int n_sum, const float* __restrict__ ds_partial,
-    int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps) {
+    int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps,
+    const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
@@ -198,9 +201,10 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
   bf16_t* dQu = dQ + ubase;
   bf16_t* dKu = dK + ubase;
   bf16_t* dVu = dV + ubase;
-  const float scale = s[unit % H];
+  const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
   Stage qst, kst, vst, gst;
   qst.fetch(Qu, row_begin, row_end);
@@ -208,11 +212,13 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
   vst.fetch(Vu, row_begin, row_end);
   gst.fetch(Gu, row_begin, row_end);
 
-  if (int(blockIdx.x) < H && w == 0) {  // ds[h] = sum of the shares of all batches
+  // ds[h] = sum of the shares of all batches (ds[b][h], one batch, with a scale per unit)
+  if (int(blockIdx.x) < (s_per_unit ? B * H : H) && w == 0) {
     float t = 0.f;
-    const int n = B * n_ds;
+    const int n = s_per_unit ? n_ds : B * n_ds;
     for (int i = l; i < n; i += 64)
-      t += ds_partial[(size_t(i / n_ds) * H + blockIdx.x) * n_ds + (i % n_ds)];
+      t += s_per_unit ? ds_partial[size_t(blockIdx.x) * n_ds + i]
+                      : ds_partial[(size_t(i / n_ds) * H + blockIdx.x) * n_ds + (i % n_ds)];
     t = group_sum<64>(t);
     if (l == 0) ds[blockIdx.x] = t;
   }
@@ -295,6 +301,11 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
     store_row_pieces<D>(done_k, dKu, last + 16 * w, row_end, l);
     store_row_pieces<D>(done_v, dVu, last + 16 * w, row_end, l);
   }
+  if (seq_len != nullptr) {  // rows that do not exist
+    zero_rows_bf16<D>(dQu, row_end, seg_end);
+    zero_rows_bf16<D>(dKu, row_end, seg_end);
+    zero_rows_bf16<D>(dVu, row_end, seg_end);
+  }
 }
 
 SegmentTotalsArgs totals_args(const CausalArgs& a, const void* X, const void* Y, float* dst) {
@@ -302,6 +313,7 @@ SegmentTotalsArgs totals_args(const CausalArgs& a, const void* X, const void* Y,
   t.X = X; t.Y = Y; t.dst = dst;
   t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
+  t.seq_len = a.seq_len; t.H = a.H;
   return t;
 }
 
@@ -322,7 +334,8 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
   return launch_kernel("fwd_bidir_apply_bf16", fwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q), a.s,
                        static_cast<bf16_t*>(a.O), totals, a.G, sum_in_apply ? a.G : 1,
-                       sum_in_apply ? a.state : nullptr, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps);
+                       sum_in_apply ? a.state : nullptr, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
+                       a.seq_len, a.s_per_unit);
 }
 
 template <int D>
@@ -364,7 +377,8 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
                        static_cast<const bf16_t*>(a.K), static_cast<const bf16_t*>(a.V),
                        static_cast<const bf16_t*>(a.dO), a.s, static_cast<bf16_t*>(a.dQ),
                        static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), s_src, g_totals, a.G,
-                       n_sum, ds_partial, n_ds, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps);
+                       n_sum, ds_partial, n_ds, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
+                       a.seq_len, a.s_per_unit);
 }
 
 }  // namespace

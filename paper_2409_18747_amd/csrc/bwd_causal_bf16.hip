@@ -116,7 +116,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
     const float* __restrict__ fwd_states, float* __restrict__ rev_totals,
     float* __restrict__ ds_partial, int H, int N, int G, int seg_rows, float inv_eps,
-    int sum_totals) {
+    int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -142,9 +142,10 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   const bf16_t* Vu = V + ubase;
   const bf16_t* Gu = dO + ubase;
   bf16_t* dQu = dQ + ubase;
-  const float scale = s[unit % H];
+  const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
   // fwd_states holds the carried prefixes (slot g = state at the start of segment g) or, with
   // sum_totals set, the raw segment totals, which this workgroup then adds up itself
@@ -319,6 +320,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     store_row_pieces<D>(finished, dQu, last + 16 * w, row_end, l);
   }
 
+  if (seq_len != nullptr) zero_rows_bf16<D>(dQu, row_end, seg_end);  // rows that do not exist
+
   if (with_rev && AT::active(w)) {
     float* out = rev_totals + (size_t(unit) * G + g) * D * D;
 #pragma unroll
@@ -354,7 +357,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dK,
     bf16_t* __restrict__ dV, const float* __restrict__ rev_states,
     const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H, int N, int G,
-    int seg_rows, float inv_eps, int sum_totals) {
+    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -376,18 +379,21 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
   const bf16_t* Gu = dO + ubase;
   bf16_t* dKu = dK + ubase;
   bf16_t* dVu = dV + ubase;
-  const float scale = s[unit % H];
+  const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
   const int n_chunks = (row_end - row_begin + C - 1) / C;
 
   // the first H workgroups also finish ds: ds[h] = sum over batches and segments of the
-  // partial sums the dQ kernel left behind
-  if (int(blockIdx.x) < H && w == 0) {
+  // partial sums the dQ kernel left behind (with a scale per (batch, head): the first B*H
+  // workgroups, ds[b][h] = sum over the segments)
+  if (int(blockIdx.x) < (s_per_unit ? B * H : H) && w == 0) {
     float t = 0.f;
-    const int n = B * G;
+    const int n = s_per_unit ? G : B * G;
     for (int i = l; i < n; i += 64)
-      t += ds_partial[(size_t(i / G) * H + blockIdx.x) * G + (i % G)];
+      t += s_per_unit ? ds_partial[size_t(blockIdx.x) * G + i]
+                      : ds_partial[(size_t(i / G) * H + blockIdx.x) * G + (i % G)];
     t = group_sum<64>(t);
     if (l == 0) ds[blockIdx.x] = t;
   }
@@ -401,7 +407,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     for (int y = 0; y < AT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
   // the last chunk's rows and the stored states are all requested before anything waits
   Stage qst, kst, vst, gst;
-  {
+  if (n_chunks > 0) {  // (a segment of a padded batch can be empty)
     const int first = row_begin + (n_chunks - 1) * C;
     qst.fetch(Qu, first, row_end);
     kst.fetch(Ku, first, row_end);
@@ -567,19 +573,24 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     store_row_pieces<D>(done_k, dKu, row_begin + 16 * w, row_end, l);
     store_row_pieces<D>(done_v, dVu, row_begin + 16 * w, row_end, l);
   }
+  if (seq_len != nullptr) {  // rows that do not exist
+    zero_rows_bf16<D>(dKu, row_end, seg_end);
+    zero_rows_bf16<D>(dVu, row_end, seg_end);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
 // Kernel 5: ds[h] = sum over batches b and segments g of partial[(b H + h) G + g].
 __global__ __launch_bounds__(256) void bwd_reduce_ds(const float* __restrict__ partial,
-                                                     float* __restrict__ ds, int B, int H, int G) {
+                                                     float* __restrict__ ds, int B, int H, int G,
+                                                     int per_unit) {
   __shared__ float red[256];
-  const int h = blockIdx.x;
+  const int h = blockIdx.x;  // head, or (batch, head) with per_unit
   float acc = 0.f;
-  const long n = long(B) * G;
+  const long n = per_unit ? G : long(B) * G;
   for (long i = threadIdx.x; i < n; i += 256) {
     const long b = i / G, g = i % G;
-    acc += partial[(b * H + h) * G + g];
+    acc += per_unit ? partial[long(h) * G + i] : partial[(b * H + h) * G + g];
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -628,7 +639,7 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   // the dQ scan leaves the reverse-time segment totals (of qh^T dO) behind for the dK/dV scan
   err = launch_kernel("bwd_dq_scan_bf16", bwd_dq_scan_bf16<D, C>, grid, block, 0, a.stream, Q, K, V,
                       dO, a.s, static_cast<bf16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
-                      a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0);
+                      a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
   if (err != hipSuccess) return err;
   if (a.G > 1 && !sum_in_scan) {
     err = launch_bwd_state_carry(nullptr, rev_states, units, a.G, D * D, a.stream);
@@ -638,7 +649,7 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   return launch_kernel("bwd_dkdv_scan_bf16", bwd_dkdv_scan_bf16<D, C>, grid, block, 0, a.stream, Q,
                        K, V, dO, a.s, static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV),
                        rev_states, ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, inv_eps,
-                       sum_in_scan ? 1 : 0);
+                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
 }
 
 }  // namespace
@@ -650,9 +661,10 @@ hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int
                        dim3(256), 0, st, fwd_tot, rev_tot, G, elems, total);
 }
 
-hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st) {
-  return launch_kernel("bwd_reduce_ds", bwd_reduce_ds, dim3(H), dim3(256), 0, st, partial, ds, B, H,
-                       G);
+hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, int per_unit,
+                            hipStream_t st) {
+  return launch_kernel("bwd_reduce_ds", bwd_reduce_ds, dim3(per_unit ? B * H : H), dim3(256), 0, st,
+                       partial, ds, B, H, G, per_unit);
 }
 
 hipError_t bwd_causal_bf16(const CausalArgs& a) {

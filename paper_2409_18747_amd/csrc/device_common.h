@@ -131,6 +131,26 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Padded batches (sequences of different lengths in one [B][H][N][d] tensor): rows at or
+// beyond seq_len[batch] do not exist.  They are never read, contribute to no sum, and the
+// rows of every output tensor there are written as zeros.  Without lengths all N rows exist.
+__device__ __forceinline__ int valid_rows(const int* __restrict__ seq_len, int unit, int H, int N) {
+  return seq_len != nullptr ? min(N, max(0, seq_len[unit / H])) : N;
+}
+// The scale is one value per head, or, for padded batches whose stabiliser depends on each
+// sequence's own length (Sec. 3.3), one per (batch, head).
+__device__ __forceinline__ float unit_scale(const float* __restrict__ s, int unit, int H,
+                                            int per_unit) {
+  return s[per_unit ? unit : unit % H];
+}
+// Zeros rows row_lo..row_hi-1 of a [.][D] tensor of 2-byte elements (whole workgroup).
+template <int D>
+__device__ __forceinline__ void zero_rows_bf16(bf16_t* __restrict__ dst, int row_lo, int row_hi) {
+  const long pieces = long(max(0, row_hi - row_lo)) * (D / 8);
+  uint4* p = reinterpret_cast<uint4*>(dst + size_t(row_lo) * D);
+  for (long i = threadIdx.x; i < pieces; i += blockDim.x) p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
 // 1 / max(sqrt(sum_sq), eps)
 __device__ __forceinline__ float inv_norm(float sum_sq, float eps) {
   return 1.0f / fmaxf(sqrtf(sum_sq), eps);

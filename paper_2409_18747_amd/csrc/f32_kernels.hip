@@ -142,6 +142,14 @@ __device__ __forceinline__ void state_store(float* __restrict__ dst, const float
   for (int e = threadIdx.x; e < D * D; e += NT) dst[e] = M[(e / D) * P + (e % D)];
 }
 
+// zeros rows row_lo..row_hi-1 of a [.][D] fp32 tensor (rows of a padded batch that do not exist)
+template <int D>
+__device__ __forceinline__ void zero_rows_f32(float* __restrict__ dst, int row_lo, int row_hi) {
+  const long n4 = long(max(0, row_hi - row_lo)) * (D / 4);
+  float4* p = reinterpret_cast<float4*>(dst + size_t(row_lo) * D);
+  for (long i = threadIdx.x; i < n4; i += NT) p[i] = float4{0.f, 0.f, 0.f, 0.f};
+}
+
 // dynamic LDS carve-up helper
 struct Carver {
   float* p;
@@ -155,7 +163,7 @@ template <int D>
 __global__ __launch_bounds__(NT) void segment_totals_f32(
     const float* __restrict__ X0, const float* __restrict__ Y0, const float* __restrict__ X1,
     const float* __restrict__ Y1, float* __restrict__ totals, size_t pair_stride, int N, int G,
-    int seg_rows, float eps, int skip_mode) {
+    int seg_rows, float eps, int skip_mode, const int* __restrict__ seq_len, int H) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P;
   Carver cv{lds};
@@ -167,7 +175,8 @@ __global__ __launch_bounds__(NT) void segment_totals_f32(
   const size_t ubase = size_t(unit) * N * D;
   const float* X = (pair == 0 ? X0 : X1) + ubase;
   const float* Y = (pair == 0 ? Y0 : Y1) + ubase;
-  const int row_begin = g * seg_rows, row_end = min(N, row_begin + seg_rows);
+  const int row_begin = g * seg_rows;
+  const int row_end = min(valid_rows(seq_len, unit, H, N), row_begin + seg_rows);
   state_load<D>(M, nullptr);
   for (int row0 = row_begin; row0 < row_end; row0 += CR) {
     __syncthreads();
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(NT) void fwd_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ s, float* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ states, const float* __restrict__ state_in, int H, int N, int G,
-    int seg_rows, float eps, int causal) {
+    int seg_rows, float eps, int causal, const int* __restrict__ seq_len, int s_per_unit) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -199,8 +208,9 @@ __global__ __launch_bounds__(NT) void fwd_scan_f32(
   float* S = cv.take(D * P);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const size_t ubase = size_t(unit) * N * D;
-  const float scale = s[unit % H];
-  const int row_begin = g * seg_rows, row_end = min(N, row_begin + seg_rows);
+  const float scale = unit_scale(s, unit, H, s_per_unit);
+  const int row_begin = g * seg_rows, seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
   const int i = threadIdx.x / 8, c0 = (threadIdx.x % 8) * CPT;
   // causal: state at the segment start (slot g); bidirectional: the full total (slot 0)
   const float* init = nullptr;
@@ -233,6 +243,7 @@ __global__ __launch_bounds__(NT) void fwd_scan_f32(
       state_update<D>(S, ks, vs);
     }
   }
+  if (seq_len != nullptr) zero_rows_f32<D>(O + ubase, row_end, seg_end);
   if (causal && state_out != nullptr && g == G - 1) {
     __syncthreads();
     state_store<D>(state_out + size_t(unit) * D * D, S);
@@ -263,7 +274,7 @@ __global__ __launch_bounds__(NT) void bwd_dq_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ s, float* __restrict__ dQ,
     const float* __restrict__ states, float* __restrict__ ds_partial, int H, int N, int G,
-    int seg_rows, float eps, int causal) {
+    int seg_rows, float eps, int causal, const int* __restrict__ seq_len, int s_per_unit) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -277,8 +288,9 @@ __global__ __launch_bounds__(NT) void bwd_dq_scan_f32(
   float* red = cv.take(NT / 64);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const size_t ubase = size_t(unit) * N * D;
-  const float scale = s[unit % H], r_clamped = 1.0f / eps;
-  const int row_begin = g * seg_rows, row_end = min(N, row_begin + seg_rows);
+  const float scale = unit_scale(s, unit, H, s_per_unit), r_clamped = 1.0f / eps;
+  const int row_begin = g * seg_rows, seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
   const int i = threadIdx.x / 8, c0 = (threadIdx.x % 8) * CPT;
   const float* init = nullptr;
   if (!causal) init = states + size_t(unit) * G * D * D;
@@ -314,6 +326,7 @@ __global__ __launch_bounds__(NT) void bwd_dq_scan_f32(
       state_update<D>(S, ks, vs);
     }
   }
+  if (seq_len != nullptr) zero_rows_f32<D>(dQ + ubase, row_end, seg_end);
   if (ds_partial != nullptr) {
     ds_lane = group_sum<64>(ds_lane);
     __syncthreads();
@@ -332,7 +345,7 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ s, float* __restrict__ dK,
     float* __restrict__ dV, const float* __restrict__ states, int H, int N, int G, int seg_rows,
-    float eps, int causal) {
+    float eps, int causal, const int* __restrict__ seq_len, int s_per_unit) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -346,8 +359,9 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
   float* rk = cv.take(CR);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const size_t ubase = size_t(unit) * N * D;
-  const float scale = s[unit % H], r_clamped = 1.0f / eps;
-  const int row_begin = g * seg_rows, row_end = min(N, row_begin + seg_rows);
+  const float scale = unit_scale(s, unit, H, s_per_unit), r_clamped = 1.0f / eps;
+  const int row_begin = g * seg_rows, seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
   const int n_chunks = (row_end - row_begin + CR - 1) / CR;
   const int j = threadIdx.x / 8, c0 = (threadIdx.x % 8) * CPT;
   const float* init = nullptr;
@@ -392,6 +406,10 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
       state_update<D>(R, qs, gs);
     }
   }
+  if (seq_len != nullptr) {
+    zero_rows_f32<D>(dK + ubase, row_end, seg_end);
+    zero_rows_f32<D>(dV + ubase, row_end, seg_end);
+  }
 }
 
 template <int D> size_t lds_fwd() { return sizeof(float) * (3 * CR * FCfg<D>::P + CR * PP + D * FCfg<D>::P); }
@@ -423,7 +441,7 @@ hipError_t run_fwd(const CausalArgs& a, bool causal) {
   if (!causal || a.G > 1) {
     err = launch_kernel("segment_totals_f32", segment_totals_f32<D>, dim3(units * a.G, 1), dim3(NT),
                         lds_tot<D>(), a.stream, K, V, K, V, ws, size_t(0), a.N, a.G, a.seg_rows,
-                        a.eps, causal ? 1 : 0);
+                        a.eps, causal ? 1 : 0, a.seq_len, a.H);
     if (err != hipSuccess) return err;
     err = causal ? launch_fwd_state_carry(ws, units, a.G, D * D, a.stream)
                  : launch_bidir_combine(ws, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
@@ -433,7 +451,7 @@ hipError_t run_fwd(const CausalArgs& a, bool causal) {
                        a.stream, Q, K, V, a.s, static_cast<float*>(a.O),
                        causal ? a.state : nullptr, (!causal || a.G > 1) ? ws : nullptr,
                        causal ? a.state_in : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps,
-                       causal ? 1 : 0);
+                       causal ? 1 : 0, a.seq_len, a.s_per_unit);
 }
 
 template <int D>
@@ -456,7 +474,7 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
   if (have_states) {
     err = launch_kernel("segment_totals_f32", segment_totals_f32<D>, dim3(units * a.G, 2), dim3(NT),
                         lds_tot<D>(), a.stream, K, V, Q, dO, st0, arr / sizeof(float), a.N, a.G,
-                        a.seg_rows, a.eps, causal ? 1 : 0);
+                        a.seg_rows, a.eps, causal ? 1 : 0, a.seq_len, a.H);
     if (err != hipSuccess) return err;
     err = causal ? launch_bwd_state_carry(st0, st1, units, a.G, D * D, a.stream)
                  : launch_bidir_combine(st0, arr / sizeof(float), 2, units, a.G, D * D, nullptr,
@@ -466,15 +484,16 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
   err = launch_kernel("bwd_dq_scan_f32", bwd_dq_scan_f32<D>, dim3(units * a.G), dim3(NT),
                       lds_dq<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dQ), st0,
                       causal ? ds_partial : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps,
-                      causal ? 1 : 0);
+                      causal ? 1 : 0, a.seq_len, a.s_per_unit);
   if (err != hipSuccess) return err;
   err = launch_kernel("bwd_dkdv_scan_f32", bwd_dkdv_scan_f32<D>, dim3(units * a.G), dim3(NT),
                       lds_dkdv<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dK),
                       static_cast<float*>(a.dV), st1, a.H, a.N, a.G, a.seg_rows, a.eps,
-                      causal ? 1 : 0);
+                      causal ? 1 : 0, a.seq_len, a.s_per_unit);
   if (err != hipSuccess) return err;
   // causal: partials per (unit, segment); bidirectional: d*d/256 per unit from the combine
-  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : D * D / 256, a.stream);
+  return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : D * D / 256, a.s_per_unit,
+                          a.stream);
 }
 
 template <class F>

@@ -70,7 +70,8 @@ template <int D, int C>
 __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
-    const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out) {
+    const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out,
+    const int* __restrict__ seq_len, int H) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
   const bf16_t* Ku = K + size_t(unit) * N * D;
   const bf16_t* Vu = V + size_t(unit) * N * D;
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int row_end = min(valid_rows(seq_len, unit, H, N), row_begin + seg_rows);
 
   // acc[x][y] = S tile (key tile row_tile(y), value tile col_tile(x))
   f32x4 acc[ST::NCT][ST::NRT];
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
-    int seg_rows, float inv_eps, int sum_totals) {
+    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -215,9 +216,10 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   const bf16_t* Ku = K + ubase;
   const bf16_t* Vu = V + ubase;
   bf16_t* Ou = O + ubase;
-  const float scale = s[unit % H];
+  const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
-  const int row_end = min(N, row_begin + seg_rows);
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
   // running state in fp32 accumulators, seeded with the segment's prefix ([d_key][d_value])
   // seg_states holds either the carried prefixes (slot g = state at the start of segment g)
@@ -393,6 +395,8 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
     store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
   }
 
+  if (seq_len != nullptr) zero_rows_bf16<D>(Ou, row_end, seg_end);  // rows that do not exist
+
   if (state_out != nullptr && g == G - 1 && ST::active(w)) {
     float* out = state_out + size_t(unit) * D * D;
 #pragma unroll
@@ -427,7 +431,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
                        a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
-                       sum_in_scan ? 1 : 0);
+                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
 }
 
 }  // namespace
@@ -445,14 +449,14 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   if (t.seg_rows >= TOP)
     return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
                          dim3(4 * TOP), 0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows,
-                         inv_eps, t.dot_with, t.dot_slots, t.dot_out);
+                         inv_eps, t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
   if (t.seg_rows >= 128)
     return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
-                         t.dot_with, t.dot_slots, t.dot_out);
+                         t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
   return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256), 0,
                        t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
-                       t.dot_slots, t.dot_out);
+                       t.dot_slots, t.dot_out, t.seq_len, t.H);
 }
 
 hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t) {
@@ -469,6 +473,7 @@ hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst) {
   t.X = a.K; t.Y = a.V; t.dst = dst;
   t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G - 1;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
+  t.seq_len = a.seq_len; t.H = a.H;
   return launch_segment_totals_bf16(t);
 }
 

@@ -15,6 +15,9 @@ struct CausalArgs {
   const void* dO;                 // backward only
   void* O; float* state;          // forward only (state may be null)
   const float* state_in;          // causal forward only: null, or the state the sequence starts from
+  // padded batches: null, or int[B] row counts (then s and ds are [B][H], see s_per_unit)
+  const int* seq_len;
+  int s_per_unit;                 // s (and ds) indexed by (batch, head) instead of head
   void* dQ; void* dK; void* dV; float* ds;  // backward only
   // backward only: null, or the segment states the forward call with the same split left in
   // its workspace (then the backward does not recompute them)
@@ -67,10 +70,13 @@ struct SegmentTotalsArgs {
   int units, N, d, G, n_compute, seg_rows;
   float eps;
   const float* dot_with; int dot_slots; float* dot_out;
+  const int* seq_len; int H;  // padded batches: rows at or beyond seq_len[unit / H] do not exist
   hipStream_t stream;
 };
 hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t);
-hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G, hipStream_t st);
+// ds[h] = sum over batches b and j < n of partial[(b H + h) n + j]; per_unit: ds[b][h] instead
+hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int n, int per_unit,
+                            hipStream_t st);
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st);
 
@@ -78,6 +84,11 @@ hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, 
 hipError_t launch_scale_from_m(const float* m, float* s, int H, float n, hipStream_t st);
 hipError_t launch_scale_backward(const float* m, const float* ds, float* dm, int H, float n,
                                  hipStream_t st);
+
+hipError_t launch_scale_from_m_varlen(const float* m, const int* seq_len, float* s, int B, int H,
+                                      hipStream_t st);
+hipError_t launch_scale_backward_varlen(const float* m, const int* seq_len, const float* ds,
+                                        float* dm, int B, int H, hipStream_t st);
 
 // profiling hooks (api.hip): when profiling is on, hands out a fresh pair of events that the
 // launch attaches to the kernel itself, so they time the kernel's own begin and end.

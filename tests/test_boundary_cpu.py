@@ -29,6 +29,9 @@ def lib():
     l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp]
     l.cottn_fwd_causal_from_state.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
+    l.cottn_fwd_causal_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
+    l.cottn_bwd_bidir_varlen.argtypes = [vp] * 11 + [sz, vp, sz, i, i, i, i, i, f, vp]
+    l.cottn_scale_from_m_varlen.argtypes = [vp, vp, vp, i, i, vp]
     l.cottn_scale_from_m.argtypes = [vp, vp, i, f, vp]
     l.cottn_scale_backward.argtypes = [vp, vp, vp, i, f, vp]
     yield l
@@ -45,7 +48,10 @@ def test_header_declares_the_entry_points():
     names = declared_functions()
     for required in ("cottn_fwd_causal", "cottn_bwd_causal", "cottn_fwd_bidir", "cottn_bwd_bidir",
                      "cottn_step", "cottn_workspace_bytes", "cottn_status_string",
-                     "cottn_scale_from_m", "cottn_scale_backward", "cottn_fwd_causal_from_state"):
+                     "cottn_scale_from_m", "cottn_scale_backward", "cottn_fwd_causal_from_state",
+                     "cottn_fwd_causal_varlen", "cottn_bwd_causal_varlen", "cottn_fwd_bidir_varlen",
+                     "cottn_bwd_bidir_varlen", "cottn_scale_from_m_varlen",
+                     "cottn_scale_backward_varlen"):
         assert required in names
 
 
@@ -159,6 +165,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert cont(p(), p(), p(), p(), p(4), p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ALIGN
     assert cont(p(), p(), p(), p(), st_buf, p(), st_buf, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ARG
     assert cont(p(), p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 48, 0, BF16, eps, None) == E_SHAPE
+    vl = lib.cottn_fwd_causal_varlen
+    assert vl(p(), p(), p(), p(), None, p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
+    assert vl(p(), p(), p(), p(), p(2), p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ALIGN
+    assert vl(p(), p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 64, 0, 7, eps, None) == E_DTYPE
+    assert lib.cottn_bwd_bidir_varlen(p(), p(), p(), p(), None, p(), p(), p(), p(), p(), None, 0, p(), 1 << 15, 1, 1, 8, 64, BF16, eps, None) == E_NULL
+    assert lib.cottn_scale_from_m_varlen(p(), None, p(), 2, 4, None) == E_NULL
+    assert lib.cottn_scale_from_m_varlen(p(), p(), p(), 0, 4, None) == E_SHAPE
     assert lib.cottn_scale_from_m(p(), None, 4, 128.0, None) == E_NULL
     assert lib.cottn_scale_from_m(p(), p(), 0, 128.0, None) == E_SHAPE
     assert lib.cottn_scale_from_m(p(), p(), 4, 0.5, None) == E_ARG

@@ -1,0 +1,104 @@
+"""GPU parity: padded batches (the *_varlen entry points, through the C ABI) against the CPU
+oracle run per sequence on the rows that exist."""
+import numpy as np
+import pytest
+
+from helpers import TOL, rel_err, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cottn():
+    import paper_2409_18747_amd.binding as b
+    yield b
+    b.cottn_tune_segments(0)
+
+
+def draw(B, H, N, d, dtype, seed):
+    from paper_2409_18747_amd import workloads
+    x = workloads.draw(B, H, N, d, dtype, seed)
+    rng = np.random.Generator(np.random.Philox(seed + 1000))
+    x["s_bh"] = rng.uniform(0.5, 1.5, (B, H)).astype(np.float32)
+    return x
+
+
+def run(cottn, oracle, causal, B, H, N, d, dtype, lens, seed, segments=0, saved=False):
+    import torch
+    x = draw(B, H, N, d, dtype, seed)
+    Q, K, V, dO = (to_device(x[k], dtype) for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s_bh"], "f32")
+    L = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    cottn.cottn_tune_segments(segments)
+    fwd = cottn.cottn_fwd_causal_varlen if causal else cottn.cottn_fwd_bidir_varlen
+    bwd = cottn.cottn_bwd_causal_varlen if causal else cottn.cottn_bwd_bidir_varlen
+    op = cottn.OP_FWD_CAUSAL if causal else cottn.OP_FWD_BIDIR
+    code = cottn.COTTN_BF16 if dtype == "bf16" else cottn.COTTN_F32
+    fwd_ws = None
+    if saved:
+        fwd_ws = torch.empty(max(cottn.cottn_workspace_bytes(op, B, H, N, d, 0, code), 256),
+                             dtype=torch.uint8, device="cuda")
+    # outputs start as NaN: every row, existing or not, must be written
+    nan_like = lambda t: torch.full_like(t, float("nan"))
+    O, dQ, dK, dV = nan_like(Q), nan_like(Q), nan_like(Q), nan_like(Q)
+    state = torch.full((B, H, d, d), float("nan"), dtype=torch.float32, device="cuda")
+    ds = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda")
+    fwd(Q, K, V, s, L, O=O, state=state, workspace=fwd_ws)
+    bwd(Q, K, V, s, L, dO, dQ=dQ, dK=dK, dV=dV, ds=ds, fwd_workspace=fwd_ws)
+    torch.cuda.synchronize()
+    O_ref, S_ref = oracle.fwd_varlen(x["Q"], x["K"], x["V"], x["s_bh"], lens, causal=causal)
+    g_ref = oracle.bwd_varlen(x["Q"], x["K"], x["V"], x["s_bh"], x["dO"], lens, causal=causal)
+    errs = {"O": rel_err(to_host(O), O_ref), "state": rel_err(to_host(state), S_ref)}
+    for name, got, want in zip(("dQ", "dK", "dV", "ds"), (dQ, dK, dV, ds), g_ref):
+        errs[name] = rel_err(to_host(got), want)
+    print("varlen %s %s B%d H%d N%d d%d lens %s seg%d saved%d: %s" %
+          ("causal" if causal else "bidir", dtype, B, H, N, d, lens, segments, saved,
+           {k: "%.2e" % v for k, v in errs.items()}), flush=True)
+    for b, n in enumerate(lens):  # rows that do not exist are exactly zero
+        n = min(max(n, 0), N)
+        for t in (O, dQ, dK, dV):
+            assert torch.all(t[b, :, n:] == 0)
+    # ds of this size is a short signed sum: measured against the largest entry like the tensors
+    for name, e in errs.items():
+        assert e <= TOL[dtype] * (4 if name == "ds" else 1), (name, e)
+
+
+LENS = {3: [200, 0, 77], 4: [300, 1, 64, 129]}
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("segments", [0, 1, 3, 7])
+@pytest.mark.parametrize("d,N,B", [(64, 300, 4), (128, 200, 3), (32, 300, 4)])
+def test_bf16(cottn, oracle, causal, segments, d, N, B):
+    run(cottn, oracle, causal, B, 2, N, d, "bf16", LENS[B], seed=600 + d, segments=segments)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("segments", [2, 4])
+def test_bf16_states_saved_by_forward(cottn, oracle, causal, segments):
+    run(cottn, oracle, causal, 4, 3, 300, 64, "bf16", LENS[4], seed=610, segments=segments, saved=True)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("segments", [0, 3])
+def test_f32(cottn, oracle, causal, segments):
+    run(cottn, oracle, causal, 3, 2, 200, 32, "f32", LENS[3], seed=620, segments=segments)
+
+
+def test_lengths_out_of_range_are_clamped(cottn, oracle):
+    run(cottn, oracle, True, 3, 2, 200, 64, "bf16", [500, -3, 200], seed=630)
+
+
+def test_stabiliser_per_sequence(cottn, oracle):
+    import torch
+    m = np.array([0.5, -1.2, 0.0, 2.5], dtype=np.float32)
+    lens = [1, 0, 17, 4096, 65536]
+    rng = np.random.Generator(np.random.Philox(640))
+    ds = rng.standard_normal((5, 4)).astype(np.float32)
+    L = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    s = cottn.cottn_scale_from_m_varlen(to_device(m, "f32"), L)
+    dm = cottn.cottn_scale_backward_varlen(to_device(m, "f32"), L, to_device(ds, "f32"))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host(s), oracle.scale_from_m_varlen(m, lens), rtol=1e-5)
+    dm_ref = oracle.scale_backward_varlen(m, lens, ds)
+    np.testing.assert_allclose(to_host(dm), dm_ref, rtol=1e-4, atol=1e-6 * np.abs(dm_ref).max())
