@@ -61,8 +61,11 @@ struct FwdCfg {
 
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
-// grid = units * n_compute workgroups; segment g of a unit writes slot g of the unit's
-// n_slots slots (the causal forward computes all segments but the last).  The bidirectional
+// grid = units * n_slots workgroups, workgroup (unit, g) as in the scan kernels: workgroups are
+// dealt to the XCDs by their index, and what this kernel reads stays in that XCD's L2 for the
+// scan workgroup of the same (unit, g) in the next launch.  Segment g of a unit writes slot g
+// of the unit's n_slots slots; segments at or beyond n_compute have no total to form and
+// leave at once (the causal forward needs all segments but the last).  The bidirectional
 // path uses it for Kh^T V and, with (K, V) := (Q, dO), for Qh^T dO; there, given the stored
 // segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
 // also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
@@ -79,7 +82,8 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
   __shared__ float dot_wave[Cfg::NW];
 
-  const int unit = blockIdx.x / n_compute, g = blockIdx.x % n_compute;
+  const int unit = blockIdx.x / n_slots, g = blockIdx.x % n_slots;
+  if (g >= n_compute) return;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const bf16_t* Ku = K + size_t(unit) * N * D;
@@ -444,7 +448,7 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   // The totals kernel takes the largest row tile that does not exceed the segment: with
   // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
   // paying one memory latency per 64-row chunk.
-  const dim3 grid(t.units * t.n_compute);
+  const dim3 grid(t.units * t.G);
   constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
   if (t.seg_rows >= TOP)
     return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
