@@ -57,7 +57,28 @@ struct FwdCfg {
   // never budget registers for more than two waves per SIMD unless one workgroup alone needs
   // it: spilling costs more than the second workgroup of a large chunk gains
   static constexpr int WAVES_PER_EU = NW / 4 > 2 ? NW / 4 : (WAVES_RAW > 2 ? 2 : WAVES_RAW);
+  // with CS waves per row group: one workgroup alone has NW * CS / 4 waves per SIMD; two
+  // workgroups per compute unit when the LDS (one more tile for staging) allows
+  template <int CS>
+  static constexpr int waves_per_eu() {
+    if (CS == 1) return WAVES_PER_EU;
+    const int own = NW * CS / 4;
+    const int wg = (160 * 1024) / (LDS_BYTES + 2 * TILE) >= 2 ? 2 : 1;
+    return own * wg > 4 ? (own > 4 ? own : 4) : own * wg;
+  }
 };
+
+// Waves per 16-row group in the scan kernel (see the kernel), chosen per shape by measurement:
+// two at d = 128, where one workgroup fills the LDS of a compute unit and four waves are too
+// few to cover latencies (+6 % on a 2048-token prefill of 4096 heads); at d = 64 and 32 the
+// two variants time the same and the smaller workgroup is kept.  COTTN_FWD_SPLIT_ALL builds
+// the two-wave variant for every chunk-64 shape (tuning).
+template <int D, int C> struct FwdSplit { static constexpr int CS = 1; };
+template <> struct FwdSplit<128, 64> { static constexpr int CS = 2; };
+#ifdef COTTN_FWD_SPLIT_ALL
+template <> struct FwdSplit<64, 64> { static constexpr int CS = 2; };
+template <> struct FwdSplit<32, 64> { static constexpr int CS = 2; };
+#endif
 
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
@@ -195,26 +216,36 @@ __global__ __launch_bounds__(256) void fwd_state_carry(float* __restrict__ seg_s
 // is S[key 16ct + r][value 16rt + 4 q4 + v].  That way a lane holds 4 consecutive values
 // of one key row, which it publishes to the row-major LDS copy Sl[key][value] with one
 // 8-byte write, and the update's row-side operand is the V fragment already read for P V.
-template <int D, int C>
-__global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causal_scan_bf16(
+//
+// CS = 2 puts two waves on every 16-row group: both form the masked similarity tile of the
+// group, each accumulates one half of the output columns and owns the state tiles whose
+// value side is that half.  Per-wave work and registers shrink; the workgroup has twice the
+// waves to cover latencies with.
+template <int D, int C, int CS>
+__global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS>())) void fwd_causal_scan_bf16(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
     int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = FwdCfg<D, C>;
-  using ST = AccTiles<D, Cfg::NW>;
-  using Stage = TileStage<D, C, Cfg::NT>;
+  constexpr int RG = C / 16;           // row groups of a chunk
+  constexpr int NOT = Cfg::DT / CS;    // output column tiles per wave
+  using ST = SplitTiles<D, RG, CS>;
+  using Stage = TileStage<D, C, Cfg::NT * CS>;
   constexpr int PITCH = Cfg::PITCH;
   __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q rows
   __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k rows
   __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
   __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
+  // with two waves on a row group the q rows stay live in the other wave: own staging tile
+  __shared__ __attribute__((aligned(16))) bf16_t Os[CS > 1 ? Cfg::TILE : 8];
   __shared__ float rq[C];
 
   COTTN_TRACE_POINT(7);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
+  const int rg = w % RG, cp = w / RG;  // row group, column part
   const size_t ubase = size_t(unit) * N * D;
   const bf16_t* Qu = Q + ubase;
   const bf16_t* Ku = K + ubase;
@@ -241,28 +272,28 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
   vst.fetch(Vu, row_begin, row_end);
   // the state the sequence starts from (chunked prefill) belongs to every segment's start state
   f32x4 start[ST::NCT][ST::NRT];
-  if (state_in != nullptr && ST::active(w)) {
+  if (state_in != nullptr && ST::active(rg, cp)) {
     const float* src = state_in + size_t(unit) * D * D;
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-        start[x][y] = *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(w, x) + r) * D +
-                                                      16 * ST::row_tile(w, y) + 4 * q4);
+        start[x][y] = *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(rg, cp, x) + r) * D +
+                                                      16 * ST::row_tile(rg, cp, y) + 4 * q4);
   }
-  if (seg_states != nullptr && g > 0 && ST::active(w)) {
-    const float* src = seg_states + size_t(unit) * G * D * D + (16 * ST::col_tile(w, 0) + r) * D +
-                       16 * ST::row_tile(w, 0) + 4 * q4;
+  if (seg_states != nullptr && g > 0 && ST::active(rg, cp)) {
+    const float* src = seg_states + size_t(unit) * G * D * D + (16 * ST::col_tile(rg, cp, 0) + r) * D +
+                       16 * ST::row_tile(rg, cp, 0) + 4 * q4;
     add_stored_states<ST::STATE_BATCH>(
         sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
           return *reinterpret_cast<const f32x4*>(
               src + size_t(gp) * D * D +
-              16 * (ST::col_tile(w, x) - ST::col_tile(w, 0)) * D +
-              16 * (ST::row_tile(w, y) - ST::row_tile(w, 0)));
+              16 * (ST::col_tile(rg, cp, x) - ST::col_tile(rg, cp, 0)) * D +
+              16 * (ST::row_tile(rg, cp, y) - ST::row_tile(rg, cp, 0)));
         });
   }
 
-  if (state_in != nullptr && ST::active(w)) {
+  if (state_in != nullptr && ST::active(rg, cp)) {
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
@@ -271,13 +302,15 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
         for (int v = 0; v < 4; ++v) sacc[x][y][v] += start[x][y][v];
   }
 
-  RowPieces<D> finished;  // output rows of the previous chunk, stored one chunk late
+  RowPieces<D, NOT> finished;  // output rows of the previous chunk, stored one chunk late
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<D, NOT>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  bf16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * PITCH;
+  const int col0 = 16 * NOT * cp;  // first output column of this wave
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     COTTN_TRACE_POINT(0);
     // ---- publish the state (bf16) and this chunk's tiles
-    if (ST::active(w)) {
+    if (ST::active(rg, cp)) {
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
@@ -285,8 +318,8 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
           uint2 pk;
           pk.x = pack_bf16(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack_bf16(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(w, x) + r) * PITCH +
-                                    16 * ST::row_tile(w, y) + 4 * q4) = pk;
+          *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(rg, cp, x) + r) * PITCH +
+                                    16 * ST::row_tile(rg, cp, y) + 4 * q4) = pk;
         }
     }
     {
@@ -304,7 +337,8 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
     }
-    if (row0 > row_begin) store_row_pieces<D>(finished, Ou, row0 - C + 16 * w, row_end, l);
+    if (row0 > row_begin)
+      store_row_pieces<D, NOT>(finished, Ou, row0 - C + 16 * rg, row_end, l, col0);
     COTTN_TRACE_POINT(2);
     __syncthreads();
     COTTN_TRACE_POINT(3);
@@ -313,20 +347,20 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
     bf16x8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
-      qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
-    // oacc[nt][v] = O[query 16w + r][value 16 nt + 4 q4 + v] before the row factor
-    f32x4 oacc[Cfg::DT];
+      qf[ks] = lds_row_frag(Qs + (16 * rg + r) * PITCH + 32 * ks + 8 * q4);
+    // oacc[nt][v] = O[query 16 rg + r][value col0 + 16 nt + 4 q4 + v] before the row factor
+    f32x4 oacc[NOT];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NOT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      bf16x8 sf[Cfg::DT];
+      bf16x8 sf[NOT];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt)
-        sf[nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+      for (int nt = 0; nt < NOT; ++nt)
+        sf[nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, col0 + 16 * nt, r);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(sf[nt], qf[ks], oacc[nt]);
+      for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(sf[nt], qf[ks], oacc[nt]);
       __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -334,20 +368,20 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
     // ---- intra-chunk part and state update, two key tiles (32 tokens) at a time
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
-      const bool diag_or_below = 2 * p <= w;  // wave-uniform: else every key is masked
+      const bool diag_or_below = 2 * p <= rg;  // wave-uniform: else every key is masked
       // k slot (q4, e) of the P fragment is token 32p + 16*(e/4) + 4*q4 + e%4; V and K are
       // read down their rows in the same order
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
-      bf16x8 vc[Cfg::DT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
+      bf16x8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) vc[nt] = lds_col_frag(Vs, PITCH, t0, t1, 16 * nt, r);
+      for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, PITCH, t0, t1, col0 + 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
-        kcol[x] = lds_col_frag(Ks, PITCH, t0, t1, 16 * ST::col_tile(w, x), r);
-      if (ST::WPC != 1) {
+        kcol[x] = lds_col_frag(Ks, PITCH, t0, t1, 16 * ST::col_tile(rg, cp, x), r);
+      if (!ST::ROW_OPERAND_IS_OUTPUT_V) {
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
-          vrow[y] = lds_col_frag(Vs, PITCH, t0, t1, 16 * ST::row_tile(w, y), r);
+          vrow[y] = lds_col_frag(Vs, PITCH, t0, t1, 16 * ST::row_tile(rg, cp, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
@@ -365,50 +399,51 @@ __global__ __launch_bounds__(C * 4, (FwdCfg<D, C>::WAVES_PER_EU)) void fwd_causa
           f32x4 pacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks) pacc = mma16(kr[half][ks], qf[ks], pacc);
-          // pacc[v] = q_(16w + r) . k_(16jt + 4*q4 + v); keep key <= query
+          // pacc[v] = q_(16 rg + r) . k_(16jt + 4*q4 + v); keep key <= query
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const bool keep = (jt < w) || (jt == w && 4 * q4 + v <= r);
+            const bool keep = (jt < rg) || (jt == rg && 4 * q4 + v <= r);
             pf[4 * half + v] = static_cast<__bf16>(keep ? pacc[v] : 0.f);
           }
         }
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(vc[nt], pf, oacc[nt]);
+        for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(vc[nt], pf, oacc[nt]);
       }
       // state update S^T += (r v)^T k over these 32 tokens
-      if (ST::active(w)) {
+      if (ST::active(rg, cp)) {
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
           for (int x = 0; x < ST::NCT; ++x)
-            sacc[x][y] = mma16(ST::WPC == 1 ? vc[y] : vrow[y], kcol[x], sacc[x][y]);
+            sacc[x][y] = mma16(ST::ROW_OPERAND_IS_OUTPUT_V ? vc[y] : vrow[y], kcol[x], sacc[x][y]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 
     COTTN_TRACE_POINT(5);
-    // ---- O rows: factor s_h r_i, staged through this wave's own (now dead) rows of Qs
-    const float row_factor = scale * rq[16 * w + r];
+    // ---- O rows: factor s_h r_i, staged through the wave's own (now dead) rows of Qs, or
+    // through its part of the staging tile
+    const float row_factor = scale * rq[16 * rg + r];
     wave_lds_sync();
-    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, l, finished);
+    gather_rows_transposed<D, NOT>(oacc, row_factor, stage, l, finished, col0);
     __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
     COTTN_TRACE_POINT(6);
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
+    store_row_pieces<D, NOT>(finished, Ou, last + 16 * rg, row_end, l, col0);
   }
 
   if (seq_len != nullptr) zero_rows_bf16<D>(Ou, row_end, seg_end);  // rows that do not exist
 
-  if (state_out != nullptr && g == G - 1 && ST::active(w)) {
+  if (state_out != nullptr && g == G - 1 && ST::active(rg, cp)) {
     float* out = state_out + size_t(unit) * D * D;
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-        *reinterpret_cast<f32x4*>(out + (16 * ST::col_tile(w, x) + r) * D +
-                                  16 * ST::row_tile(w, y) + 4 * q4) = sacc[x][y];
+        *reinterpret_cast<f32x4*>(out + (16 * ST::col_tile(rg, cp, x) + r) * D +
+                                  16 * ST::row_tile(rg, cp, y) + 4 * q4) = sacc[x][y];
   }
 }
 
@@ -432,8 +467,9 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
       if (err != hipSuccess) return err;
     }
   }
-  return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
+  constexpr int CS = FwdSplit<D, C>::CS;
+  return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C, CS>, dim3(units * a.G),
+                       dim3(Cfg::NT * CS), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
                        a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
 }

@@ -129,6 +129,32 @@ struct AccTiles {
   }
 };
 
+// The same ownership when the C/16 row groups of a chunk are each served by CS waves that
+// split the result columns between them (wave = (row group rg, column part cp)).  CS = 1 is
+// AccTiles over the row groups.  CS > 1: a wave owns the key tiles rg, rg + RG, ... and the
+// value tiles of its own column part, which are the tiles whose V fragments it reads anyway.
+template <int D, int RG, int CS>
+struct SplitTiles {
+  using One = AccTiles<D, RG>;
+  static constexpr int DT = D / 16;
+  static constexpr int NCT = CS == 1 ? One::NCT : (RG >= DT ? 1 : DT / RG);
+  static constexpr int NRT = CS == 1 ? One::NRT : DT / CS;
+  // whether the row-side operand of the state update is among the V fragments of the wave's
+  // output columns (else it is read separately)
+  static constexpr bool ROW_OPERAND_IS_OUTPUT_V = CS == 1 ? One::WPC == 1 : true;
+  static constexpr int STATE_BATCH = NCT * NRT <= 4 ? 3 : NCT * NRT <= 8 ? 2 : 1;
+  static_assert(CS == 1 || DT % CS == 0, "column parts must be whole tiles");
+  __device__ static __forceinline__ bool active(int rg, int cp) {
+    return CS == 1 ? One::active(rg) : rg < DT;
+  }
+  __device__ static __forceinline__ int col_tile(int rg, int cp, int x) {
+    return CS == 1 ? One::col_tile(rg, x) : rg % DT + x * RG;
+  }
+  __device__ static __forceinline__ int row_tile(int rg, int cp, int y) {
+    return CS == 1 ? One::row_tile(rg, y) : cp * NRT + y;
+  }
+};
+
 // acc += the wave's tiles of the stored states first..last, `load(state, x, y)` returning
 // tile (x, y) of one of them.  States are taken BATCH at a time with every load of a batch
 // issued before the first addition, so a batch costs one memory latency, not one per state.
@@ -158,56 +184,61 @@ __device__ __forceinline__ void add_stored_states(f32x4 (&acc)[NCT][NRT], int fi
   }
 }
 
-// A wave's finished 16-row x D-column result block as whole 16-byte pieces of rows, one or
-// more per lane, ready for coalesced global stores.
-template <int D>
+// A wave's finished result block (16 rows x NTILES*16 columns, by default all D columns) as
+// whole 16-byte pieces of rows, one or more per lane, ready for coalesced global stores.
+template <int D, int NTILES = D / 16>
 struct RowPieces {
-  static constexpr int PIECES = 16 * D / 8;  // 16-byte pieces in the wave's 16 rows
-  static constexpr int PER_LANE = PIECES / 64;
-  static_assert(PIECES % 64 == 0, "a wave's rows must split evenly over its lanes");
+  static constexpr int PPR = 2 * NTILES;     // 16-byte pieces per row
+  static constexpr int PIECES = 16 * PPR;    // in the wave's 16 rows
+  static constexpr int PER_LANE = (PIECES + 63) / 64;
   uint4 v[PER_LANE];
 };
 
 // Turns a wave's result block whose accumulators are laid out TRANSPOSED (acc[nt][v] =
-// result[row r][column 16 nt + 4 q4 + v], i.e. each lane holds 4 consecutive columns of one
-// row) into row pieces: scales by the per-lane row factor, rounds to bf16, passes the block
-// through the wave's own 16 rows of an LDS tile with 8-byte writes and reads it back as
-// 16-byte pieces.
-template <int D>
+// result[row r][column col0 + 16 nt + 4 q4 + v], i.e. each lane holds 4 consecutive columns
+// of one row) into row pieces: scales by the per-lane row factor, rounds to bf16, passes the
+// block through 16 rows of an LDS tile (columns col0.. of stage_rows, private to the wave)
+// with 8-byte writes and reads it back as 16-byte pieces.
+template <int D, int NTILES = D / 16>
 __device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float row_factor,
                                                        bf16_t* stage_rows, int l,
-                                                       RowPieces<D>& out) {
-  constexpr int DT = D / 16, PITCH = lds_pitch(D);
+                                                       RowPieces<D, NTILES>& out, int col0 = 0) {
+  using RP = RowPieces<D, NTILES>;
+  constexpr int PITCH = lds_pitch(D);
   const int r = l % 16, q4 = l / 16;
 #pragma unroll
-  for (int nt = 0; nt < DT; ++nt) {
+  for (int nt = 0; nt < NTILES; ++nt) {
     uint2 pk;
     pk.x = pack_bf16(row_factor * acc[nt][0], row_factor * acc[nt][1]);
     pk.y = pack_bf16(row_factor * acc[nt][2], row_factor * acc[nt][3]);
-    *reinterpret_cast<uint2*>(stage_rows + r * PITCH + 16 * nt + 4 * q4) = pk;
+    *reinterpret_cast<uint2*>(stage_rows + r * PITCH + col0 + 16 * nt + 4 * q4) = pk;
   }
   wave_lds_sync();
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) {
+  for (int j = 0; j < RP::PER_LANE; ++j) {
     const int i = l + 64 * j;
-    const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
-    out.v[j] = *reinterpret_cast<const uint4*>(stage_rows + lr * PITCH + col);
+    const int lr = i / RP::PPR, col = col0 + (i % RP::PPR) * 8;
+    if (RP::PIECES % 64 == 0 || i < RP::PIECES)
+      out.v[j] = *reinterpret_cast<const uint4*>(stage_rows + lr * PITCH + col);
   }
 }
 
-// Writes the pieces to rows first_row.. of dst; rows at or beyond row_end are not written.
-// The scan kernels call this one chunk late (after the next chunk's loads have been issued):
-// the wait for those loads at the top of a chunk step is a wait for every outstanding memory
-// operation, and must not find stores that were issued a moment ago.
-template <int D>
-__device__ __forceinline__ void store_row_pieces(const RowPieces<D>& p, bf16_t* __restrict__ dst,
-                                                 int first_row, int row_end, int l) {
+// Writes the pieces to rows first_row.. (columns col0..) of dst; rows at or beyond row_end are
+// not written.  The scan kernels call this one chunk late (after the next chunk's loads have
+// been issued): the wait for those loads at the top of a chunk step is a wait for every
+// outstanding memory operation, and must not find stores that were issued a moment ago.
+template <int D, int NTILES = D / 16>
+__device__ __forceinline__ void store_row_pieces(const RowPieces<D, NTILES>& p,
+                                                 bf16_t* __restrict__ dst, int first_row,
+                                                 int row_end, int l, int col0 = 0) {
+  using RP = RowPieces<D, NTILES>;
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) {
+  for (int j = 0; j < RP::PER_LANE; ++j) {
     const int i = l + 64 * j;
-    const int lr = i / (D / 8), col = (i % (D / 8)) * 8;
+    const int lr = i / RP::PPR, col = col0 + (i % RP::PPR) * 8;
     const int row = first_row + lr;
-    if (row < row_end) *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) = p.v[j];
+    if ((RP::PIECES % 64 == 0 || i < RP::PIECES) && row < row_end)
+      *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) = p.v[j];
   }
 }
 
