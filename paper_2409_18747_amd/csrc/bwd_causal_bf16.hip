@@ -328,8 +328,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < AT::NRT; ++y)
-        *reinterpret_cast<f32x4*>(out + (16 * AT::col_tile(w, x) + r) * D +
-                                  16 * AT::row_tile(w, y) + 4 * q4) = racc[x][y];
+        store_state_words(out + (16 * AT::col_tile(w, x) + r) * D + 16 * AT::row_tile(w, y) + 4 * q4,
+                          racc[x][y]);
   }
 
   // per-workgroup partial of ds: lanes of the first lane row hold the row sums

@@ -13,6 +13,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef uint16_t bf16_t;  // storage type of bf16 data in global memory and LDS
 
 #define COTTN_LDS __attribute__((address_space(3)))
@@ -149,6 +150,34 @@ __device__ __forceinline__ void zero_rows_bf16(bf16_t* __restrict__ dst, int row
   const long pieces = long(max(0, row_hi - row_lo)) * (D / 8);
   uint4* p = reinterpret_cast<uint4*>(dst + size_t(row_lo) * D);
   for (long i = threadIdx.x; i < pieces; i += blockDim.x) p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
+// 16-byte store of a result that this library does not read again soon: marked non-temporal,
+// so that the line does not displace input rows another kernel of the same step re-reads
+// from this XCD's L2.
+__device__ __forceinline__ void store_streaming(void* dst, uint4 v) {
+#ifdef COTTN_PLAIN_OUTPUT_STORES
+  *reinterpret_cast<uint4*>(dst) = v;
+#else
+  __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(dst));
+#endif
+}
+
+// Stores of segment states to the workspace: read next by workgroups on other XCDs, which this
+// XCD's L2 cannot serve, so they are marked non-temporal as well.
+__device__ __forceinline__ void store_state_word(float* dst, float v) {
+#ifdef COTTN_PLAIN_STATE_STORES
+  *dst = v;
+#else
+  __builtin_nontemporal_store(v, dst);
+#endif
+}
+__device__ __forceinline__ void store_state_words(float* dst, f32x4 v) {
+#ifdef COTTN_PLAIN_STATE_STORES
+  *reinterpret_cast<f32x4*>(dst) = v;
+#else
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+#endif
 }
 
 // 1 / max(sqrt(sum_sq), eps)

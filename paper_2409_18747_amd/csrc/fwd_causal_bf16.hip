@@ -161,8 +161,8 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
       for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          out[(16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r] =
-              acc[x][y][v];
+          store_state_word(out + (16 * ST::row_tile(w, y) + 4 * q4 + v) * D +
+                               16 * ST::col_tile(w, x) + r, acc[x][y][v]);
   }
   if (dot_with != nullptr) {  // workgroup-uniform
     float dot = 0.f;

@@ -238,7 +238,7 @@ __device__ __forceinline__ void store_row_pieces(const RowPieces<D, NTILES>& p,
     const int lr = i / RP::PPR, col = col0 + (i % RP::PPR) * 8;
     const int row = first_row + lr;
     if ((RP::PIECES % 64 == 0 || i < RP::PIECES) && row < row_end)
-      *reinterpret_cast<uint4*>(dst + size_t(row) * D + col) = p.v[j];
+      store_streaming(dst + size_t(row) * D + col, p.v[j]);
   }
 }
 
