@@ -101,3 +101,19 @@ def test_bf16_zero_rows_and_determinism(cottn, oracle):
     for x, y in zip(a, b):
         assert torch.isfinite(x.float()).all()
         assert torch.equal(x, y)
+
+
+def test_bf16_zero_key_rows_with_values(cottn, oracle):
+    """Key rows that are exactly zero while their value rows are not (Sec. 3.2 normalisation
+    clamped at eps): they contribute nothing forward, their dK follows the x/eps rule without
+    the projection, and nothing becomes NaN or Inf."""
+    import torch
+
+    def mutate(x):
+        x["K"][:, :, 5] = 0.0
+        x["K"][:, :, 70:72] = 0.0
+        x["Q"][:, :, 64] = 0.0
+
+    out = run_bwd(cottn, oracle, 2, 2, 200, 64, "bf16", seed=33, segments=2, mutate=mutate)
+    for t in out:
+        assert torch.isfinite(t.float()).all()
