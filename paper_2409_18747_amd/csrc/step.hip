@@ -35,6 +35,17 @@ template <> struct Elem<bf16_t> {
   }
 };
 
+__device__ __forceinline__ float4 load_state_row(const float* p) {
+  return *reinterpret_cast<const float4*>(p);
+}
+// The updated state is written with non-temporal stores: by the time the next step reads a
+// state again, 512 MiB have passed through the caches, so keeping the written lines only costs
+// (measured: 79.4 us per step against 83.4 us with plain stores; non-temporal loads on top of
+// that are slower, 90 us).
+__device__ __forceinline__ void store_state_row(float* p, float4 x) {
+  __builtin_nontemporal_store(f32x4{x.x, x.y, x.z, x.w}, reinterpret_cast<f32x4*>(p));
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_step_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
@@ -83,7 +94,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(
   float4 rows[PASSES];
 #pragma unroll
   for (int p = 0; p < PASSES; ++p)
-    rows[p] = *reinterpret_cast<const float4*>(Su + size_t(p * RPP + row_in_pass) * D + col);
+    rows[p] = load_state_row(Su + size_t(p * RPP + row_in_pass) * D + col);
   __syncthreads();
 
   float4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -96,7 +107,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(
     x.y += kr * v4.y;
     x.z += kr * v4.z;
     x.w += kr * v4.w;
-    *reinterpret_cast<float4*>(Su + size_t(row) * D + col) = x;
+    store_state_row(Su + size_t(row) * D + col, x);
     acc.x += qr * x.x;
     acc.y += qr * x.y;
     acc.z += qr * x.z;
