@@ -7,26 +7,30 @@
 // running backward.  With S_t = sum_{j<=t} kh_j^T v_j and R_t = sum_{i>=t} qh_i^T dO_i:
 //     dqh_t = s dO_t S_t^T,    dkh_t = s v_t R_t^T,    dv_t = s kh_t R_t.
 // Both sums are regrouped exactly into chunks of C rows inside G segments per (batch, head):
-//   kernel 1  per-segment totals of Kh^T V (forward states) and Qh^T dO (reverse states),
-//             both stored [d_key][d_value];
-//   kernel 2  exclusive prefix of the first and exclusive suffix of the second along the
-//             segment axis;
-//   kernel 3  forward-time scan: dQ of a segment, chunk by chunk, first to last;
-//   kernel 4  reverse-time scan: dK and dV of a segment, chunk by chunk, last to first;
-//   kernel 5  ds[h] from per-workgroup partial sums.
+//   forward-time states   per-segment totals of Kh^T V, [d_key][d_value]: taken over from the
+//             forward call when it hands its workspace on, else rebuilt by the forward's
+//             totals kernel; with many segments a carry kernel turns totals into prefixes
+//             (and the reverse-time totals into suffixes), with few the scans add them up;
+//   dQ scan   forward-time: dQ of a segment, chunk by chunk, first to last; it has Q and dO
+//             in LDS anyway and leaves the segment's reverse-time total Qh^T dO behind;
+//   dK/dV scan  reverse-time: dK and dV of a segment, chunk by chunk, last to first (so it
+//             starts on the rows the dQ scan read last, which are still in the XCD's L2);
+//             its first workgroups also add up ds from the dQ scan's partial sums
+//             (a separate small kernel does that for the fp32 path).
 //
 // Normalisation factors r_i = 1/max(|q_i|, eps), r_j = 1/max(|k_j|, eps) are not applied to
 // Q and K element-wise where a row factor does the same:
 //   dQ pass    V is rescaled to r_j v_j on its way into LDS (then A_ij r_j = dO_i . (r_j v_j)
-//              and S = sum k_j^T (r_j v_j)); Q and K stay raw;
+//              and S = sum k_j^T (r_j v_j)); K stays raw; Q is only needed normalised (for
+//              the chain rule below and for the reverse-time total) and is stored as qh;
 //              dqh_i = sum_j A'_ij k_j + dO_i S^T;
 //   dK/dV pass Q is rescaled to r_i q_i (it is contracted over the token index in the
 //              reverse state R = sum (r_i q_i)^T dO_i); K and V stay raw;
 //              dv_j = s r_j [ sum_i ((r_i q_i).k_j) dO_i + k_j R ],
 //              dkh_j = sum_i A_ij (r_i q_i) + v_j R^T.
 // The chain rule through x/max(||x||, eps), with t = x . dxh on the raw row:
-//     dx = s r (dxh - x r^2 t)   (rows at or below eps: dx = s r dxh),
-// and ds_h = sum over rows of qh_i . dqh_i = r_i t_i before scaling by s.
+//     dx = s r (dxh - x r^2 t) = s r (dxh - xh (xh . dxh))   (rows at or below eps: dx = s r dxh),
+// and ds_h = sum over rows of qh_i . dqh_i before scaling by s.
 //
 // Inside a chunk the masked A and P tiles are produced directly in the register layout the
 // next product needs as an operand, so they never pass through LDS; operands contracted

@@ -5,7 +5,8 @@
 //   * the sequence of one (batch, head) is cut into G segments, each a whole number of chunks
 //     of C rows;
 //   * kernel 1 (segment totals) reduces kh^T v over every segment but the last;
-//   * kernel 2 (carry) turns the totals into exclusive prefixes: the state at each segment start;
+//   * kernel 2 (carry, only with many segments; with few the scan adds the totals up itself)
+//     turns the totals into exclusive prefixes: the state at each segment start;
 //   * kernel 3 (scan) walks the chunks of its segment with the d x d state in fp32
 //     accumulators:  O_c = s_h [ (Qh_c Kh_c^T (.) M) V_c + Qh_c S ],  S += Kh_c^T V_c,
 //     where the first term is eq. attn_1 restricted to the chunk.
@@ -28,10 +29,13 @@
 // accumulated transposed (O^T = V^T P^T + S^T Q^T) so that a lane ends up with 4 consecutive
 // columns of one output row: one row factor per lane and 8-byte staging writes.
 //
-// Scheduling: the kernels are bound by instruction issue and latency, not by MFMA rate, so
-// every group of MFMAs is preceded by all of its LDS reads, issued back to back into distinct
-// registers (a scheduling barrier keeps the compiler from sinking a read next to its use),
-// and the next chunk's tiles are prefetched into registers while the current one is computed.
+// Scheduling: the kernels wait for memory and for their own latencies, not for the MFMA
+// units, so every group of MFMAs is preceded by all of its LDS reads, issued back to back into
+// distinct registers (a scheduling barrier keeps the compiler from sinking a read next to its
+// use), the next chunk's tiles are prefetched into registers while the current one is
+// computed, and finished output rows are stored one chunk late, non-temporally.  An XCD's L2
+// keeps its contents between launches and workgroups are dealt to the XCDs by index, so the
+// totals kernel and the scan number their workgroups alike: the scan finds its K, V rows in L2.
 #include "device_common.h"
 #include "launch.h"
 #include "tile_io.h"
