@@ -98,7 +98,8 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
  *   earlier call left in `state`, or cottn_step's state); O_i = s qh_i (state_in + sum_{j<=i}
  *   kh_j^T v_j) and `state` (may be NULL) receives state_in + the sum over this piece.
  *   state_in and state must not be the same buffer (COTTN_E_ARG): workgroups read the one
- *   while others write the other.  N = 0 copies state_in to state. */
+ *   while others write the other.  N = 0 copies state_in to state.  With a small N this is
+ *   also a several-token decode step: it gives what N calls of cottn_step give. */
 int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
                                 const float* state_in, void* O, float* state, void* workspace,
                                 size_t workspace_bytes, int B, int H, int N, int d, int chunk,

@@ -158,3 +158,33 @@ def test_empty_piece_copies_the_state(cottn):
     torch.cuda.synchronize()
     assert st == 0
     assert torch.equal(state, state_in)
+
+
+@pytest.mark.parametrize("k", [1, 4, 7])
+def test_multi_token_step_equals_single_steps(cottn, oracle, k):
+    """A k-token step (speculative decoding) is cottn_fwd_causal_from_state with N = k: same
+    outputs and same final state as k calls of cottn_step, to bf16 output rounding."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    B, H, d, warm = 3, 4, 128, 40
+    x = workloads.draw(B, H, warm + k, d, "bf16", 93, with_dO=False)
+    s = to_device(x["s"], "f32")
+    Q, K, V = (to_device(x[n], "bf16") for n in "QKV")
+    state0 = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    cottn.cottn_fwd_causal(Q[:, :, :warm].contiguous(), K[:, :, :warm].contiguous(),
+                           V[:, :, :warm].contiguous(), s, state=state0)
+    # k single steps
+    st_a = state0.clone()
+    o_a = [cottn.cottn_step(Q[:, :, warm + t].contiguous(), K[:, :, warm + t].contiguous(),
+                            V[:, :, warm + t].contiguous(), s, st_a) for t in range(k)]
+    # one k-token call
+    st_b = torch.empty_like(state0)
+    O_b = cottn.cottn_fwd_causal_from_state(Q[:, :, warm:].contiguous(), K[:, :, warm:].contiguous(),
+                                            V[:, :, warm:].contiguous(), s, state0, state=st_b)
+    torch.cuda.synchronize()
+    ref, S_ref = oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"])
+    got_a = np.stack([to_host(o) for o in o_a], axis=2)
+    assert rel_err(got_a, ref[:, :, warm:]) <= TOL["bf16"]
+    assert rel_err(to_host(O_b), ref[:, :, warm:]) <= TOL["bf16"]
+    assert rel_err(to_host(st_a), S_ref) <= TOL["bf16"] and rel_err(to_host(st_b), S_ref) <= TOL["bf16"]
+    assert rel_err(to_host(O_b), got_a) <= 2.0 ** -6
