@@ -20,8 +20,10 @@
  *     and do NOT contain s (it is applied at read-out, so a state written by
  *     cottn_fwd_causal can be continued by cottn_step).
  *   - `dtype` is the storage type of Q, K, V, O, dO, dQ, dK, dV, q, k, v, o:
- *     COTTN_F32 (fp32 arithmetic) or COTTN_BF16 (bf16 MFMA operands, fp32 accumulation,
- *     outputs rounded to nearest-even).  s, ds, states and the workspace are always fp32.
+ *     COTTN_F32 (fp32 arithmetic), COTTN_BF16 or COTTN_F16 (16-bit MFMA operands, fp32
+ *     accumulation, outputs rounded to nearest-even; with COTTN_F16 the operands the kernels
+ *     keep in 16 bits, among them the running d x d state, must stay below 65504 in magnitude).
+ *     s, ds, states and the workspace are always fp32.
  *   - Normalisation is x / max(||x||_2, eps); rows with ||x|| <= eps are x / eps.
  *   - The caller owns every buffer.  The library allocates nothing, frees nothing, never
  *     synchronises, and enqueues all work on `hip_stream` (a hipStream_t; NULL = the default
@@ -30,7 +32,8 @@
  *   - Base pointers of tensors must be 16-byte aligned; the workspace 256-byte aligned.
  *   - Supported shapes: d in {32, 64, 128}; B, H, N >= 1 (N == 0 is accepted and does
  *     nothing but define the outputs that do not depend on rows); chunk in {0, 64, 128, 256}
- *     for bf16 (0 = library default, 64; d = 128 supports 64 only), and chunk in {0, 32} for fp32.
+ *     for the 16-bit types (0 = library default, 64; d = 128 supports 64 only), and chunk in
+ *     {0, 32} for fp32.
  *     N need not be a multiple of chunk.
  *   - Return value: COTTN_OK or a cottn_status error code.  Argument errors are detected
  *     before anything is enqueued (so they can be exercised without a GPU); HIP launch
@@ -48,13 +51,13 @@
 extern "C" {
 #endif
 
-typedef enum { COTTN_F32 = 0, COTTN_BF16 = 1 } cottn_dtype;
+typedef enum { COTTN_F32 = 0, COTTN_BF16 = 1, COTTN_F16 = 2 } cottn_dtype;
 
 typedef enum {
   COTTN_OK = 0,
   COTTN_E_NULL = 1,      /* a required pointer is NULL */
   COTTN_E_SHAPE = 2,     /* B, H, N, d or chunk outside the supported set */
-  COTTN_E_DTYPE = 3,     /* dtype is neither COTTN_F32 nor COTTN_BF16 */
+  COTTN_E_DTYPE = 3,     /* dtype is none of COTTN_F32, COTTN_BF16, COTTN_F16 */
   COTTN_E_ALIGN = 4,     /* a pointer is not aligned as required */
   COTTN_E_WORKSPACE = 5, /* workspace NULL or smaller than cottn_workspace_bytes() */
   COTTN_E_HIP = 6,       /* a HIP call failed (launch error) */

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 library_path = os.path.join(_HERE, "libcottn.so")
 
-COTTN_F32, COTTN_BF16 = 0, 1
+COTTN_F32, COTTN_BF16, COTTN_F16 = 0, 1, 2
 OP_FWD_CAUSAL, OP_BWD_CAUSAL, OP_FWD_BIDIR, OP_BWD_BIDIR, OP_STEP = range(5)
 
 
@@ -92,7 +92,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return COTTN_F32
     if t.dtype == torch.bfloat16:
         return COTTN_BF16
-    raise TypeError("tensors must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return COTTN_F16
+    raise TypeError("tensors must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def _ptr(t):

@@ -39,10 +39,10 @@ bool dims_ok(int B, int H, int N, int d) {
 
 // Split of one (batch, head) sequence into segments; see workspace.h.
 bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan* plan) {
-  if (dtype != COTTN_F32 && dtype != COTTN_BF16) return false;
+  if (dtype != COTTN_F32 && dtype != COTTN_BF16 && dtype != COTTN_F16) return false;
   if (!dims_ok(B, H, N, d)) return false;
   int C;
-  if (dtype == COTTN_BF16) {
+  if (dtype != COTTN_F32) {
     C = chunk == 0 ? 64 : chunk;
     if (C != 64 && C != 128 && C != 256) return false;
     if (d == 128 && C != 64) return false;
@@ -107,7 +107,7 @@ int check_common(const void* const* ptrs, int n_ptrs, int B, int H, int N, int d
                  float eps) {
   for (int i = 0; i < n_ptrs; ++i)
     if (ptrs[i] == nullptr) return COTTN_E_NULL;
-  if (dtype != COTTN_F32 && dtype != COTTN_BF16) return COTTN_E_DTYPE;
+  if (dtype != COTTN_F32 && dtype != COTTN_BF16 && dtype != COTTN_F16) return COTTN_E_DTYPE;
   if (!dims_ok(B, H, N, d)) return COTTN_E_SHAPE;
   if (!(eps > 0.f)) return COTTN_E_ARG;
   for (int i = 0; i < n_ptrs; ++i)
@@ -133,7 +133,9 @@ extern "C" {
 
 size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int dtype) {
   if (op == COTTN_OP_STEP) {
-    return (dtype == COTTN_F32 || dtype == COTTN_BF16) && dims_ok(B, H, 1, d) ? 0 : size_t(-1);
+    return (dtype == COTTN_F32 || dtype == COTTN_BF16 || dtype == COTTN_F16) && dims_ok(B, H, 1, d)
+               ? 0
+               : size_t(-1);
   }
   if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_STEP) return size_t(-1);
   SeqPlan plan;
@@ -155,8 +157,8 @@ const char* cottn_status_string(int status) {
     case COTTN_OK: return "ok";
     case COTTN_E_NULL: return "a required pointer is NULL";
     case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d in {32,64,128}, "
-                               "chunk in {0,64,128,256} (bf16; 64 only when d = 128) or {0,32} (fp32)";
-    case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0) or COTTN_BF16 (1)";
+                               "chunk in {0,64,128,256} (16-bit; 64 only when d = 128) or {0,32} (fp32)";
+    case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0), COTTN_BF16 (1) or COTTN_F16 (2)";
     case COTTN_E_ALIGN: return "tensor pointers must be 16-byte aligned, the workspace 256-byte aligned";
     case COTTN_E_WORKSPACE: return "workspace is NULL or smaller than cottn_workspace_bytes()";
     case COTTN_E_HIP: return "a HIP call failed";
@@ -206,7 +208,7 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
-  return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : fwd_causal_f32(a));
+  return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : dtype == COTTN_F16 ? fwd_causal_f16(a) : fwd_causal_f32(a));
 }
 
 }  // namespace
@@ -252,7 +254,7 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   a.eps = eps; a.stream = stream;
   // the forward's segment states are taken over only if the forward split the sequence as
   // the backward does
-  if (fwd_workspace != nullptr && dtype == COTTN_BF16 && plan.G > 1) {
+  if (fwd_workspace != nullptr && dtype != COTTN_F32 && plan.G > 1) {
     SeqPlan fwd_plan;
     if (make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &fwd_plan) &&
         fwd_plan.C == plan.C && fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
@@ -262,7 +264,7 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
       a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
     }
   }
-  return map_hip(dtype == COTTN_BF16 ? bwd_causal_bf16(a) : bwd_causal_f32(a));
+  return map_hip(dtype == COTTN_BF16 ? bwd_causal_bf16(a) : dtype == COTTN_F16 ? bwd_causal_f16(a) : bwd_causal_f32(a));
 }
 
 int fwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
@@ -285,7 +287,7 @@ int fwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, c
   a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
-  return map_hip(dtype == COTTN_BF16 ? fwd_bidir_bf16(a) : fwd_bidir_f32(a));
+  return map_hip(dtype == COTTN_BF16 ? fwd_bidir_bf16(a) : dtype == COTTN_F16 ? fwd_bidir_f16(a) : fwd_bidir_f32(a));
 }
 
 int bwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
@@ -309,7 +311,7 @@ int bwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, c
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
-  if (fwd_workspace != nullptr && dtype == COTTN_BF16 && plan.G <= kMaxSegmentsSummedInScan) {
+  if (fwd_workspace != nullptr && dtype != COTTN_F32 && plan.G <= kMaxSegmentsSummedInScan) {
     SeqPlan fwd_plan;
     if (make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &fwd_plan) && fwd_plan.C == plan.C &&
         fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
@@ -319,7 +321,7 @@ int bwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, c
       a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
     }
   }
-  return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : bwd_bidir_f32(a));
+  return map_hip(dtype == COTTN_BF16 ? bwd_bidir_bf16(a) : dtype == COTTN_F16 ? bwd_bidir_f16(a) : bwd_bidir_f32(a));
 }
 
 }  // namespace

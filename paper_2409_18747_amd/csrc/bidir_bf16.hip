@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
 // dst (LDS, bf16, row-major [D][D] with the tile pitch) <- sum of the first n_sum of the
 // [D][D] fp32 matrices at src; the fp32 sum also goes to `copy` when that is not null.
 template <int D, int NT>
-__device__ __forceinline__ void stage_summed_matrix(bf16_t* dst, const float* __restrict__ src,
+__device__ __forceinline__ void stage_summed_matrix(e16_t* dst, const float* __restrict__ src,
                                                     int n_sum, float* __restrict__ copy) {
   constexpr int PITCH = lds_pitch(D);
   for (int e = 4 * threadIdx.x; e < D * D; e += 4 * NT) {
@@ -86,8 +86,8 @@ __device__ __forceinline__ void stage_summed_matrix(bf16_t* dst, const float* __
     }
     if (copy != nullptr) *reinterpret_cast<f32x4*>(copy + e) = a;
     uint2 pk;
-    pk.x = pack_bf16(a[0], a[1]);
-    pk.y = pack_bf16(a[2], a[3]);
+    pk.x = pack2(a[0], a[1]);
+    pk.y = pack2(a[2], a[3]);
     *reinterpret_cast<uint2*>(dst + (e / D) * PITCH + e % D) = pk;
   }
 }
@@ -96,23 +96,23 @@ __device__ __forceinline__ void stage_summed_matrix(bf16_t* dst, const float* __
 // n_sum stored matrices per unit at a stride of `slots` matrices; the workgroup of segment 0
 // writes their sum to `state` when that is asked for.
 template <int D, int C>
-__global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
-    const bf16_t* __restrict__ Q, const float* __restrict__ s, bf16_t* __restrict__ O,
+__global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
+    const e16_t* __restrict__ Q, const float* __restrict__ s, e16_t* __restrict__ O,
     const float* __restrict__ totals, int slots, int n_sum, float* __restrict__ state, int H, int N,
     int G, int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
-  __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // [d_key][d_value]
   __shared__ float rq[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* Qu = Q + ubase;
-  bf16_t* Ou = O + ubase;
+  const e16_t* Qu = Q + ubase;
+  e16_t* Ou = O + ubase;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
     f32x4 oacc[Cfg::DT];
 #pragma unroll
     for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bf16x8 qf[Cfg::KS], sf[Cfg::KS][Cfg::DT];
+    frag8 qf[Cfg::KS], sf[Cfg::KS][Cfg::DT];
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
       qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
@@ -172,35 +172,35 @@ __global__ __launch_bounds__(C * 4) void fwd_bidir_apply_bf16(
 //   dqh^T = S dO^T (over d_value),  dkh^T = G V^T (over d_value),  (k G)^T = G^T k^T (over
 //   d_key), then dq_i = s r_i (dqh_i - qh_i (qh_i . dqh_i)), dk_j likewise, dv_j = s r_j (k_j G).
 template <int D, int C>
-__global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
-    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, const float* __restrict__ s_totals,
+__global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
+    const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
+    const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
+    e16_t* __restrict__ dK, e16_t* __restrict__ dV, const float* __restrict__ s_totals,
     const float* __restrict__ g_totals, int slots, int n_sum, const float* __restrict__ ds_partial,
     int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps,
     const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
-  __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // Kh^T V,  [d_key][d_value]
-  __shared__ __attribute__((aligned(16))) bf16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
+  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // Kh^T V,  [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
   __shared__ float rq[C], rk[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* Qu = Q + ubase;
-  const bf16_t* Ku = K + ubase;
-  const bf16_t* Vu = V + ubase;
-  const bf16_t* Gu = dO + ubase;
-  bf16_t* dQu = dQ + ubase;
-  bf16_t* dKu = dK + ubase;
-  bf16_t* dVu = dV + ubase;
+  const e16_t* Qu = Q + ubase;
+  const e16_t* Ku = K + ubase;
+  const e16_t* Vu = V + ubase;
+  const e16_t* Gu = dO + ubase;
+  e16_t* dQu = dQ + ubase;
+  e16_t* dKu = dK + ubase;
+  e16_t* dVu = dV + ubase;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -265,9 +265,9 @@ __global__ __launch_bounds__(C * 4) void bwd_bidir_apply_bf16(
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
       const int off = (16 * w + r) * PITCH + 32 * ks + 8 * q4;
-      const bf16x8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off),
+      const frag8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off),
                    kf = lds_row_frag(Ks + off);
-      bf16x8 srow[Cfg::DT], grow[Cfg::DT], gcol[Cfg::DT];
+      frag8 srow[Cfg::DT], grow[Cfg::DT], gcol[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
         const int soff = (16 * nt + r) * PITCH + 32 * ks + 8 * q4;
@@ -323,7 +323,7 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
   using Cfg = BiCfg<D, C>;
   const int units = a.B * a.H;
   float* totals = static_cast<float*>(a.workspace);
-  hipError_t err = launch_segment_totals_bf16(totals_args(a, a.K, a.V, totals));
+  hipError_t err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.K, a.V, totals));
   if (err != hipSuccess) return err;
   // few segments: the apply workgroups add the totals up themselves (and write `state`)
   const bool sum_in_apply = a.G <= kMaxSegmentsSummedInScan;
@@ -331,9 +331,9 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
     err = launch_bidir_combine(totals, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
     if (err != hipSuccess) return err;
   }
-  return launch_kernel("fwd_bidir_apply_bf16", fwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q), a.s,
-                       static_cast<bf16_t*>(a.O), totals, a.G, sum_in_apply ? a.G : 1,
+  return launch_kernel(COTTN_SYM_STR(fwd_bidir_apply), COTTN_SYM(fwd_bidir_apply)<D, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q), a.s,
+                       static_cast<e16_t*>(a.O), totals, a.G, sum_in_apply ? a.G : 1,
                        sum_in_apply ? a.state : nullptr, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
                        a.seq_len, a.s_per_unit);
 }
@@ -357,39 +357,41 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
     // the same kernel forms the share <S, G_segment> of ds
     SegmentTotalsArgs t = totals_args(a, a.Q, a.dO, g_totals);
     t.dot_with = a.saved_fwd_states; t.dot_slots = a.G; t.dot_out = ds_partial;
-    err = launch_segment_totals_bf16(t);
+    err = COTTN_SYM(launch_segment_totals)(t);
     if (err != hipSuccess) return err;
     s_src = a.saved_fwd_states;
     n_sum = a.G;
     n_ds = a.G;
   } else {
-    err = launch_segment_totals_bf16(totals_args(a, a.K, a.V, s_totals));
+    err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.K, a.V, s_totals));
     if (err != hipSuccess) return err;
-    err = launch_segment_totals_bf16(totals_args(a, a.Q, a.dO, g_totals));
+    err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.Q, a.dO, g_totals));
     if (err != hipSuccess) return err;
     err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
                                a.stream);
     if (err != hipSuccess) return err;
     n_ds = D * D / 256;  // the combine kernel's partial sums per (batch, head)
   }
-  return launch_kernel("bwd_bidir_apply_bf16", bwd_bidir_apply_bf16<D, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, static_cast<const bf16_t*>(a.Q),
-                       static_cast<const bf16_t*>(a.K), static_cast<const bf16_t*>(a.V),
-                       static_cast<const bf16_t*>(a.dO), a.s, static_cast<bf16_t*>(a.dQ),
-                       static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV), s_src, g_totals, a.G,
+  return launch_kernel(COTTN_SYM_STR(bwd_bidir_apply), COTTN_SYM(bwd_bidir_apply)<D, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q),
+                       static_cast<const e16_t*>(a.K), static_cast<const e16_t*>(a.V),
+                       static_cast<const e16_t*>(a.dO), a.s, static_cast<e16_t*>(a.dQ),
+                       static_cast<e16_t*>(a.dK), static_cast<e16_t*>(a.dV), s_src, g_totals, a.G,
                        n_sum, ds_partial, n_ds, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
                        a.seq_len, a.s_per_unit);
 }
 
 }  // namespace
 
+#ifndef COTTN_ELEM_F16  // not specific to the element type: defined once, by the bf16 build
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st) {
   return launch_kernel("bidir_combine", bidir_combine, dim3(elems / 256, units), dim3(256), 0, st,
                        totals, pair_stride, n_pairs, G, elems, state, ds_partial);
 }
+#endif
 
-hipError_t fwd_bidir_bf16(const CausalArgs& a) {
+hipError_t COTTN_SYM(fwd_bidir)(const CausalArgs& a) {
   switch (a.d) {
     case 32: return run_fwd_bidir<32>(a);
     case 64: return run_fwd_bidir<64>(a);
@@ -398,7 +400,7 @@ hipError_t fwd_bidir_bf16(const CausalArgs& a) {
   }
 }
 
-hipError_t bwd_bidir_bf16(const CausalArgs& a) {
+hipError_t COTTN_SYM(bwd_bidir)(const CausalArgs& a) {
   switch (a.d) {
     case 32: return run_bwd_bidir<32>(a);
     case 64: return run_bwd_bidir<64>(a);

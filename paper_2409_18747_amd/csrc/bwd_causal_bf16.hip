@@ -70,12 +70,12 @@ struct BwdCfg {
 };
 
 // pack a masked accumulator tile into half of an operand fragment
-__device__ __forceinline__ void put_half(bf16x8& frag, int half, f32x4 acc, bool k0, bool k1,
+__device__ __forceinline__ void put_half(frag8& frag, int half, f32x4 acc, bool k0, bool k1,
                                          bool k2, bool k3) {
-  frag[4 * half + 0] = static_cast<__bf16>(k0 ? acc[0] : 0.f);
-  frag[4 * half + 1] = static_cast<__bf16>(k1 ? acc[1] : 0.f);
-  frag[4 * half + 2] = static_cast<__bf16>(k2 ? acc[2] : 0.f);
-  frag[4 * half + 3] = static_cast<__bf16>(k3 ? acc[3] : 0.f);
+  frag[4 * half + 0] = static_cast<elem_native>(k0 ? acc[0] : 0.f);
+  frag[4 * half + 1] = static_cast<elem_native>(k1 ? acc[1] : 0.f);
+  frag[4 * half + 2] = static_cast<elem_native>(k2 ? acc[2] : 0.f);
+  frag[4 * half + 3] = static_cast<elem_native>(k3 ? acc[3] : 0.f);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -115,9 +115,9 @@ __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_t
 // write to the transposed LDS copy St[d_value][d_key]; the update's row-side operand is the
 // K fragment already read for the intra-chunk product.
 template <int D, int C>
-__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_scan_bf16(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dQ,
+__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dq_scan)(
+    const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
+    const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
     const float* __restrict__ fwd_states, float* __restrict__ rev_totals,
     float* __restrict__ ds_partial, int H, int N, int G, int seg_rows, float inv_eps,
     int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
@@ -125,15 +125,15 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // qh = r_i q_i
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
-  __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
-  __shared__ __attribute__((aligned(16))) bf16_t St[Cfg::STATE];  // state, [d_value][d_key]
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // qh = r_i q_i
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // r_j v_j
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
+  __shared__ __attribute__((aligned(16))) e16_t St[Cfg::STATE];  // state, [d_value][d_key]
   // Every wave reads all rows of all four tiles until the end of a chunk (the reverse total
   // contracts Qs and Gs over the tokens), so finished dQ rows are staged in a tile of their
   // own when LDS has room for one; otherwise behind a barrier in the dead dO tile.
-  __shared__ __attribute__((aligned(16))) bf16_t Os[Cfg::DQ_OWN_STAGE ? Cfg::TILE : 8];
+  __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::DQ_OWN_STAGE ? Cfg::TILE : 8];
   __shared__ float rq[C];
   __shared__ float ds_wave[Cfg::NW];
 
@@ -141,11 +141,11 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* Qu = Q + ubase;
-  const bf16_t* Ku = K + ubase;
-  const bf16_t* Vu = V + ubase;
-  const bf16_t* Gu = dO + ubase;
-  bf16_t* dQu = dQ + ubase;
+  const e16_t* Qu = Q + ubase;
+  const e16_t* Ku = K + ubase;
+  const e16_t* Vu = V + ubase;
+  const e16_t* Gu = dO + ubase;
+  e16_t* dQu = dQ + ubase;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -193,8 +193,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y) {
           uint2 pk;
-          pk.x = pack_bf16(sacc[x][y][0], sacc[x][y][1]);
-          pk.y = pack_bf16(sacc[x][y][2], sacc[x][y][3]);
+          pk.x = pack2(sacc[x][y][0], sacc[x][y][1]);
+          pk.y = pack2(sacc[x][y][2], sacc[x][y][3]);
           *reinterpret_cast<uint2*>(St + (16 * AT::col_tile(w, x) + r) * PITCH +
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     __syncthreads();
 
     // earlier chunks: dqh^T += S dO^T (contraction over d_value = rows of St)
-    bf16x8 gf[Cfg::KS];  // dO rows of this wave: column-side operand of every product
+    frag8 gf[Cfg::KS];  // dO rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
       gf[ks] = lds_row_frag(Gs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      bf16x8 sf[Cfg::DT];
+      frag8 sf[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
         sf[nt] = lds_col_frag(St, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
@@ -245,8 +245,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_below = 2 * p <= w;
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the A slots
-      bf16x8 kc[Cfg::DT], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KS];
-      bf16x8 qcol[AT::NCT], grow[AT::NRT];
+      frag8 kc[Cfg::DT], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KS];
+      frag8 qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) kc[nt] = lds_col_frag(Ks, PITCH, t0, t1, 16 * nt, r);
 #pragma unroll
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
-        bf16x8 af;
+        frag8 af;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const int jt = 2 * p + half;
@@ -356,33 +356,33 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dq_sc
 // copy Rl[d_key][d_value]; the update's row-side operand is the dO fragment already read
 // for the intra-chunk dV product.
 template <int D, int C>
-__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_scan_bf16(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ dO, const float* __restrict__ s, bf16_t* __restrict__ dK,
-    bf16_t* __restrict__ dV, const float* __restrict__ rev_states,
+__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dkdv_scan)(
+    const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
+    const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dK,
+    e16_t* __restrict__ dV, const float* __restrict__ rev_states,
     const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H, int N, int G,
     int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // r_i q_i
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // raw v
-  __shared__ __attribute__((aligned(16))) bf16_t Gs[Cfg::TILE];   // dO
-  __shared__ __attribute__((aligned(16))) bf16_t Rl[Cfg::STATE];  // reverse state, [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // r_i q_i
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
+  __shared__ __attribute__((aligned(16))) e16_t Rl[Cfg::STATE];  // reverse state, [d_key][d_value]
   __shared__ float rk[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* Qu = Q + ubase;
-  const bf16_t* Ku = K + ubase;
-  const bf16_t* Vu = V + ubase;
-  const bf16_t* Gu = dO + ubase;
-  bf16_t* dKu = dK + ubase;
-  bf16_t* dVu = dV + ubase;
+  const e16_t* Qu = Q + ubase;
+  const e16_t* Ku = K + ubase;
+  const e16_t* Vu = V + ubase;
+  const e16_t* Gu = dO + ubase;
+  e16_t* dKu = dK + ubase;
+  e16_t* dVu = dV + ubase;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -440,8 +440,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y) {
           uint2 pk;
-          pk.x = pack_bf16(racc[x][y][0], racc[x][y][1]);
-          pk.y = pack_bf16(racc[x][y][2], racc[x][y][3]);
+          pk.x = pack2(racc[x][y][0], racc[x][y][1]);
+          pk.y = pack2(racc[x][y][2], racc[x][y][3]);
           *reinterpret_cast<uint2*>(Rl + (16 * AT::col_tile(w, x) + r) * PITCH +
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     }
     __syncthreads();
 
-    bf16x8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows (column side)
+    frag8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows (column side)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
       kf[ks] = lds_row_frag(Ks + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     // later chunks: dv^T += R^T k^T (over d_key), dkh^T += R v^T (over d_value)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      bf16x8 rcol[Cfg::DT], rrow[Cfg::DT];
+      frag8 rcol[Cfg::DT], rrow[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
         rcol[nt] = lds_col_frag(Rl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
@@ -505,7 +505,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_above = 2 * p + 1 >= w;
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the slots
-      bf16x8 gc[Cfg::DT], qcol[AT::NCT], grow[AT::NRT];
+      frag8 gc[Cfg::DT], qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) gc[nt] = lds_col_frag(Gs, PITCH, t0, t1, 16 * nt, r);
 #pragma unroll
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
             racc[x][y] = mma16(AT::WPC == 1 ? gc[y] : grow[y], qcol[x], racc[x][y]);
       }
       if (diag_or_above) {
-        bf16x8 qr[2][Cfg::KS], gr[2][Cfg::KS], qc[Cfg::DT];
+        frag8 qr[2][Cfg::KS], gr[2][Cfg::KS], qc[Cfg::DT];
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -538,7 +538,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void bwd_dkdv_
 #pragma unroll
         for (int nt = 0; nt < Cfg::DT; ++nt) qc[nt] = lds_col_frag(Qs, PITCH, t0, t1, 16 * nt, r);
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 pf, af;
+        frag8 pf, af;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const int it = 2 * p + half;
@@ -609,10 +609,10 @@ template <int D, int C>
 hipError_t run_bwd_causal(const CausalArgs& a) {
   using Cfg = BwdCfg<D, C>;
   const int units = a.B * a.H;
-  const bf16_t* Q = static_cast<const bf16_t*>(a.Q);
-  const bf16_t* K = static_cast<const bf16_t*>(a.K);
-  const bf16_t* V = static_cast<const bf16_t*>(a.V);
-  const bf16_t* dO = static_cast<const bf16_t*>(a.dO);
+  const e16_t* Q = static_cast<const e16_t*>(a.Q);
+  const e16_t* K = static_cast<const e16_t*>(a.K);
+  const e16_t* V = static_cast<const e16_t*>(a.V);
+  const e16_t* dO = static_cast<const e16_t*>(a.dO);
   char* ws = static_cast<char*>(a.workspace);
   const float* fwd_states = nullptr;
   float* rev_states = nullptr;
@@ -630,7 +630,7 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
     if (a.saved_fwd_states != nullptr) {
       fwd_states = a.saved_fwd_states;
     } else {
-      err = launch_fwd_segment_totals_bf16(a, own_fwd);
+      err = COTTN_SYM(launch_fwd_segment_totals)(a, own_fwd);
       if (err != hipSuccess) return err;
       if (!sum_in_scan) {
         err = launch_bwd_state_carry(own_fwd, nullptr, units, a.G, D * D, a.stream);
@@ -641,8 +641,8 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   }
   float* ds_partial = reinterpret_cast<float*>(ws);
   // the dQ scan leaves the reverse-time segment totals (of qh^T dO) behind for the dK/dV scan
-  err = launch_kernel("bwd_dq_scan_bf16", bwd_dq_scan_bf16<D, C>, grid, block, 0, a.stream, Q, K, V,
-                      dO, a.s, static_cast<bf16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
+  err = launch_kernel(COTTN_SYM_STR(bwd_dq_scan), COTTN_SYM(bwd_dq_scan)<D, C>, grid, block, 0, a.stream, Q, K, V,
+                      dO, a.s, static_cast<e16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
                       a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
   if (err != hipSuccess) return err;
   if (a.G > 1 && !sum_in_scan) {
@@ -650,14 +650,15 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
     if (err != hipSuccess) return err;
   }
   // the dK/dV kernel also reduces the ds partial sums written by the dQ kernel
-  return launch_kernel("bwd_dkdv_scan_bf16", bwd_dkdv_scan_bf16<D, C>, grid, block, 0, a.stream, Q,
-                       K, V, dO, a.s, static_cast<bf16_t*>(a.dK), static_cast<bf16_t*>(a.dV),
+  return launch_kernel(COTTN_SYM_STR(bwd_dkdv_scan), COTTN_SYM(bwd_dkdv_scan)<D, C>, grid, block, 0, a.stream, Q,
+                       K, V, dO, a.s, static_cast<e16_t*>(a.dK), static_cast<e16_t*>(a.dV),
                        rev_states, ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
 }
 
 }  // namespace
 
+#ifndef COTTN_ELEM_F16  // not specific to the element type: defined once, by the bf16 build
 hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
                                   hipStream_t st) {
   const long total = long(units) * elems;
@@ -670,8 +671,9 @@ hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G
   return launch_kernel("bwd_reduce_ds", bwd_reduce_ds, dim3(per_unit ? B * H : H), dim3(256), 0, st,
                        partial, ds, B, H, G, per_unit);
 }
+#endif
 
-hipError_t bwd_causal_bf16(const CausalArgs& a) {
+hipError_t COTTN_SYM(bwd_causal)(const CausalArgs& a) {
   switch (a.d * 1000 + a.C) {
     case 32064: return run_bwd_causal<32, 64>(a);
     case 32128: return run_bwd_causal<32, 128>(a);

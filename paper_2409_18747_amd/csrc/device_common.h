@@ -1,20 +1,33 @@
-// Device-side primitives shared by the gfx950 kernels: vector types, the bf16 MFMA
-// wrapper, LDS fragment reads (plain and transposing), bf16 packing, lane reductions.
+// Device-side primitives shared by the gfx950 kernels: vector types, the 16-bit MFMA
+// wrapper, LDS fragment reads (plain and transposing), packing, lane reductions.
 // Nothing in here knows about attention.
+//
+// The MFMA kernels are written once for a 16-bit floating-point element and compiled twice:
+// bfloat16 by default, IEEE half when the translation unit defines COTTN_ELEM_F16 before
+// including anything (the *_f16.hip files do exactly that and then include the kernel
+// source).  COTTN_SYM(name) appends the element's suffix to kernel and launcher names.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace cottn {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+#ifdef COTTN_ELEM_F16
+typedef _Float16 elem_native;  // the compiler's type for one element
+#define COTTN_SYM(name) name##_f16
+#define COTTN_SYM_STR(name) #name "_f16"
+#else
+typedef __bf16 elem_native;
+#define COTTN_SYM(name) name##_bf16
+#define COTTN_SYM_STR(name) #name "_bf16"
+#endif
+typedef __attribute__((ext_vector_type(8))) elem_native frag8;  // one MFMA operand fragment
+typedef __attribute__((ext_vector_type(2))) elem_native elem2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef uint16_t bf16_t;  // storage type of bf16 data in global memory and LDS
+typedef uint16_t e16_t;  // storage type of a 16-bit element in global memory and LDS
 
 #define COTTN_LDS __attribute__((address_space(3)))
 
@@ -25,34 +38,38 @@ typedef uint16_t bf16_t;  // storage type of bf16 data in global memory and LDS
 #define COTTN_TRACE_POINT(i)
 #endif
 
-// Row pitch (in elements) of a bf16 LDS tile with `cols` columns: 8 extra elements (16 B)
+// Row pitch (in elements) of a 16-bit LDS tile with `cols` columns: 8 extra elements (16 B)
 // shift consecutive rows by 4 banks, which makes both the 16-byte row reads of 16 rows and
 // the 8-byte transposing reads conflict-free.
 __host__ __device__ constexpr int lds_pitch(int cols) { return cols + 8; }
 
-// D(16x16) += A(16x32) * B(32x16), bf16 in, fp32 accumulate.
+// D(16x16) += A(16x32) * B(32x16), 16-bit elements in, fp32 accumulate.
 // Lane l = 16*g + r holds  A[row r][k = 8g..8g+7],  B[k = 8g..8g+7][col r],
 // and D[row 4g+v][col r] in acc[v].  The order of the k slots is free as long as A and B
 // use the same one, which several kernels exploit to feed an accumulator tile straight
 // back in as an operand.
-__device__ __forceinline__ f32x4 mma16(bf16x8 a, bf16x8 b, f32x4 acc) {
+__device__ __forceinline__ f32x4 mma16(frag8 a, frag8 b, f32x4 acc) {
+#ifdef COTTN_ELEM_F16
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+#else
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+#endif
 }
 
-__device__ __forceinline__ bf16x8 zero_frag() {
+__device__ __forceinline__ frag8 zero_frag() {
   s16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-  return __builtin_bit_cast(bf16x8, z);
+  return __builtin_bit_cast(frag8, z);
 }
 
 // Operand fragment whose k index runs along an LDS row: 8 consecutive elements.
-__device__ __forceinline__ bf16x8 lds_row_frag(const bf16_t* p) {
-  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+__device__ __forceinline__ frag8 lds_row_frag(const e16_t* p) {
+  return __builtin_bit_cast(frag8, *reinterpret_cast<const uint4*>(p));
 }
 
 // Transposing 8-byte LDS read (gfx950): inside each group of 16 lanes, lane i passes the
 // address of 4 consecutive elements, taken as row i/4, columns 4*(i%4).. of a 4x16 block;
 // it receives column i of the block's 4 rows.
-__device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
+__device__ __forceinline__ s16x4 lds_read_tr(const e16_t* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((COTTN_LDS s16x4*)(p));
 }
 
@@ -60,41 +77,61 @@ __device__ __forceinline__ s16x4 lds_read_tr(const bf16_t* p) {
 // elements): the lane with r = lane%16 receives tile[k0 + 0..3][col0 + r] and
 // tile[k1 + 0..3][col0 + r].  k0/k1 are the first rows of the two 4-row groups that
 // fill this lane's 8 k slots.
-__device__ __forceinline__ bf16x8 lds_col_frag(const bf16_t* tile, int pitch, int k0, int k1,
+__device__ __forceinline__ frag8 lds_col_frag(const e16_t* tile, int pitch, int k0, int k1,
                                                int col0, int r) {
   const int sub_row = r >> 2, sub_col = (r & 3) * 4;
   s16x4 lo = lds_read_tr(tile + (k0 + sub_row) * pitch + col0 + sub_col);
   s16x4 hi = lds_read_tr(tile + (k1 + sub_row) * pitch + col0 + sub_col);
   s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, v);
+  return __builtin_bit_cast(frag8, v);
 }
 
-__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+// element <-> fp32; to_e16 rounds to nearest even
+__device__ __forceinline__ float from_e16(e16_t b) {
+#ifdef COTTN_ELEM_F16
+  return float(__builtin_bit_cast(_Float16, b));
+#else
   return __builtin_bit_cast(float, uint32_t(b) << 16);
+#endif
 }
-// round to nearest even
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f));
+__device__ __forceinline__ e16_t to_e16(float f) {
+  return __builtin_bit_cast(e16_t, static_cast<elem_native>(f));
 }
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return uint32_t(f32_to_bf16(lo)) | (uint32_t(f32_to_bf16(hi)) << 16);
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  return uint32_t(to_e16(lo)) | (uint32_t(to_e16(hi)) << 16);
+}
+// the two elements of a 32-bit word (low half first)
+__device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+#ifdef COTTN_ELEM_F16
+  const elem2 p = __builtin_bit_cast(elem2, w);
+  lo = float(p[0]);
+  hi = float(p[1]);
+#else
+  lo = __builtin_bit_cast(float, w << 16);
+  hi = __builtin_bit_cast(float, w & 0xFFFF0000u);
+#endif
+}
+// fp32 sum of squares of the two elements of a word, added to acc
+__device__ __forceinline__ float dot2_self(uint32_t w, float acc) {
+  const elem2 p = __builtin_bit_cast(elem2, w);
+#ifdef COTTN_ELEM_F16
+  return __builtin_amdgcn_fdot2(p, p, acc, false);
+#else
+  return __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
+#endif
 }
 __device__ __forceinline__ void unpack8(uint4 raw, float* f) {
-  f[0] = __builtin_bit_cast(float, raw.x << 16);
-  f[1] = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
-  f[2] = __builtin_bit_cast(float, raw.y << 16);
-  f[3] = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
-  f[4] = __builtin_bit_cast(float, raw.z << 16);
-  f[5] = __builtin_bit_cast(float, raw.z & 0xFFFF0000u);
-  f[6] = __builtin_bit_cast(float, raw.w << 16);
-  f[7] = __builtin_bit_cast(float, raw.w & 0xFFFF0000u);
+  unpack2(raw.x, f[0], f[1]);
+  unpack2(raw.y, f[2], f[3]);
+  unpack2(raw.z, f[4], f[5]);
+  unpack2(raw.w, f[6], f[7]);
 }
 __device__ __forceinline__ uint4 pack8(const float* f) {
   uint4 r;
-  r.x = pack_bf16(f[0], f[1]);
-  r.y = pack_bf16(f[2], f[3]);
-  r.z = pack_bf16(f[4], f[5]);
-  r.w = pack_bf16(f[6], f[7]);
+  r.x = pack2(f[0], f[1]);
+  r.y = pack2(f[2], f[3]);
+  r.z = pack2(f[4], f[5]);
+  r.w = pack2(f[6], f[7]);
   return r;
 }
 
@@ -146,7 +183,7 @@ __device__ __forceinline__ float unit_scale(const float* __restrict__ s, int uni
 }
 // Zeros rows row_lo..row_hi-1 of a [.][D] tensor of 2-byte elements (whole workgroup).
 template <int D>
-__device__ __forceinline__ void zero_rows_bf16(bf16_t* __restrict__ dst, int row_lo, int row_hi) {
+__device__ __forceinline__ void zero_rows_bf16(e16_t* __restrict__ dst, int row_lo, int row_hi) {
   const long pieces = long(max(0, row_hi - row_lo)) * (D / 8);
   uint4* p = reinterpret_cast<uint4*>(dst + size_t(row_lo) * D);
   for (long i = threadIdx.x; i < pieces; i += blockDim.x) p[i] = uint4{0u, 0u, 0u, 0u};

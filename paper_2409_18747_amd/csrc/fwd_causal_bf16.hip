@@ -95,24 +95,24 @@ template <> struct FwdSplit<32, 64> { static constexpr int CS = 2; };
 // segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
 // also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
 template <int D, int C>
-__global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
-    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, float* __restrict__ seg_state,
+__global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
+    const e16_t* __restrict__ K, const e16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
     const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out,
     const int* __restrict__ seq_len, int H) {
   using Cfg = FwdCfg<D, C>;
   using ST = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];
   __shared__ float dot_wave[Cfg::NW];
 
   const int unit = blockIdx.x / n_slots, g = blockIdx.x % n_slots;
   if (g >= n_compute) return;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const bf16_t* Ku = K + size_t(unit) * N * D;
-  const bf16_t* Vu = V + size_t(unit) * N * D;
+  const e16_t* Ku = K + size_t(unit) * N * D;
+  const e16_t* Vu = V + size_t(unit) * N * D;
   const int row_begin = g * seg_rows;
   const int row_end = min(valid_rows(seq_len, unit, H, N), row_begin + seg_rows);
 
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(C * 4) void fwd_segment_state_bf16(
 #pragma unroll
       for (int p = 0; p < Cfg::NP; ++p) {
         const int k0 = 32 * p + 8 * q4;
-        bf16x8 bv[ST::NCT], ak[ST::NRT];
+        frag8 bv[ST::NCT], ak[ST::NRT];
 #pragma unroll
         for (int x = 0; x < ST::NCT; ++x)
           bv[x] = lds_col_frag(Vs, Cfg::PITCH, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
@@ -226,9 +226,9 @@ __global__ __launch_bounds__(256) void fwd_state_carry(float* __restrict__ seg_s
 // value side is that half.  Per-wave work and registers shrink; the workgroup has twice the
 // waves to cover latencies with.
 template <int D, int C, int CS>
-__global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS>())) void fwd_causal_scan_bf16(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const float* __restrict__ s, bf16_t* __restrict__ O, float* __restrict__ state_out,
+__global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS>())) void COTTN_SYM(fwd_causal_scan)(
+    const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
+    const float* __restrict__ s, e16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
     int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = FwdCfg<D, C>;
@@ -237,12 +237,12 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   using ST = SplitTiles<D, RG, CS>;
   using Stage = TileStage<D, C, Cfg::NT * CS>;
   constexpr int PITCH = Cfg::PITCH;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[Cfg::TILE];   // raw q rows
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[Cfg::TILE];   // raw k rows
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[Cfg::TILE];   // r_j v_j
-  __shared__ __attribute__((aligned(16))) bf16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q rows
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k rows
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // r_j v_j
+  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
   // with two waves on a row group the q rows stay live in the other wave: own staging tile
-  __shared__ __attribute__((aligned(16))) bf16_t Os[CS > 1 ? Cfg::TILE : 8];
+  __shared__ __attribute__((aligned(16))) e16_t Os[CS > 1 ? Cfg::TILE : 8];
   __shared__ float rq[C];
 
   COTTN_TRACE_POINT(7);
@@ -251,10 +251,10 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
             r = l % 16, q4 = l / 16;
   const int rg = w % RG, cp = w / RG;  // row group, column part
   const size_t ubase = size_t(unit) * N * D;
-  const bf16_t* Qu = Q + ubase;
-  const bf16_t* Ku = K + ubase;
-  const bf16_t* Vu = V + ubase;
-  bf16_t* Ou = O + ubase;
+  const e16_t* Qu = Q + ubase;
+  const e16_t* Ku = K + ubase;
+  const e16_t* Vu = V + ubase;
+  e16_t* Ou = O + ubase;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   RowPieces<D, NOT> finished;  // output rows of the previous chunk, stored one chunk late
 #pragma unroll
   for (int j = 0; j < RowPieces<D, NOT>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
-  bf16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * PITCH;
+  e16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * PITCH;
   const int col0 = 16 * NOT * cp;  // first output column of this wave
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     COTTN_TRACE_POINT(0);
@@ -320,8 +320,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y) {
           uint2 pk;
-          pk.x = pack_bf16(sacc[x][y][0], sacc[x][y][1]);
-          pk.y = pack_bf16(sacc[x][y][2], sacc[x][y][3]);
+          pk.x = pack2(sacc[x][y][0], sacc[x][y][1]);
+          pk.y = pack2(sacc[x][y][2], sacc[x][y][3]);
           *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(rg, cp, x) + r) * PITCH +
                                     16 * ST::row_tile(rg, cp, y) + 4 * q4) = pk;
         }
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     COTTN_TRACE_POINT(3);
 
     // ---- inter-chunk part: O^T += S^T Q^T (contraction over d_key = rows of Sl)
-    bf16x8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
+    frag8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
       qf[ks] = lds_row_frag(Qs + (16 * rg + r) * PITCH + 32 * ks + 8 * q4);
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     for (int nt = 0; nt < NOT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      bf16x8 sf[NOT];
+      frag8 sf[NOT];
 #pragma unroll
       for (int nt = 0; nt < NOT; ++nt)
         sf[nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, col0 + 16 * nt, r);
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       // k slot (q4, e) of the P fragment is token 32p + 16*(e/4) + 4*q4 + e%4; V and K are
       // read down their rows in the same order
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
-      bf16x8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
+      frag8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
 #pragma unroll
       for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, PITCH, t0, t1, col0 + 16 * nt, r);
 #pragma unroll
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
-        bf16x8 pf;
+        frag8 pf;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const int jt = 2 * p + half;
@@ -407,7 +407,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const bool keep = (jt < rg) || (jt == rg && 4 * q4 + v <= r);
-            pf[4 * half + v] = static_cast<__bf16>(keep ? pacc[v] : 0.f);
+            pf[4 * half + v] = static_cast<elem_native>(keep ? pacc[v] : 0.f);
           }
         }
 #pragma unroll
@@ -455,16 +455,16 @@ template <int D, int C>
 hipError_t run_fwd_causal(const CausalArgs& a) {
   using Cfg = FwdCfg<D, C>;
   const int units = a.B * a.H;
-  const bf16_t* Q = static_cast<const bf16_t*>(a.Q);
-  const bf16_t* K = static_cast<const bf16_t*>(a.K);
-  const bf16_t* V = static_cast<const bf16_t*>(a.V);
+  const e16_t* Q = static_cast<const e16_t*>(a.Q);
+  const e16_t* K = static_cast<const e16_t*>(a.K);
+  const e16_t* V = static_cast<const e16_t*>(a.V);
   float* ws = static_cast<float*>(a.workspace);  // [units][G][D][D] when G > 1
   const float inv_eps = 1.0f / a.eps;
   hipError_t err = hipSuccess;
   // few segments: no carry launch, each scan workgroup adds up the totals before its segment
   const bool sum_in_scan = a.G <= kMaxSegmentsSummedInScan;
   if (a.G > 1) {
-    err = launch_fwd_segment_totals_bf16(a, ws);
+    err = COTTN_SYM(launch_fwd_segment_totals)(a, ws);
     if (err != hipSuccess) return err;
     if (!sum_in_scan) {
       err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
@@ -472,8 +472,8 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
     }
   }
   constexpr int CS = FwdSplit<D, C>::CS;
-  return launch_kernel("fwd_causal_scan_bf16", fwd_causal_scan_bf16<D, C, CS>, dim3(units * a.G),
-                       dim3(Cfg::NT * CS), 0, a.stream, Q, K, V, a.s, static_cast<bf16_t*>(a.O), a.state,
+  return launch_kernel(COTTN_SYM_STR(fwd_causal_scan), COTTN_SYM(fwd_causal_scan)<D, C, CS>, dim3(units * a.G),
+                       dim3(Cfg::NT * CS), 0, a.stream, Q, K, V, a.s, static_cast<e16_t*>(a.O), a.state,
                        a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
 }
@@ -482,8 +482,8 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 
 template <int D>
 static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
-  const bf16_t* X = static_cast<const bf16_t*>(t.X);
-  const bf16_t* Y = static_cast<const bf16_t*>(t.Y);
+  const e16_t* X = static_cast<const e16_t*>(t.X);
+  const e16_t* Y = static_cast<const e16_t*>(t.Y);
   const float inv_eps = 1.0f / t.eps;
   // The totals kernel takes the largest row tile that does not exceed the segment: with
   // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
@@ -491,19 +491,19 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   const dim3 grid(t.units * t.G);
   constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
   if (t.seg_rows >= TOP)
-    return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, TOP>, grid,
+    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, TOP>, grid,
                          dim3(4 * TOP), 0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows,
                          inv_eps, t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
   if (t.seg_rows >= 128)
-    return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 128>, grid, dim3(512),
+    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, 128>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
                          t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
-  return launch_kernel("fwd_segment_state_bf16", fwd_segment_state_bf16<D, 64>, grid, dim3(256), 0,
+  return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, 64>, grid, dim3(256), 0,
                        t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
                        t.dot_slots, t.dot_out, t.seq_len, t.H);
 }
 
-hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t) {
+hipError_t COTTN_SYM(launch_segment_totals)(const SegmentTotalsArgs& t) {
   switch (t.d) {
     case 32: return run_segment_totals<32>(t);
     case 64: return run_segment_totals<64>(t);
@@ -512,22 +512,24 @@ hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t) {
   }
 }
 
-hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst) {
+hipError_t COTTN_SYM(launch_fwd_segment_totals)(const CausalArgs& a, float* dst) {
   SegmentTotalsArgs t{};
   t.X = a.K; t.Y = a.V; t.dst = dst;
   t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G - 1;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
   t.seq_len = a.seq_len; t.H = a.H;
-  return launch_segment_totals_bf16(t);
+  return COTTN_SYM(launch_segment_totals)(t);
 }
 
+#ifndef COTTN_ELEM_F16  // not specific to the element type: defined once, by the bf16 build
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {
   const long total = long(units) * elems;
   return launch_kernel("fwd_state_carry", fwd_state_carry, dim3(unsigned((total + 255) / 256)),
                        dim3(256), 0, st, seg_state, G, elems, total);
 }
+#endif
 
-hipError_t fwd_causal_bf16(const CausalArgs& a) {
+hipError_t COTTN_SYM(fwd_causal)(const CausalArgs& a) {
   switch (a.d * 1000 + a.C) {
     case 32064: return run_fwd_causal<32, 64>(a);
     case 32128: return run_fwd_causal<32, 128>(a);

@@ -1,0 +1,4 @@
+// The fwd causal kernels for IEEE half-precision elements: the same source as the bfloat16 build,
+// compiled with the element type switched (see device_common.h).
+#define COTTN_ELEM_F16
+#include "fwd_causal_bf16.hip"

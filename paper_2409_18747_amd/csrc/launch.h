@@ -46,6 +46,10 @@ hipError_t fwd_causal_bf16(const CausalArgs& a);
 hipError_t bwd_causal_bf16(const CausalArgs& a);
 hipError_t fwd_bidir_bf16(const CausalArgs& a);
 hipError_t bwd_bidir_bf16(const CausalArgs& a);
+hipError_t fwd_causal_f16(const CausalArgs& a);
+hipError_t bwd_causal_f16(const CausalArgs& a);
+hipError_t fwd_bidir_f16(const CausalArgs& a);
+hipError_t bwd_bidir_f16(const CausalArgs& a);
 hipError_t fwd_causal_f32(const CausalArgs& a);
 hipError_t bwd_causal_f32(const CausalArgs& a);
 hipError_t fwd_bidir_f32(const CausalArgs& a);
@@ -60,6 +64,7 @@ hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int
 // bf16 segment totals of Kh^T V for all segments but the last, [units][G][d][d] fp32 in `dst`
 // (the first kernel of the causal forward, also used by a backward without saved states)
 hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
+hipError_t launch_fwd_segment_totals_f16(const CausalArgs& a, float* dst);
 
 // The same kernel in general: dst[unit][g] = sum over the rows of segment g of N(X)^T Y for
 // g < n_compute (G slots per unit).  With dot_with (stored totals of another d x d matrix,
@@ -74,6 +79,7 @@ struct SegmentTotalsArgs {
   hipStream_t stream;
 };
 hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t);
+hipError_t launch_segment_totals_f16(const SegmentTotalsArgs& t);
 // ds[h] = sum over batches b and j < n of partial[(b H + h) n + j]; per_unit: ds[b][h] instead
 hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int n, int per_unit,
                             hipStream_t st);

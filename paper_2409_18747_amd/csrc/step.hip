@@ -13,25 +13,15 @@
 namespace cottn {
 namespace {
 
-template <typename T> struct Elem;
-template <> struct Elem<float> {
-  static __device__ __forceinline__ float load(const float* p) { return *p; }
-  static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
-  static __device__ __forceinline__ float4 load4(const float* p) {
-    return *reinterpret_cast<const float4*>(p);
-  }
-};
-template <> struct Elem<bf16_t> {
-  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
-  static __device__ __forceinline__ void store(bf16_t* p, float x) { *p = f32_to_bf16(x); }
-  static __device__ __forceinline__ float4 load4(const bf16_t* p) {
-    const uint2 raw = *reinterpret_cast<const uint2*>(p);
-    float4 r;
-    r.x = __builtin_bit_cast(float, raw.x << 16);
-    r.y = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
-    r.z = __builtin_bit_cast(float, raw.y << 16);
-    r.w = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
-    return r;
+// q, k, v, o elements: float, or one of the two 16-bit types (converted with the compiler's
+// round-to-nearest-even casts)
+template <typename T> struct Elem {
+  typedef __attribute__((ext_vector_type(4))) T vec4;
+  static __device__ __forceinline__ float load(const T* p) { return float(*p); }
+  static __device__ __forceinline__ void store(T* p, float x) { *p = static_cast<T>(x); }
+  static __device__ __forceinline__ float4 load4(const T* p) {
+    const vec4 raw = *reinterpret_cast<const vec4*>(p);
+    return float4{float(raw[0]), float(raw[1]), float(raw[2]), float(raw[3])};
   }
 };
 
@@ -149,7 +139,7 @@ hipError_t run_step(const StepArgs& a) {
 }  // namespace
 
 hipError_t step_any(const StepArgs& a, int dtype) {
-  return dtype == 0 ? run_step<float>(a) : run_step<bf16_t>(a);
+  return dtype == 0 ? run_step<float>(a) : dtype == 1 ? run_step<__bf16>(a) : run_step<_Float16>(a);
 }
 
 }  // namespace cottn

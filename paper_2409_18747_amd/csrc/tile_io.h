@@ -27,10 +27,10 @@ struct TileStage {
   uint4 regs[PASSES];
 
   // rows >= n_rows (end of the sequence or of the segment) read as zero
-  __device__ __forceinline__ void fetch(const bf16_t* __restrict__ base, int row0, int n_rows) {
+  __device__ __forceinline__ void fetch(const e16_t* __restrict__ base, int row0, int n_rows) {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;
-    const bf16_t* p0 = base + size_t(row0) * D + (tid / LPR) * D + col;
+    const e16_t* p0 = base + size_t(row0) * D + (tid / LPR) * D + col;
     if (C % RPP == 0 && row0 + C <= n_rows) {
       // whole tile in range (workgroup-uniform): plain loads at constant strides
 #pragma unroll
@@ -56,8 +56,7 @@ struct TileStage {
       const uint32_t w[4] = {regs[p].x, regs[p].y, regs[p].z, regs[p].w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const bf16x2 pair = __builtin_bit_cast(bf16x2, w[e]);
-        ss = __builtin_amdgcn_fdot2_f32_bf16(pair, pair, ss, false);
+        ss = dot2_self(w[e], ss);
       }
       ss = group_sum<LPR>(ss);
       rinv[p] = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
@@ -76,14 +75,14 @@ struct TileStage {
 
   // tile[lr][:] = row / max(||row||, eps) rounded to bf16; rinv_out[lr] (may be null) = that
   // factor.  For the places that need the normalised rows themselves as an operand.
-  __device__ __forceinline__ void commit_normalised(bf16_t* tile, float eps, float* rinv_out) const {
+  __device__ __forceinline__ void commit_normalised(e16_t* tile, float eps, float* rinv_out) const {
     float rinv[PASSES];
     row_rinv(1.0f / eps, rinv);
     commit_scaled(tile, rinv);
     if (rinv_out != nullptr) store_rinv(rinv_out, rinv);
   }
 
-  __device__ __forceinline__ void commit_plain(bf16_t* tile) const {
+  __device__ __forceinline__ void commit_plain(e16_t* tile) const {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;
 #pragma unroll
@@ -94,7 +93,7 @@ struct TileStage {
   }
 
   // tile[lr][:] = scale[p] * row, rounded to bf16
-  __device__ __forceinline__ void commit_scaled(bf16_t* tile, const float* scale) const {
+  __device__ __forceinline__ void commit_scaled(e16_t* tile, const float* scale) const {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;
 #pragma unroll
@@ -201,7 +200,7 @@ struct RowPieces {
 // with 8-byte writes and reads it back as 16-byte pieces.
 template <int D, int NTILES = D / 16>
 __device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float row_factor,
-                                                       bf16_t* stage_rows, int l,
+                                                       e16_t* stage_rows, int l,
                                                        RowPieces<D, NTILES>& out, int col0 = 0) {
   using RP = RowPieces<D, NTILES>;
   constexpr int PITCH = lds_pitch(D);
@@ -209,8 +208,8 @@ __device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float r
 #pragma unroll
   for (int nt = 0; nt < NTILES; ++nt) {
     uint2 pk;
-    pk.x = pack_bf16(row_factor * acc[nt][0], row_factor * acc[nt][1]);
-    pk.y = pack_bf16(row_factor * acc[nt][2], row_factor * acc[nt][3]);
+    pk.x = pack2(row_factor * acc[nt][0], row_factor * acc[nt][1]);
+    pk.y = pack2(row_factor * acc[nt][2], row_factor * acc[nt][3]);
     *reinterpret_cast<uint2*>(stage_rows + r * PITCH + col0 + 16 * nt + 4 * q4) = pk;
   }
   wave_lds_sync();
@@ -229,7 +228,7 @@ __device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float r
 // outstanding memory operation, and must not find stores that were issued a moment ago.
 template <int D, int NTILES = D / 16>
 __device__ __forceinline__ void store_row_pieces(const RowPieces<D, NTILES>& p,
-                                                 bf16_t* __restrict__ dst, int first_row,
+                                                 e16_t* __restrict__ dst, int first_row,
                                                  int row_end, int l, int col0 = 0) {
   using RP = RowPieces<D, NTILES>;
 #pragma unroll
@@ -245,7 +244,7 @@ __device__ __forceinline__ void store_row_pieces(const RowPieces<D, NTILES>& p,
 // Both at once, for the kernels that do not defer their stores.
 template <int D>
 __device__ __forceinline__ void store_rows_transposed(const f32x4* acc, float row_factor,
-                                                      bf16_t* stage_rows, bf16_t* __restrict__ dst,
+                                                      e16_t* stage_rows, e16_t* __restrict__ dst,
                                                       int first_row, int row_end, int l) {
   RowPieces<D> p;
   gather_rows_transposed<D>(acc, row_factor, stage_rows, l, p);
@@ -267,7 +266,7 @@ __device__ __forceinline__ float sum_over_lane_rows(float x) {
 // then across the four lane rows) and replaces acc by dxh - xh (xh . dxh)  (no projection
 // for rows at or below eps).  Returns xh . dxh.
 template <int D, bool NORMALISED>
-__device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_rows, float rinv,
+__device__ __forceinline__ float project_out_row(f32x4* acc, const e16_t* x_rows, float rinv,
                                                  float inv_eps, int r, int q4) {
   constexpr int DT = D / 16, PITCH = lds_pitch(D);
   float xv[DT][4];
@@ -275,10 +274,8 @@ __device__ __forceinline__ float project_out_row(f32x4* acc, const bf16_t* x_row
 #pragma unroll
   for (int nt = 0; nt < DT; ++nt) {
     const uint2 raw = *reinterpret_cast<const uint2*>(x_rows + r * PITCH + 16 * nt + 4 * q4);
-    xv[nt][0] = __builtin_bit_cast(float, raw.x << 16);
-    xv[nt][1] = __builtin_bit_cast(float, raw.x & 0xFFFF0000u);
-    xv[nt][2] = __builtin_bit_cast(float, raw.y << 16);
-    xv[nt][3] = __builtin_bit_cast(float, raw.y & 0xFFFF0000u);
+    unpack2(raw.x, xv[nt][0], xv[nt][1]);
+    unpack2(raw.y, xv[nt][2], xv[nt][3]);
 #pragma unroll
     for (int v = 0; v < 4; ++v) t += xv[nt][v] * acc[nt][v];
   }

@@ -22,7 +22,7 @@ class Workload:
     H: int
     N: int
     d: int
-    dtype: str          # "f32" or "bf16": storage type of Q, K, V, O and the gradients
+    dtype: str          # "f32", "bf16" or "f16": storage type of Q, K, V, O and the gradients
     causal: bool
     backward: bool
     seed: int
@@ -70,9 +70,12 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "bf16":
         return round_to_bf16(x)
+    if dtype == "f16":
+        # numpy's float16 conversion rounds to nearest even; back to float32 is exact
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
     if dtype == "f32":
         return np.ascontiguousarray(x, dtype=np.float32)
-    raise ValueError("dtype must be 'f32' or 'bf16'")
+    raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
 
 
 def draw(B, H, N, d, dtype="f32", seed=0, value_scale=1.0, with_dO=True):

@@ -100,7 +100,8 @@ def test_workspace_sizes(lib):
     (0, 1, 1, 8, 64, 32, BF16),     # bf16 chunk must be 64/128/256
     (0, 1, 1, 8, 128, 128, BF16),   # d = 128 supports chunk 64 only
     (0, 1, 1, 8, 64, 64, F32),      # fp32 chunk must be 32
-    (0, 1, 1, 8, 64, 0, 2),         # dtype
+    (0, 1, 1, 8, 64, 0, 3),         # dtype
+    (0, 1, 1, 8, 64, 32, 2),        # fp16 follows the bf16 chunk rules
     (7, 1, 1, 8, 64, 0, BF16),      # op
 ])
 def test_unsupported_arguments_have_no_size(lib, args):
