@@ -20,10 +20,10 @@
 //
 // Normalisation factors r_i = 1/max(|q_i|, eps), r_j = 1/max(|k_j|, eps) are not applied to
 // Q and K element-wise where a row factor does the same:
-//   dQ pass    V is rescaled to r_j v_j on its way into LDS (then A_ij r_j = dO_i . (r_j v_j)
-//              and S = sum k_j^T (r_j v_j)); K stays raw; Q is only needed normalised (for
-//              the chain rule below and for the reverse-time total) and is stored as qh;
-//              dqh_i = sum_j A'_ij k_j + dO_i S^T;
+//   dQ pass    K is contracted over the token index everywhere and is stored as kh = r_j k_j;
+//              V stays raw; Q is only needed normalised (for the chain rule below and for
+//              the reverse-time total) and is stored as qh;
+//              dqh_i = sum_j A_ij kh_j + dO_i S^T,  S = sum kh_j^T v_j;
 //   dK/dV pass Q is rescaled to r_i q_i (it is contracted over the token index in the
 //              reverse state R = sum (r_i q_i)^T dO_i); K and V stay raw;
 //              dv_j = s r_j [ sum_i ((r_i q_i).k_j) dO_i + k_j R ],
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
   using Stage = TileStage<D, C, Cfg::NT>;
   constexpr int PITCH = Cfg::PITCH;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // qh = r_i q_i
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // r_j v_j
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
   __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
   __shared__ __attribute__((aligned(16))) e16_t St[Cfg::STATE];  // state, [d_value][d_key]
   // Every wave reads all rows of all four tiles until the end of a chunk (the reverse total
@@ -205,8 +205,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       kst.row_rinv(inv_eps, rkv);
       qst.commit_scaled(Qs, rqv);
       qst.store_rinv(rq, rqv);
-      kst.commit_plain(Ks);
-      vst.commit_scaled(Vs, rkv);
+      kst.commit_scaled(Ks, rkv);
+      vst.commit_plain(Vs);
       gst.commit_plain(Gs);
     }
     if (row0 + C < row_end) {
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // this chunk: dqh^T += K^T (A' (.) M)^T with A'^T = (r v) dO^T, and the state update,
+    // this chunk: dqh^T += Kh^T (A (.) M)^T with A^T = V dO^T, and the state update,
     // 32 tokens at a time
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks) t = mma16(vr[half][ks], gf[ks], t);
-          // t[v] = dO_(16w + r) . (r v)_(16jt + 4 q4 + v); keep key <= query
+          // t[v] = dO_(16w + r) . v_(16jt + 4 q4 + v); keep key <= query
           const bool full = jt < w, diag = jt == w;
           put_half(af, half, t, full || (diag && 4 * q4 + 0 <= r), full || (diag && 4 * q4 + 1 <= r),
                    full || (diag && 4 * q4 + 2 <= r), full || (diag && 4 * q4 + 3 <= r));
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
 #pragma unroll
         for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(kc[nt], af, dq[nt]);
       }
-      // state update: S += k^T (r v) over these 32 tokens
+      // state update: S += kh^T v over these 32 tokens
       if (AT::active(w)) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)

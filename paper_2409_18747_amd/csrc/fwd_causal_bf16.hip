@@ -13,11 +13,10 @@
 // With G = 1 only the scan kernel runs; with one chunk per segment this is the fully
 // chunk-parallel form.
 //
-// Normalisation (Sec. 3.2) without touching Q and K element-wise: with r_i = 1/max(|q_i|,eps)
-// and r_j = 1/max(|k_j|,eps),
-//     O_i = s_h r_i [ sum_{j<=i} (q_i . k_j) (r_j v_j) + q_i S ],   S = sum_j k_j^T (r_j v_j),
-// so the raw Q and K rows are the MFMA operands, V is rescaled by r_j on its way into LDS,
-// and r_i multiplies the finished output row.
+// Normalisation (Sec. 3.2): with r_i = 1/max(|q_i|,eps) and kh_j = k_j / max(|k_j|,eps),
+//     O_i = s_h r_i [ sum_{j<=i} (q_i . kh_j) v_j + q_i S ],   S = sum_j kh_j^T v_j,
+// so the raw Q rows are an MFMA operand and r_i multiplies the finished output row, while K,
+// which is contracted over the token index in S, is rescaled to kh on its way into LDS.
 //
 // Work split inside the scan workgroup (C/16 waves): wave w owns query rows 16w..16w+15 of
 // the chunk for the output, and a fixed set of 16x16 tiles of the state for the update.
@@ -130,8 +129,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     float rk[Stage::PASSES];
     kst.row_rinv(inv_eps, rk);
     __syncthreads();  // previous chunk's reads of Ks/Vs are done
-    kst.commit_plain(Ks);
-    vst.commit_scaled(Vs, rk);
+    kst.commit_scaled(Ks, rk);
+    vst.commit_plain(Vs);
     if (row0 + C < row_end) {
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
@@ -238,8 +237,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   using Stage = TileStage<D, C, Cfg::NT * CS>;
   constexpr int PITCH = Cfg::PITCH;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q rows
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k rows
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // r_j v_j
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v rows
   __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
   // with two waves on a row group the q rows stay live in the other wave: own staging tile
   __shared__ __attribute__((aligned(16))) e16_t Os[CS > 1 ? Cfg::TILE : 8];
@@ -332,8 +331,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       kst.row_rinv(inv_eps, rk);
       qst.commit_plain(Qs);
       qst.store_rinv(rq, rqv);
-      kst.commit_plain(Ks);
-      vst.commit_scaled(Vs, rk);
+      kst.commit_scaled(Ks, rk);
+      vst.commit_plain(Vs);
     }
     COTTN_TRACE_POINT(1);
     if (row0 + C < row_end) {
@@ -413,7 +412,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
 #pragma unroll
         for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(vc[nt], pf, oacc[nt]);
       }
-      // state update S^T += (r v)^T k over these 32 tokens
+      // state update S^T += v^T kh over these 32 tokens
       if (ST::active(rg, cp)) {
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)

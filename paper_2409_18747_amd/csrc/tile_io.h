@@ -2,12 +2,14 @@
 // Sec. 3.2 computed on the way (sum of squares with the packed bf16 dot instruction, reduced
 // over the lanes that share a row with DPP moves).
 //
-// The normalisation x / max(||x||, eps) is never applied to Q and K element by element.
+// The normalisation x / max(||x||, eps) is applied element by element only where it must be.
 // With r_i = 1 / max(||q_i||, eps) and r_j likewise for k_j, every product of the method is
-// linear in qh_i = r_i q_i and kh_j = r_j k_j, so the kernels keep the raw rows as MFMA
-// operands and apply r_i to the rows of the result, and fold r_j into the rows of the one
-// operand that is contracted over the token index together with k_j (V in the forward and
-// dQ passes, Q itself in the dK/dV pass).  Only that one tile is rescaled element-wise.
+// linear in qh_i = r_i q_i and kh_j = r_j k_j.  Where the rows of a result belong to the
+// normalised operand's rows, the raw rows are the MFMA operand and the factor multiplies the
+// finished fp32 result row; only an operand that is contracted over the token index is
+// rescaled on its way into LDS (K in the forward and dQ passes, Q in the dK/dV pass).  A
+// rescaled row has norm at most 1, so this is safe in IEEE half precision too: no row is
+// ever multiplied by the factor of another row, which is 1/eps when that row is zero.
 #pragma once
 #include "device_common.h"
 
@@ -92,7 +94,7 @@ struct TileStage {
     }
   }
 
-  // tile[lr][:] = scale[p] * row, rounded to bf16
+  // tile[lr][:] = scale[p] * row, rounded to the element type
   __device__ __forceinline__ void commit_scaled(e16_t* tile, const float* scale) const {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;

@@ -118,3 +118,44 @@ def test_padded_batch(cottn, oracle):
     for got, want in zip(g[:3], ref[:3]):
         assert rel_err(to_host(got), want) <= TOL["f16"]
     assert rel_err(to_host(g[3]), ref[3]) <= 4 * TOL["f16"]
+
+
+@pytest.mark.parametrize("eps", [1e-6, 1e-3])
+def test_zero_norm_rows(cottn, oracle, eps):
+    """Key and query rows that are exactly zero (padding by zeroed rows, Sec. 4) while their
+    value rows are not: every other row must come out finite and right, which requires that no
+    row is ever multiplied by a zero row's factor 1/eps inside the kernels (fp16 would
+    overflow).  The gradient of a zero row itself is 1/eps times a quantity of order one (the
+    derivative of x/max(|x|, eps) at the clamp): representable in fp16 only for the larger
+    eps; with the default eps those rows overflow fp16 storage and are left out."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    B, H, N, d = 2, 2, 200, 64
+    x = workloads.draw(B, H, N, d, "f16", 870)
+    zero_k, zero_q = [5, 70, 71, 199], [64]
+    x["K"][:, :, zero_k] = 0.0
+    x["Q"][:, :, zero_q] = 0.0
+    Q, K, V, dO = (to_device(x[k], "f16") for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    cottn.cottn_tune_segments(2)
+    for causal in (True, False):
+        if causal:
+            O = cottn.cottn_fwd_causal(Q, K, V, s, eps=eps)
+            g = cottn.cottn_bwd_causal(Q, K, V, s, dO, eps=eps)
+        else:
+            O = cottn.cottn_fwd_bidir(Q, K, V, s, eps=eps)
+            g = cottn.cottn_bwd_bidir(Q, K, V, s, dO, eps=eps)
+        torch.cuda.synchronize()
+        O_ref = oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"], eps=eps, causal=causal)
+        ref = [t.copy() for t in
+               oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], eps=eps, causal=causal)]
+        got = [to_host(t).copy() for t in g]
+        if eps < 1e-4:   # (1/eps) * O(1) is beyond fp16's largest finite value
+            for t in (got[0], ref[0]):
+                t[:, :, zero_q] = 0.0
+            for t in (got[1], ref[1]):
+                t[:, :, zero_k] = 0.0
+        assert rel_err(to_host(O), O_ref) <= TOL["f16"]
+        for name, a, b in zip(("dQ", "dK", "dV"), got, ref):
+            assert np.isfinite(a).all(), (causal, name)
+            assert rel_err(a, b) <= TOL["f16"], (causal, name)
