@@ -37,9 +37,12 @@ struct BiCfg {
   static constexpr int NT = NW * 64;
   static constexpr int DT = D / 16;
   static constexpr int KS = D / 32;
-  static constexpr int PITCH = lds_pitch(D);
-  static constexpr int TILE = C * PITCH;
-  static constexpr int STATE = D * PITCH;
+  static constexpr int TP = tile_pitch(D, C);   // operand tiles
+  // the d x d matrices are written once per workgroup and then only read, as row fragments
+  // too: they take the operand tiles' pitch
+  static constexpr int SP = tile_pitch(D, C);
+  static constexpr int TILE = C * TP;
+  static constexpr int STATE = D * SP;
 };
 
 // Slot 0 of each pair <- sum over g of the slots, one matrix element per thread (grid:
@@ -71,12 +74,11 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
   }
 }
 
-// dst (LDS, bf16, row-major [D][D] with the tile pitch) <- sum of the first n_sum of the
+// dst (LDS, bf16, row-major [D][D] with row pitch SP) <- sum of the first n_sum of the
 // [D][D] fp32 matrices at src; the fp32 sum also goes to `copy` when that is not null.
-template <int D, int NT>
+template <int D, int NT, int SP>
 __device__ __forceinline__ void stage_summed_matrix(e16_t* dst, const float* __restrict__ src,
                                                     int n_sum, float* __restrict__ copy) {
-  constexpr int PITCH = lds_pitch(D);
   for (int e = 4 * threadIdx.x; e < D * D; e += 4 * NT) {
     f32x4 a = *reinterpret_cast<const f32x4*>(src + e);
     for (int j = 1; j < n_sum; ++j) {
@@ -88,7 +90,7 @@ __device__ __forceinline__ void stage_summed_matrix(e16_t* dst, const float* __r
     uint2 pk;
     pk.x = pack2(a[0], a[1]);
     pk.y = pack2(a[2], a[3]);
-    *reinterpret_cast<uint2*>(dst + (e / D) * PITCH + e % D) = pk;
+    *reinterpret_cast<uint2*>(dst + (e / D) * SP + e % D) = pk;
   }
 }
 
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
     int G, int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int PITCH = Cfg::PITCH;
+  constexpr int TP = Cfg::TP, SP = Cfg::SP;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
   __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // [d_key][d_value]
   __shared__ float rq[C];
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
 
   Stage qst;
   qst.fetch(Qu, row_begin, row_end);
-  stage_summed_matrix<D, Cfg::NT>(Sl, totals + size_t(unit) * slots * D * D, n_sum,
+  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Sl, totals + size_t(unit) * slots * D * D, n_sum,
                                   (state != nullptr && g == 0) ? state + size_t(unit) * D * D
                                                                : nullptr);
 
@@ -144,10 +146,10 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
     frag8 qf[Cfg::KS], sf[Cfg::KS][Cfg::DT];
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      qf[ks] = lds_row_frag(Qs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
+      qf[ks] = lds_row_frag(Qs + (16 * w + r) * TP + 32 * ks + 8 * q4);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
-        sf[ks][nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+        sf[ks][nt] = lds_col_frag(Sl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
     }
     __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
     __builtin_amdgcn_sched_barrier(0);
     const float row_factor = scale * rq[16 * w + r];
     wave_lds_sync();  // this wave's reads of its Qs rows precede the staging writes
-    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * PITCH, l, finished);
+    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * TP, l, finished);
     __syncthreads();
   }
   if (row_begin < row_end) {
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<D, C>;
   using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int PITCH = Cfg::PITCH;
+  constexpr int TP = Cfg::TP, SP = Cfg::SP;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];
@@ -222,8 +224,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     t = group_sum<64>(t);
     if (l == 0) ds[blockIdx.x] = t;
   }
-  stage_summed_matrix<D, Cfg::NT>(Sl, s_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
-  stage_summed_matrix<D, Cfg::NT>(Gl, g_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
+  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Sl, s_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
+  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Gl, g_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
 
   RowPieces<D> done_q, done_k, done_v;  // rows of the previous chunk, stored one chunk late
 #pragma unroll
@@ -264,16 +266,16 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     }
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      const int off = (16 * w + r) * PITCH + 32 * ks + 8 * q4;
+      const int off = (16 * w + r) * TP + 32 * ks + 8 * q4;
       const frag8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off),
                    kf = lds_row_frag(Ks + off);
       frag8 srow[Cfg::DT], grow[Cfg::DT], gcol[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
-        const int soff = (16 * nt + r) * PITCH + 32 * ks + 8 * q4;
+        const int soff = (16 * nt + r) * SP + 32 * ks + 8 * q4;
         srow[nt] = lds_row_frag(Sl + soff);
         grow[nt] = lds_row_frag(Gl + soff);
-        gcol[nt] = lds_col_frag(Gl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+        gcol[nt] = lds_col_frag(Gl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       }
       __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
@@ -287,12 +289,12 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     // every tile row is private to its wave here: chain rule on the raw rows, then the
     // results are staged in place (dO rows for dQ, K rows for dK, V rows for dV)
     const float ri = rq[16 * w + r], rj = rk[16 * w + r];
-    project_out_row<D, false>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
-    project_out_row<D, false>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
+    project_out_row<D, TP, false>(dq, Qs + 16 * w * TP, ri, inv_eps, r, q4);
+    project_out_row<D, TP, false>(dk, Ks + 16 * w * TP, rj, inv_eps, r, q4);
     wave_lds_sync();  // own rows of Gs, Ks, Vs were read before the staging writes
-    gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, l, done_q);
-    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, l, done_k);
-    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, l, done_v);
+    gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * TP, l, done_q);
+    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * TP, l, done_k);
+    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * TP, l, done_v);
     __syncthreads();
   }
   if (row_begin < row_end) {

@@ -55,9 +55,10 @@ struct BwdCfg {
   static constexpr int DT = D / 16;
   static constexpr int KS = D / 32;
   static constexpr int NP = C / 32;
-  static constexpr int PITCH = lds_pitch(D);
-  static constexpr int TILE = C * PITCH;
-  static constexpr int STATE = D * PITCH;
+  static constexpr int TP = tile_pitch(D, C);   // operand tiles
+  static constexpr int SP = lds_pitch(D);    // state copies
+  static constexpr int TILE = C * TP;
+  static constexpr int STATE = D * SP;
   static constexpr int LDS_BYTES = 2 * (4 * TILE + STATE) + 4 * C + 64;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
   // the dQ kernel adds a staging tile when that does not lower the workgroups per compute unit
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int PITCH = Cfg::PITCH;
+  constexpr int TP = Cfg::TP, SP = Cfg::SP;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // qh = r_i q_i
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           uint2 pk;
           pk.x = pack2(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack2(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(St + (16 * AT::col_tile(w, x) + r) * PITCH +
+          *reinterpret_cast<uint2*>(St + (16 * AT::col_tile(w, x) + r) * SP +
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
     }
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     frag8 gf[Cfg::KS];  // dO rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
-      gf[ks] = lds_row_frag(Gs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
+      gf[ks] = lds_row_frag(Gs + (16 * w + r) * TP + 32 * ks + 8 * q4);
     // dq[nt][v] = dqh[query 16w + r][key feature 16 nt + 4 q4 + v]
     f32x4 dq[Cfg::DT];
 #pragma unroll
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       frag8 sf[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt)
-        sf[nt] = lds_col_frag(St, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+        sf[nt] = lds_col_frag(St, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(sf[nt], gf[ks], dq[nt]);
@@ -248,29 +249,29 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       frag8 kc[Cfg::DT], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KS];
       frag8 qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) kc[nt] = lds_col_frag(Ks, PITCH, t0, t1, 16 * nt, r);
+      for (int nt = 0; nt < Cfg::DT; ++nt) kc[nt] = lds_col_frag(Ks, TP, t0, t1, 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
-        vcol[x] = lds_col_frag(Vs, PITCH, t0, t1, 16 * AT::col_tile(w, x), r);
+        vcol[x] = lds_col_frag(Vs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
       if (AT::WPC != 1) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
-          krow[y] = lds_col_frag(Ks, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
+          krow[y] = lds_col_frag(Ks, TP, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       if (with_rev && AT::active(w)) {
 #pragma unroll
         for (int x = 0; x < AT::NCT; ++x)
-          qcol[x] = lds_col_frag(Qs, PITCH, t0, t1, 16 * AT::col_tile(w, x), r);
+          qcol[x] = lds_col_frag(Qs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
-          grow[y] = lds_col_frag(Gs, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
+          grow[y] = lds_col_frag(Gs, TP, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks)
-            vr[half][ks] = lds_row_frag(Vs + (16 * (2 * p + half) + r) * PITCH + 32 * ks + 8 * q4);
+            vr[half][ks] = lds_row_frag(Vs + (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
@@ -309,13 +310,13 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
 
     // epilogue: normalisation chain rule on the rows (Qs holds qh), then s r_i and the store
     const float ri = rq[16 * w + r];
-    const float rho = project_out_row<D, true>(dq, Qs + 16 * w * PITCH, ri, inv_eps, r, q4);
+    const float rho = project_out_row<D, TP, true>(dq, Qs + 16 * w * TP, ri, inv_eps, r, q4);
     if (q4 == 0) ds_lane += rho;
     if (Cfg::DQ_OWN_STAGE) {
-      gather_rows_transposed<D>(dq, scale * ri, Os + 16 * w * PITCH, l, finished);
+      gather_rows_transposed<D>(dq, scale * ri, Os + 16 * w * TP, l, finished);
     } else {
       __syncthreads();  // every wave is done with the dO tile
-      gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * PITCH, l, finished);
+      gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * TP, l, finished);
     }
     __syncthreads();
   }
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int PITCH = Cfg::PITCH;
+  constexpr int TP = Cfg::TP, SP = Cfg::SP;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // r_i q_i
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
@@ -442,7 +443,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           uint2 pk;
           pk.x = pack2(racc[x][y][0], racc[x][y][1]);
           pk.y = pack2(racc[x][y][2], racc[x][y][3]);
-          *reinterpret_cast<uint2*>(Rl + (16 * AT::col_tile(w, x) + r) * PITCH +
+          *reinterpret_cast<uint2*>(Rl + (16 * AT::col_tile(w, x) + r) * SP +
                                     16 * AT::row_tile(w, y) + 4 * q4) = pk;
         }
     }
@@ -471,8 +472,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     frag8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows (column side)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks) {
-      kf[ks] = lds_row_frag(Ks + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
-      vf[ks] = lds_row_frag(Vs + (16 * w + r) * PITCH + 32 * ks + 8 * q4);
+      kf[ks] = lds_row_frag(Ks + (16 * w + r) * TP + 32 * ks + 8 * q4);
+      vf[ks] = lds_row_frag(Vs + (16 * w + r) * TP + 32 * ks + 8 * q4);
     }
     // dk[nt][v] = dkh[key 16w + r][feature 16 nt + 4 q4 + v]; dv likewise before s r_j
     f32x4 dk[Cfg::DT], dv[Cfg::DT];
@@ -488,8 +489,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       frag8 rcol[Cfg::DT], rrow[Cfg::DT];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DT; ++nt) {
-        rcol[nt] = lds_col_frag(Rl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
-        rrow[nt] = lds_row_frag(Rl + (16 * nt + r) * PITCH + 32 * ks + 8 * q4);
+        rcol[nt] = lds_col_frag(Rl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+        rrow[nt] = lds_row_frag(Rl + (16 * nt + r) * SP + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -507,14 +508,14 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the slots
       frag8 gc[Cfg::DT], qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) gc[nt] = lds_col_frag(Gs, PITCH, t0, t1, 16 * nt, r);
+      for (int nt = 0; nt < Cfg::DT; ++nt) gc[nt] = lds_col_frag(Gs, TP, t0, t1, 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
-        qcol[x] = lds_col_frag(Qs, PITCH, t0, t1, 16 * AT::col_tile(w, x), r);
+        qcol[x] = lds_col_frag(Qs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
       if (AT::WPC != 1) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
-          grow[y] = lds_col_frag(Gs, PITCH, t0, t1, 16 * AT::row_tile(w, y), r);
+          grow[y] = lds_col_frag(Gs, TP, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       __builtin_amdgcn_sched_barrier(0);
       // reverse state update: R^T += dO^T (r q) over these 32 tokens
@@ -531,12 +532,12 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
         for (int half = 0; half < 2; ++half)
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks) {
-            const int off = (16 * (2 * p + half) + r) * PITCH + 32 * ks + 8 * q4;
+            const int off = (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4;
             qr[half][ks] = lds_row_frag(Qs + off);
             gr[half][ks] = lds_row_frag(Gs + off);
           }
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) qc[nt] = lds_col_frag(Qs, PITCH, t0, t1, 16 * nt, r);
+        for (int nt = 0; nt < Cfg::DT; ++nt) qc[nt] = lds_col_frag(Qs, TP, t0, t1, 16 * nt, r);
         __builtin_amdgcn_sched_barrier(0);
         frag8 pf, af;
 #pragma unroll
@@ -567,10 +568,10 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     // epilogue: dv_j = s r_j dv; dk_j through the normalisation chain rule; both staged in
     // this wave's own (dead) rows of Vs and Ks
     const float rj = rk[16 * w + r];
-    project_out_row<D, false>(dk, Ks + 16 * w * PITCH, rj, inv_eps, r, q4);
+    project_out_row<D, TP, false>(dk, Ks + 16 * w * TP, rj, inv_eps, r, q4);
     wave_lds_sync();  // own Ks / Vs rows (kf, vf, raw k) were read before the staging writes
-    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * PITCH, l, done_k);
-    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * PITCH, l, done_v);
+    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * TP, l, done_k);
+    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * TP, l, done_v);
     __syncthreads();
   }
   if (n_chunks > 0) {

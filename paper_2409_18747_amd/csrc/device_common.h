@@ -38,10 +38,26 @@ typedef uint16_t e16_t;  // storage type of a 16-bit element in global memory an
 #define COTTN_TRACE_POINT(i)
 #endif
 
-// Row pitch (in elements) of a 16-bit LDS tile with `cols` columns: 8 extra elements (16 B)
-// shift consecutive rows by 4 banks, which makes both the 16-byte row reads of 16 rows and
-// the 8-byte transposing reads conflict-free.
+// Row pitches (in elements) of 16-bit LDS arrays.  The LDS moves 64 lanes x 16 bytes in 4
+// cycles and 64 x 8 bytes in 2.4 at best (4 for a transposing read of rows that are 8 apart);
+// how the 64 addresses of an instruction fall into banks decides whether it gets there.
+// Measured on gfx950 with every access pattern of these kernels (cycles per wave instruction,
+// 16 waves issuing; the same at d = 32, 64, 128):
+//                                         pitch = cols + 8        pitch = cols + 16
+//   16-byte row fragments (16 rows)            8.0                     4.1
+//   transposing reads over the tokens          4.1                     2.4
+//   8-byte writes / reads of 4 cols of a row   8.0 / 2.4              16.0 / 4.1
+//   16-byte pieces read back row by row        8.0                    12.0
+//   (16-byte writes cost 13 and transposing reads of a state 4.1 with either.)
+// So the [rows][cols] operand tiles (read as row fragments and token-column fragments) use
+// cols + 16 (unless four such tiles and a state copy would not fit the 160 KB of a compute
+// unit: 256-row chunks at d = 64), the state copies and the staging of finished rows
+// (8-byte writes) cols + 8.
 __host__ __device__ constexpr int lds_pitch(int cols) { return cols + 8; }
+__host__ __device__ constexpr int tile_pitch(int cols, int rows) {
+  return 2 * (4 * rows * (cols + 16) + cols * lds_pitch(cols)) + 1024 <= 160 * 1024 ? cols + 16
+                                                                                  : cols + 8;
+}
 
 // D(16x16) += A(16x32) * B(32x16), 16-bit elements in, fp32 accumulate.
 // Lane l = 16*g + r holds  A[row r][k = 8g..8g+7],  B[k = 8g..8g+7][col r],

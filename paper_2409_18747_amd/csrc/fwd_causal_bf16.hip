@@ -49,9 +49,10 @@ struct FwdCfg {
   static constexpr int DT = D / 16;
   static constexpr int KS = D / 32;     // k steps of a contraction over the feature dim
   static constexpr int NP = C / 32;     // pairs of 16-token tiles in a chunk
-  static constexpr int PITCH = lds_pitch(D);
-  static constexpr int TILE = C * PITCH;            // elements of one [C][D] LDS tile
-  static constexpr int STATE = D * PITCH;           // elements of the [D][D] bf16 state copy
+  static constexpr int TP = tile_pitch(D, C);   // operand tiles
+  static constexpr int SP = lds_pitch(D);    // state copies
+  static constexpr int TILE = C * TP;            // elements of one [C][D] LDS tile
+  static constexpr int STATE = D * SP;           // elements of the [D][D] bf16 state copy
   static constexpr int LDS_BYTES = 2 * (3 * TILE + STATE) + 4 * C;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
   // waves per SIMD the register allocation is capped for (two workgroups per compute unit
@@ -143,10 +144,10 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
         frag8 bv[ST::NCT], ak[ST::NRT];
 #pragma unroll
         for (int x = 0; x < ST::NCT; ++x)
-          bv[x] = lds_col_frag(Vs, Cfg::PITCH, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
+          bv[x] = lds_col_frag(Vs, Cfg::TP, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
-          ak[y] = lds_col_frag(Ks, Cfg::PITCH, k0, k0 + 4, 16 * ST::row_tile(w, y), r);
+          ak[y] = lds_col_frag(Ks, Cfg::TP, k0, k0 + 4, 16 * ST::row_tile(w, y), r);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   constexpr int NOT = Cfg::DT / CS;    // output column tiles per wave
   using ST = SplitTiles<D, RG, CS>;
   using Stage = TileStage<D, C, Cfg::NT * CS>;
-  constexpr int PITCH = Cfg::PITCH;
+  constexpr int TP = Cfg::TP, SP = Cfg::SP;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q rows
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v rows
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   RowPieces<D, NOT> finished;  // output rows of the previous chunk, stored one chunk late
 #pragma unroll
   for (int j = 0; j < RowPieces<D, NOT>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
-  e16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * PITCH;
+  e16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * TP;
   const int col0 = 16 * NOT * cp;  // first output column of this wave
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     COTTN_TRACE_POINT(0);
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
           uint2 pk;
           pk.x = pack2(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack2(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(rg, cp, x) + r) * PITCH +
+          *reinterpret_cast<uint2*>(Sl + (16 * ST::col_tile(rg, cp, x) + r) * SP +
                                     16 * ST::row_tile(rg, cp, y) + 4 * q4) = pk;
         }
     }
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     frag8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KS; ++ks)
-      qf[ks] = lds_row_frag(Qs + (16 * rg + r) * PITCH + 32 * ks + 8 * q4);
+      qf[ks] = lds_row_frag(Qs + (16 * rg + r) * TP + 32 * ks + 8 * q4);
     // oacc[nt][v] = O[query 16 rg + r][value col0 + 16 nt + 4 q4 + v] before the row factor
     f32x4 oacc[NOT];
 #pragma unroll
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       frag8 sf[NOT];
 #pragma unroll
       for (int nt = 0; nt < NOT; ++nt)
-        sf[nt] = lds_col_frag(Sl, PITCH, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, col0 + 16 * nt, r);
+        sf[nt] = lds_col_frag(Sl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, col0 + 16 * nt, r);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(sf[nt], qf[ks], oacc[nt]);
@@ -377,21 +378,21 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
       frag8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
 #pragma unroll
-      for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, PITCH, t0, t1, col0 + 16 * nt, r);
+      for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, TP, t0, t1, col0 + 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
-        kcol[x] = lds_col_frag(Ks, PITCH, t0, t1, 16 * ST::col_tile(rg, cp, x), r);
+        kcol[x] = lds_col_frag(Ks, TP, t0, t1, 16 * ST::col_tile(rg, cp, x), r);
       if (!ST::ROW_OPERAND_IS_OUTPUT_V) {
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
-          vrow[y] = lds_col_frag(Vs, PITCH, t0, t1, 16 * ST::row_tile(rg, cp, y), r);
+          vrow[y] = lds_col_frag(Vs, TP, t0, t1, 16 * ST::row_tile(rg, cp, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks)
-            kr[half][ks] = lds_row_frag(Ks + (16 * (2 * p + half) + r) * PITCH + 32 * ks + 8 * q4);
+            kr[half][ks] = lds_row_frag(Ks + (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {

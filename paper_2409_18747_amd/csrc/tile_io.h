@@ -90,7 +90,7 @@ struct TileStage {
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
-      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = regs[p];
+      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * tile_pitch(D, C) + col) = regs[p];
     }
   }
 
@@ -105,7 +105,7 @@ struct TileStage {
       unpack8(regs[p], f);
 #pragma unroll
       for (int e = 0; e < 8; ++e) f[e] *= scale[p];
-      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * lds_pitch(D) + col) = pack8(f);
+      if (C % RPP == 0 || lr < C) *reinterpret_cast<uint4*>(tile + lr * tile_pitch(D, C) + col) = pack8(f);
     }
   }
 };
@@ -198,8 +198,9 @@ struct RowPieces {
 // Turns a wave's result block whose accumulators are laid out TRANSPOSED (acc[nt][v] =
 // result[row r][column col0 + 16 nt + 4 q4 + v], i.e. each lane holds 4 consecutive columns
 // of one row) into row pieces: scales by the per-lane row factor, rounds to bf16, passes the
-// block through 16 rows of an LDS tile (columns col0.. of stage_rows, private to the wave)
-// with 8-byte writes and reads it back as 16-byte pieces.
+// block through a staging area private to the wave (16 rows of lds_pitch(D) elements from
+// stage_rows on, columns col0..; it fits the wave's 16 rows of an operand tile, whose pitch is
+// larger) with 8-byte writes and reads it back as 16-byte pieces.
 template <int D, int NTILES = D / 16>
 __device__ __forceinline__ void gather_rows_transposed(const f32x4* acc, float row_factor,
                                                        e16_t* stage_rows, int l,
@@ -263,14 +264,14 @@ __device__ __forceinline__ float sum_over_lane_rows(float x) {
 
 // Chain rule through the row normalisation on a wave's transposed 16 x D block:
 // acc[nt][v] = dxh[row r][column 16 nt + 4 q4 + v].  Reads the row from `x_rows` (the wave's
-// 16 rows of its LDS tile), which holds either the raw row x (NORMALISED = false) or
+// 16 rows of its LDS tile, row pitch PITCH), which holds either the raw row x (NORMALISED = false) or
 // xh = r x (true); forms the dot product with dxh over the whole row (16 columns per lane,
 // then across the four lane rows) and replaces acc by dxh - xh (xh . dxh)  (no projection
 // for rows at or below eps).  Returns xh . dxh.
-template <int D, bool NORMALISED>
+template <int D, int PITCH, bool NORMALISED>
 __device__ __forceinline__ float project_out_row(f32x4* acc, const e16_t* x_rows, float rinv,
                                                  float inv_eps, int r, int q4) {
-  constexpr int DT = D / 16, PITCH = lds_pitch(D);
+  constexpr int DT = D / 16;
   float xv[DT][4];
   float t = 0.f;
 #pragma unroll
