@@ -1,5 +1,6 @@
-// Bidirectional cosine attention, forward and backward, bf16 storage / bf16 MFMA / fp32
-// accumulation (gfx950).
+// Bidirectional cosine attention, forward and backward, 16-bit storage / 16-bit MFMA / fp32
+// accumulation (gfx950).  Written for a 16-bit element type: this file builds the bfloat16
+// kernels, and the IEEE half ones when it is included with COTTN_ELEM_F16 defined.
 //
 // Sec. 4 eq. subQuadCos: without a mask the product reassociates to O = s_h Qh (Kh^T V), so
 // the d x d matrix S = Kh^T V is reduced once over the whole sequence and then applied to
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
     store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
   }
-  if (seq_len != nullptr) zero_rows_bf16<D>(Ou, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<D>(Ou, row_end, seg_end);  // rows that do not exist
 }
 
 // dQ, dK, dV rows of one segment; the first H workgroups also finish ds from the n_ds
@@ -304,9 +305,9 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     store_row_pieces<D>(done_v, dVu, last + 16 * w, row_end, l);
   }
   if (seq_len != nullptr) {  // rows that do not exist
-    zero_rows_bf16<D>(dQu, row_end, seg_end);
-    zero_rows_bf16<D>(dKu, row_end, seg_end);
-    zero_rows_bf16<D>(dVu, row_end, seg_end);
+    zero_rows_e16<D>(dQu, row_end, seg_end);
+    zero_rows_e16<D>(dKu, row_end, seg_end);
+    zero_rows_e16<D>(dVu, row_end, seg_end);
   }
 }
 

@@ -1,4 +1,6 @@
-// Causal cosine attention backward, bf16 storage / bf16 MFMA / fp32 accumulation (gfx950).
+// Causal cosine attention backward, 16-bit storage / 16-bit MFMA / fp32 accumulation (gfx950).
+// Written for a 16-bit element type: this file builds the bfloat16 kernels, and the IEEE half
+// ones when it is included with COTTN_ELEM_F16 defined.
 //
 // Sec. 4 gives, for the normalised operands Qh, Kh (A = dO V^T, P = Qh Kh^T, M the
 // lower-triangular mask),
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     store_row_pieces<D>(finished, dQu, last + 16 * w, row_end, l);
   }
 
-  if (seq_len != nullptr) zero_rows_bf16<D>(dQu, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<D>(dQu, row_end, seg_end);  // rows that do not exist
 
   if (with_rev && AT::active(w)) {
     float* out = rev_totals + (size_t(unit) * G + g) * D * D;
@@ -579,8 +581,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     store_row_pieces<D>(done_v, dVu, row_begin + 16 * w, row_end, l);
   }
   if (seq_len != nullptr) {  // rows that do not exist
-    zero_rows_bf16<D>(dKu, row_end, seg_end);
-    zero_rows_bf16<D>(dVu, row_end, seg_end);
+    zero_rows_e16<D>(dKu, row_end, seg_end);
+    zero_rows_e16<D>(dVu, row_end, seg_end);
   }
 }
 

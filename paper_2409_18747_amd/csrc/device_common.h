@@ -199,7 +199,7 @@ __device__ __forceinline__ float unit_scale(const float* __restrict__ s, int uni
 }
 // Zeros rows row_lo..row_hi-1 of a [.][D] tensor of 2-byte elements (whole workgroup).
 template <int D>
-__device__ __forceinline__ void zero_rows_bf16(e16_t* __restrict__ dst, int row_lo, int row_hi) {
+__device__ __forceinline__ void zero_rows_e16(e16_t* __restrict__ dst, int row_lo, int row_hi) {
   const long pieces = long(max(0, row_hi - row_lo)) * (D / 8);
   uint4* p = reinterpret_cast<uint4*>(dst + size_t(row_lo) * D);
   for (long i = threadIdx.x; i < pieces; i += blockDim.x) p[i] = uint4{0u, 0u, 0u, 0u};

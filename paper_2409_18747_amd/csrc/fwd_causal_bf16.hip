@@ -1,4 +1,6 @@
-// Causal cosine attention forward, bf16 storage / bf16 MFMA / fp32 accumulation (gfx950).
+// Causal cosine attention forward, 16-bit storage / 16-bit MFMA / fp32 accumulation (gfx950).
+// Written for a 16-bit element type: this file builds the bfloat16 kernels, and the IEEE half
+// ones when it is included with COTTN_ELEM_F16 defined.
 //
 // Sec. 4 eq. attn_2 writes the causal output as an inclusive cumulative sum over the sequence
 // of the outer products kh_j^T v_j, contracted with qh_i.  Regrouping that sum exactly:
@@ -438,7 +440,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     store_row_pieces<D, NOT>(finished, Ou, last + 16 * rg, row_end, l, col0);
   }
 
-  if (seq_len != nullptr) zero_rows_bf16<D>(Ou, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<D>(Ou, row_end, seg_end);  // rows that do not exist
 
   if (state_out != nullptr && g == G - 1 && ST::active(rg, cp)) {
     float* out = state_out + size_t(unit) * D * D;

@@ -56,12 +56,12 @@ hipError_t fwd_bidir_f32(const CausalArgs& a);
 hipError_t bwd_bidir_f32(const CausalArgs& a);
 hipError_t step_any(const StepArgs& a, int dtype);
 
-// small fp32 state kernels shared by the bf16 and fp32 paths (defined next to their kernels)
+// small fp32 state kernels shared by the 16-bit and fp32 paths (defined next to their kernels)
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st);
 // either array may be null: then only the other one is carried
 hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
                                   hipStream_t st);
-// bf16 segment totals of Kh^T V for all segments but the last, [units][G][d][d] fp32 in `dst`
+// 16-bit paths: segment totals of Kh^T V for all segments but the last, [units][G][d][d] fp32 in `dst`
 // (the first kernel of the causal forward, also used by a backward without saved states)
 hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
 hipError_t launch_fwd_segment_totals_f16(const CausalArgs& a, float* dst);

@@ -1,5 +1,5 @@
-// Global -> register -> LDS staging of [rows][D] bf16 tiles, with the row L2 norm of
-// Sec. 3.2 computed on the way (sum of squares with the packed bf16 dot instruction, reduced
+// Global -> register -> LDS staging of [rows][D] tiles of 16-bit elements, with the row L2 norm
+// of Sec. 3.2 computed on the way (sum of squares with the packed 16-bit dot instruction, reduced
 // over the lanes that share a row with DPP moves).
 //
 // The normalisation x / max(||x||, eps) is applied element by element only where it must be.
@@ -75,7 +75,7 @@ struct TileStage {
     }
   }
 
-  // tile[lr][:] = row / max(||row||, eps) rounded to bf16; rinv_out[lr] (may be null) = that
+  // tile[lr][:] = row / max(||row||, eps) rounded to the element type; rinv_out[lr] (may be null) = that
   // factor.  For the places that need the normalised rows themselves as an operand.
   __device__ __forceinline__ void commit_normalised(e16_t* tile, float eps, float* rinv_out) const {
     float rinv[PASSES];
@@ -197,7 +197,7 @@ struct RowPieces {
 
 // Turns a wave's result block whose accumulators are laid out TRANSPOSED (acc[nt][v] =
 // result[row r][column col0 + 16 nt + 4 q4 + v], i.e. each lane holds 4 consecutive columns
-// of one row) into row pieces: scales by the per-lane row factor, rounds to bf16, passes the
+// of one row) into row pieces: scales by the per-lane row factor, rounds to the element type, passes the
 // block through a staging area private to the wave (16 rows of lds_pitch(D) elements from
 // stage_rows on, columns col0..; it fits the wave's 16 rows of an operand tile, whose pitch is
 // larger) with 8-byte writes and reads it back as 16-byte pieces.
