@@ -132,6 +132,29 @@ def other_workloads(torch, cottn, workloads):
             "flops": flop_rates(B * H * N, d, chunk, ms * 1e-3),
             "segments": cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d, chunk),
             "workspace_bytes": ws.numel() + fwd_ws.numel()}
+
+    # the GPT-shaped step at head dimension 128 (4x the flops per byte of d = 64: the shape
+    # where the MFMA rate, not only HBM, is worth reporting)
+    B, H, N, d = 8, 12, 1024, 128
+    t = {n: rnd(B, H, N, d) for n in ("Q", "K", "V", "dO")}
+    t.update({n: torch.empty_like(t["Q"]) for n in ("O", "dQ", "dK", "dV")})
+    s = torch.ones(H, device=dev)
+    fwd_ws = torch.empty(max(cottn.cottn_workspace_bytes(cottn.OP_FWD_CAUSAL, B, H, N, d), 256),
+                         dtype=torch.uint8, device=dev)
+    ws = torch.empty(cottn.cottn_workspace_bytes(cottn.OP_BWD_CAUSAL, B, H, N, d),
+                     dtype=torch.uint8, device=dev)
+
+    def d128(i):
+        cottn.cottn_fwd_causal(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=fwd_ws)
+        cottn.cottn_bwd_causal(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"],
+                               dV=t["dV"], ds=ds, workspace=ws, fwd_workspace=fwd_ws)
+    ms = time_calls(torch, d128, 100, 10)
+    byt = 11 * B * H * N * d * 2
+    out["d128_causal_fwd_bwd_B8_H12_N1024"] = {
+        "ms_per_step": ms, "tokens_per_s": B * N / (ms * 1e-3), "algorithmic_GBs": byt / ms / 1e6,
+        "frac_of_hbm_peak": byt / ms / 1e6 / HBM_PEAK_GBS,
+        "flops": flop_rates(B * H * N, d, 64, ms * 1e-3),
+        "segments": cottn.cottn_segments(cottn.OP_FWD_CAUSAL, B, H, N, d)}
     return out
 
 

@@ -56,13 +56,20 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
   if (g_tuned_segments > 0) {
     want = g_tuned_segments;
   } else {
-    // about one and a half workgroups per compute unit: measured best for the scan kernels
-    // (more segments shorten the serial chain but add totals to reduce and to add up)
-    const long target = 384;
-    want = (target + units - 1) / units;
-    // long serial chains (16 chunks or more per segment) are bound by the memory path, not by
-    // the prologue: there two workgroups on every compute unit measured best
-    if (n_chunks >= 16 * want) want = (512 + units - 1) / units;
+    if (dtype != COTTN_F32 && d == 128) {
+      // one workgroup fills the LDS of a compute unit at d = 128: a second round of
+      // workgroups costs more than shorter segments gain, so never more than one per unit
+      // (measured on B8 H12 N1024: 2 segments 143 us, 4 segments 178 us per step)
+      want = 256 / units;
+    } else {
+      // about one and a half workgroups per compute unit: measured best for the scan kernels
+      // (more segments shorten the serial chain but add totals to reduce and to add up)
+      const long target = 384;
+      want = (target + units - 1) / units;
+      // long serial chains (16 chunks or more per segment) are bound by the memory path, not
+      // by the prologue: there two workgroups on every compute unit measured best
+      if (n_chunks >= 16 * want) want = (512 + units - 1) / units;
+    }
   }
   if (want > n_chunks) want = n_chunks;
   if (want < 1) want = 1;
