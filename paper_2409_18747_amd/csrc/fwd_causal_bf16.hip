@@ -232,7 +232,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
     const float* __restrict__ s, e16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
-    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
+    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
+    int stream_q) {
   using Cfg = FwdCfg<D, C>;
   constexpr int RG = C / 16;           // row groups of a chunk
   constexpr int NOT = Cfg::DT / CS;    // output column tiles per wave
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     for (int y = 0; y < ST::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
   // the first chunk's rows and the stored states are all requested before anything waits
   Stage qst, kst, vst;
-  qst.fetch(Qu, row_begin, row_end);
+  qst.fetch(Qu, row_begin, row_end, stream_q != 0);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   // the state the sequence starts from (chunked prefill) belongs to every segment's start state
@@ -339,7 +340,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     }
     COTTN_TRACE_POINT(1);
     if (row0 + C < row_end) {
-      qst.fetch(Qu, row0 + C, row_end);
+      qst.fetch(Qu, row0 + C, row_end, stream_q != 0);
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
     }
@@ -474,10 +475,15 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
     }
   }
   constexpr int CS = FwdSplit<D, C>::CS;
+  // Q rows are read once here.  When the call's four tensors exceed the 256 MB last-level cache
+  // nothing of them survives until a backward call either, and loading them non-temporally
+  // keeps the K, V rows the totals kernel left in the L2 in place (long context: scan 98 ->
+  // 87 us); below that size a backward that follows finds the rows cached, and plain loads win.
+  const bool stream_q = 4.0 * units * double(a.N) * D * sizeof(e16_t) > 256.0 * 1024 * 1024;
   return launch_kernel(COTTN_SYM_STR(fwd_causal_scan), COTTN_SYM(fwd_causal_scan)<D, C, CS>, dim3(units * a.G),
                        dim3(Cfg::NT * CS), 0, a.stream, Q, K, V, a.s, static_cast<e16_t*>(a.O), a.state,
                        a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
-                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
+                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit, stream_q ? 1 : 0);
 }
 
 }  // namespace

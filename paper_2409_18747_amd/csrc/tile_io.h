@@ -18,6 +18,14 @@ namespace cottn {
 // A workgroup of NT threads moves a tile of C rows x D columns.  Each lane owns 8
 // consecutive columns (16 bytes) of a row; D/8 neighbouring lanes share a row, so a
 // wavefront reads whole 2*D-byte rows: fully coalesced.
+__device__ __forceinline__ uint4 load_rows(const e16_t* p, bool stream) {
+  if (stream) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+  }
+  return *reinterpret_cast<const uint4*>(p);
+}
+
 template <int D, int C, int NT>
 struct TileStage {
   static constexpr int LPR = D / 8;       // lanes per row
@@ -28,8 +36,10 @@ struct TileStage {
 
   uint4 regs[PASSES];
 
-  // rows >= n_rows (end of the sequence or of the segment) read as zero
-  __device__ __forceinline__ void fetch(const e16_t* __restrict__ base, int row0, int n_rows) {
+  // rows >= n_rows (end of the sequence or of the segment) read as zero; `stream` (uniform
+  // over the workgroup) marks the loads non-temporal: rows nothing will find in a cache again
+  __device__ __forceinline__ void fetch(const e16_t* __restrict__ base, int row0, int n_rows,
+                                        bool stream = false) {
     const int tid = threadIdx.x;
     const int col = (tid % LPR) * 8;
     const e16_t* p0 = base + size_t(row0) * D + (tid / LPR) * D + col;
@@ -37,14 +47,14 @@ struct TileStage {
       // whole tile in range (workgroup-uniform): plain loads at constant strides
 #pragma unroll
       for (int p = 0; p < PASSES; ++p)
-        regs[p] = *reinterpret_cast<const uint4*>(p0 + p * RPP * D);
+        regs[p] = load_rows(p0 + p * RPP * D, stream);
       return;
     }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int lr = p * RPP + tid / LPR;
       uint4 v = {0u, 0u, 0u, 0u};
-      if (lr < C && row0 + lr < n_rows) v = *reinterpret_cast<const uint4*>(p0 + p * RPP * D);
+      if (lr < C && row0 + lr < n_rows) v = load_rows(p0 + p * RPP * D, stream);
       regs[p] = v;
     }
   }
