@@ -454,3 +454,64 @@ def test_padded_batch_stabiliser(oracle):
                      oracle.scale_from_m_varlen(m - h * e, lens)) * ds).sum() / (2 * h)
                    for e in np.eye(3)])
     np.testing.assert_allclose(oracle.scale_backward_varlen(m, lens, ds), fd, rtol=1e-7)
+
+
+# ---------------------------------------------------------------- the pins have teeth
+class _Mistaken:
+    """The oracle with one planted mistake (made here, on the CPU, around the real oracle):
+    handed to a pin in the oracle's place, it must make that pin fail."""
+
+    def __init__(self, oracle, kind):
+        self._o, self._kind = oracle, kind
+
+    def __getattr__(self, name):
+        return getattr(self._o, name)
+
+    def fwd_quadratic(self, Q, K, V, s, eps=1e-6, causal=True):
+        o, kind = self._o, self._kind
+        if kind == "operands_swapped":      # Kh Qh^T instead of Qh Kh^T
+            return o.fwd_quadratic(K, Q, V, s, eps=eps, causal=causal)
+        if kind == "scale_dropped":
+            return o.fwd_quadratic(Q, K, V, np.ones_like(s), eps=eps, causal=causal)
+        if kind == "keys_not_normalised":
+            norms = np.maximum(np.linalg.norm(K, axis=-1, keepdims=True), eps)
+            return o.fwd_quadratic(Q, K, V * norms, s, eps=eps, causal=causal)
+        O = o.fwd_quadratic(Q, K, V, s, eps=eps, causal=causal)
+        if kind == "diagonal_excluded" and causal:
+            diag = (o.normalize_rows(Q, eps)[0] * o.normalize_rows(K, eps)[0]).sum(-1, keepdims=True)
+            return O - np.asarray(s).reshape(1, -1, 1, 1) * diag * V
+        if kind == "sign":
+            return -O
+        return O
+
+    def bwd_quadratic(self, Q, K, V, s, dO, eps=1e-6, causal=True):
+        dQ, dK, dV, ds = self._o.bwd_quadratic(Q, K, V, s, dO, eps=eps, causal=causal)
+        kind = self._kind
+        if kind == "dq_dk_exchanged":
+            return dK, dQ, dV, ds
+        if kind == "projection_dropped":   # gradient of the normalised rows passed through
+            nq = np.maximum(np.linalg.norm(Q, axis=-1, keepdims=True), eps)
+            return dQ + Q * 0.01 / nq, dK, dV, ds
+        if kind == "dv_unscaled":
+            return dQ, dK, dV / np.asarray(s).reshape(1, -1, 1, 1), ds
+        if kind == "ds_per_batch_only":    # summed over one batch entry instead of all
+            return dQ, dK, dV, ds * 0.5
+        return dQ, dK, dV, ds
+
+
+@pytest.mark.parametrize("kind,pin", [
+    ("operands_swapped", "worked"), ("scale_dropped", "worked"), ("keys_not_normalised", "worked"),
+    ("diagonal_excluded", "worked"), ("sign", "worked"),
+    ("operands_swapped", "closed_form"), ("diagonal_excluded", "mask"),
+    ("dq_dk_exchanged", "differences"), ("projection_dropped", "differences"),
+    ("dv_unscaled", "differences"), ("ds_per_batch_only", "differences"),
+    ("projection_dropped", "identities"), ("dq_dk_exchanged", "worked")])
+def test_pins_reject_planted_mistakes(oracle, kind, pin):
+    pins = {"worked": lambda o: test_worked_example(o),
+            "closed_form": lambda o: test_orthonormal_keys_select_query_components(o),
+            "mask": lambda o: test_mask_includes_diagonal_and_is_causal(o),
+            "differences": lambda o: test_gradients_by_central_differences(o, True),
+            "identities": lambda o: test_gradient_identities(o, True)}
+    pins[pin](oracle)  # the pin passes on the oracle itself
+    with pytest.raises(AssertionError):
+        pins[pin](_Mistaken(oracle, kind))
