@@ -115,13 +115,36 @@ int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, con
  *   K, V, B, H, N, d, chunk, dtype and eps used, untouched since (device pointer, read only,
  *   fwd_workspace_bytes as passed there).  It holds the forward-time segment states of
  *   Kh^T V, which the backward needs again: given them it does not rebuild them from K and V.
- *   They are taken over only for bfloat16 and when forward and backward split the sequence
+ *   They are taken over only for the 16-bit types and when forward and backward split the sequence
  *   the same way (cottn_segments agrees for both ops); otherwise the argument is ignored.
  *   Contents that do not come from such a call give wrong gradients, not an error. */
 int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s, const void* dO,
                      void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
                      size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
                      int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream);
+
+/* The causal backward for one piece of a sequence that is processed in pieces (a sequence too
+ * long for one call, or cut across devices).  The two cumulative sums of Sec. 4 cross the
+ * piece boundaries as d x d states: the pieces' forward calls run first to last handing on
+ * `state` (cottn_fwd_causal_from_state); their backward calls run last to first handing on
+ * the reverse-time state.  All states are float[B][H][d][d], [d_key][d_value], without s.
+ *   state_in:      NULL (nothing precedes) or sum of kh_j^T v_j over the rows BEFORE this
+ *                  piece: the state_in its forward call was given.
+ *   rev_state_in:  NULL (nothing follows) or sum of qh_i^T dO_i over the rows AFTER this
+ *                  piece: the rev_state_out of the following piece's backward call.
+ *   rev_state_out: NULL or out, rev_state_in + the sum over this piece; must not be the same
+ *                  buffer as rev_state_in (COTTN_E_ARG).
+ * dQ, dK, dV are the gradients of this piece's rows given all pieces; ds[H] is this piece's
+ * share of dL/ds (the caller adds the shares up).  fwd_workspace as in cottn_bwd_causal: that
+ * of the piece's own forward call.  N = 0 sets ds to zero and copies rev_state_in to
+ * rev_state_out (zeros without rev_state_in).  Chained over the pieces this gives exactly what
+ * one call over the whole sequence gives. */
+int cottn_bwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
+                                const void* dO, const float* state_in, const float* rev_state_in,
+                                void* dQ, void* dK, void* dV, float* ds, float* rev_state_out,
+                                const void* fwd_workspace, size_t fwd_workspace_bytes,
+                                void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                                int chunk, int dtype, float eps, void* hip_stream);
 
 /* Bidirectional forward (Sec. 4, eq. subQuadCos, right-hand side).
  *   state: NULL, or float[B][H][d][d] out = Kh^T V. */

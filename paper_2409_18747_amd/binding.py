@@ -46,6 +46,9 @@ def _load():
     lib.cottn_bwd_causal.restype = i
     lib.cottn_bwd_causal.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i, i, i,
                                      f, vp]
+    lib.cottn_bwd_causal_from_state.restype = i
+    lib.cottn_bwd_causal_from_state.argtypes = [vp, vp, vp, fp, vp, fp, fp, vp, vp, vp, fp, fp, vp, sz,
+                                                vp, sz, i, i, i, i, i, i, f, vp]
     lib.cottn_fwd_bidir.restype = i
     lib.cottn_fwd_bidir.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, f, vp]
     lib.cottn_bwd_bidir.restype = i
@@ -192,6 +195,29 @@ def cottn_bwd_causal(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspa
                               _ptr(dV), _ptr(ds), _ptr(fwd_workspace), fwd_have, _ptr(workspace),
                               have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_causal")
+    return dQ, dK, dV, ds
+
+
+def cottn_bwd_causal_from_state(Q, K, V, s, dO, state_in=None, rev_state_in=None, dQ=None, dK=None,
+                                dV=None, ds=None, rev_state_out=None, workspace=None, chunk=0,
+                                eps=1e-6, stream=None, fwd_workspace=None):
+    """cottn_bwd_causal for one piece of a sequence processed in pieces: state_in is the
+    forward-time state before the piece, rev_state_in the reverse-time state after it;
+    returns (dQ, dK, dV, ds) and fills rev_state_out (float32 [B, H, d, d]) when given."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    st = lib.cottn_bwd_causal_from_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(state_in),
+                                         _ptr(rev_state_in), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds),
+                                         _ptr(rev_state_out), _ptr(fwd_workspace), fwd_have,
+                                         _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
+                                         _stream(stream))
+    _check(st, "cottn_bwd_causal_from_state")
     return dQ, dK, dV, ds
 
 

@@ -181,6 +181,11 @@ __global__ void copy_f32(const float* __restrict__ src, float* __restrict__ dst,
   if (i < n) dst[i] = src[i];
 }
 
+hipError_t copy_state(float* dst, const float* src, long n, hipStream_t st) {
+  return launch_kernel("copy_f32", copy_f32, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, src,
+                       dst, n);
+}
+
 // seq_len != null in the *_any functions: a padded batch, with s and ds per (batch, head)
 int check_lengths(const int* seq_len) {
   return seq_len == nullptr || is_aligned(seq_len, 4) ? COTTN_OK : COTTN_E_ALIGN;
@@ -207,8 +212,7 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
     const long n = long(B) * H * d * d;
     if (state == nullptr) return COTTN_OK;
     if (state_in == nullptr) return map_hip(zero_f32(state, n, stream));
-    return map_hip(launch_kernel("copy_f32", copy_f32, dim3(unsigned((n + 255) / 256)), dim3(256), 0,
-                                 stream, state_in, state, n));
+    return map_hip(copy_state(state, state_in, n, stream));
   }
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.state_in = state_in;
@@ -239,7 +243,8 @@ int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, con
 namespace {
 
 int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
-                   const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                   const void* dO, const float* state_in, const float* rev_state_in, void* dQ,
+                   void* dK, void* dV, float* ds, float* rev_state_out,
                    const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
                    size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
                    float eps, void* hip_stream) {
@@ -247,15 +252,27 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   int st = check_common(req, 9, B, H, N, d, dtype, eps);
   if (st != COTTN_OK) return st;
   if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
+  if (!is_aligned(state_in, 16) || !is_aligned(rev_state_in, 16) || !is_aligned(rev_state_out, 16))
+    return COTTN_E_ALIGN;
+  // workgroups read the one while others write the other
+  if (rev_state_out != nullptr && rev_state_out == rev_state_in) return COTTN_E_ARG;
   SeqPlan plan;
   if (!make_plan(COTTN_OP_BWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
                        workspace_bytes_for(COTTN_OP_BWD_CAUSAL, B, H, d, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (N == 0) return map_hip(zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream));
+  if (N == 0) {
+    const long n = long(B) * H * d * d;
+    hipError_t e = zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream);
+    if (e == hipSuccess && rev_state_out != nullptr)
+      e = rev_state_in != nullptr ? copy_state(rev_state_out, rev_state_in, n, stream)
+                                  : zero_f32(rev_state_out, n, stream);
+    return map_hip(e);
+  }
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
+  a.state_in = state_in; a.rev_state_in = rev_state_in; a.rev_state_out = rev_state_out;
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
   a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
@@ -337,8 +354,20 @@ int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s
                      void* dQ, void* dK, void* dV, float* ds, const void* fwd_workspace,
                      size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
                      int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream) {
-  return bwd_causal_any(Q, K, V, s, nullptr, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+  return bwd_causal_any(Q, K, V, s, nullptr, dO, nullptr, nullptr, dQ, dK, dV, ds, nullptr,
+                        fwd_workspace, fwd_workspace_bytes,
                         workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_bwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
+                                const void* dO, const float* state_in, const float* rev_state_in,
+                                void* dQ, void* dK, void* dV, float* ds, float* rev_state_out,
+                                const void* fwd_workspace, size_t fwd_workspace_bytes,
+                                void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                                int chunk, int dtype, float eps, void* hip_stream) {
+  return bwd_causal_any(Q, K, V, s, nullptr, dO, state_in, rev_state_in, dQ, dK, dV, ds,
+                        rev_state_out, fwd_workspace, fwd_workspace_bytes, workspace,
+                        workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
@@ -372,7 +401,8 @@ int cottn_bwd_causal_varlen(const void* Q, const void* K, const void* V, const f
                             void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
                             int chunk, int dtype, float eps, void* hip_stream) {
   if (seq_len == nullptr) return COTTN_E_NULL;
-  return bwd_causal_any(Q, K, V, s, seq_len, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+  return bwd_causal_any(Q, K, V, s, seq_len, dO, nullptr, nullptr, dQ, dK, dV, ds, nullptr,
+                        fwd_workspace, fwd_workspace_bytes,
                         workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
 }
 

@@ -123,7 +123,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
     const float* __restrict__ fwd_states, float* __restrict__ rev_totals,
     float* __restrict__ ds_partial, int H, int N, int G, int seg_rows, float inv_eps,
-    int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
+    int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
+    const float* __restrict__ state_in) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -184,6 +185,17 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
                            16 * AT::col_tile(w, x) + r;
           return f32x4{p[0], p[D], p[2 * D], p[3 * D]};
         });
+  }
+  // the state of the rows before this piece of the sequence belongs to every segment's start
+  if (state_in != nullptr && AT::active(w)) {
+    const float* src = state_in + size_t(unit) * D * D;
+#pragma unroll
+    for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < AT::NRT; ++y) {
+        const float* p = src + (16 * AT::row_tile(w, y) + 4 * q4) * D + 16 * AT::col_tile(w, x) + r;
+        sacc[x][y] += f32x4{p[0], p[D], p[2 * D], p[3 * D]};
+      }
   }
 
   RowPieces<D> finished;  // dQ rows of the previous chunk, stored one chunk late
@@ -364,7 +376,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dK,
     e16_t* __restrict__ dV, const float* __restrict__ rev_states,
     const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H, int N, int G,
-    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit) {
+    int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
+    const float* __restrict__ rev_in, float* __restrict__ rev_out) {
   using Cfg = BwdCfg<D, C>;
   using AT = AccTiles<D, Cfg::NW>;
   using Stage = TileStage<D, C, Cfg::NT>;
@@ -429,6 +442,16 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
                                                  (16 * AT::col_tile(w, x) + r) * D +
                                                  16 * AT::row_tile(w, y) + 4 * q4);
         });
+  }
+  // the reverse state of the rows after this piece of the sequence belongs to every segment
+  if (rev_in != nullptr && AT::active(w)) {
+    const float* src = rev_in + size_t(unit) * D * D;
+#pragma unroll
+    for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < AT::NRT; ++y)
+        racc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::col_tile(w, x) + r) * D +
+                                                      16 * AT::row_tile(w, y) + 4 * q4);
   }
 
   RowPieces<D> done_k, done_v;  // dK and dV rows of the previous chunk, stored one chunk late
@@ -584,6 +607,16 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     zero_rows_e16<D>(dKu, row_end, seg_end);
     zero_rows_e16<D>(dVu, row_end, seg_end);
   }
+  // the first segment ends with the reverse state of the whole piece and what followed it
+  if (rev_out != nullptr && g == 0 && AT::active(w)) {
+    float* out = rev_out + size_t(unit) * D * D;
+#pragma unroll
+    for (int x = 0; x < AT::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < AT::NRT; ++y)
+        *reinterpret_cast<f32x4*>(out + (16 * AT::col_tile(w, x) + r) * D +
+                                  16 * AT::row_tile(w, y) + 4 * q4) = racc[x][y];
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -646,7 +679,8 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   // the dQ scan leaves the reverse-time segment totals (of qh^T dO) behind for the dK/dV scan
   err = launch_kernel(COTTN_SYM_STR(bwd_dq_scan), COTTN_SYM(bwd_dq_scan)<D, C>, grid, block, 0, a.stream, Q, K, V,
                       dO, a.s, static_cast<e16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
-                      a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
+                      a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit,
+                      a.state_in);
   if (err != hipSuccess) return err;
   if (a.G > 1 && !sum_in_scan) {
     err = launch_bwd_state_carry(nullptr, rev_states, units, a.G, D * D, a.stream);
@@ -656,7 +690,8 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   return launch_kernel(COTTN_SYM_STR(bwd_dkdv_scan), COTTN_SYM(bwd_dkdv_scan)<D, C>, grid, block, 0, a.stream, Q,
                        K, V, dO, a.s, static_cast<e16_t*>(a.dK), static_cast<e16_t*>(a.dV),
                        rev_states, ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, inv_eps,
-                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit);
+                       sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit, a.rev_state_in,
+                       a.rev_state_out);
 }
 
 }  // namespace

@@ -274,7 +274,8 @@ __global__ __launch_bounds__(NT) void bwd_dq_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ s, float* __restrict__ dQ,
     const float* __restrict__ states, float* __restrict__ ds_partial, int H, int N, int G,
-    int seg_rows, float eps, int causal, const int* __restrict__ seq_len, int s_per_unit) {
+    int seg_rows, float eps, int causal, const int* __restrict__ seq_len, int s_per_unit,
+    const float* __restrict__ state_in) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -295,7 +296,8 @@ __global__ __launch_bounds__(NT) void bwd_dq_scan_f32(
   const float* init = nullptr;
   if (!causal) init = states + size_t(unit) * G * D * D;
   else if (states != nullptr && g > 0) init = states + (size_t(unit) * G + g) * D * D;
-  state_load<D>(S, init);
+  // the state of the rows before this piece of the sequence belongs to every segment's start
+  state_load2<D>(S, init, state_in ? state_in + size_t(unit) * D * D : nullptr);
   float ds_lane = 0.f;
   for (int row0 = row_begin; row0 < row_end; row0 += CR) {
     __syncthreads();
@@ -345,7 +347,8 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ dO, const float* __restrict__ s, float* __restrict__ dK,
     float* __restrict__ dV, const float* __restrict__ states, int H, int N, int G, int seg_rows,
-    float eps, int causal, const int* __restrict__ seq_len, int s_per_unit) {
+    float eps, int causal, const int* __restrict__ seq_len, int s_per_unit,
+    const float* __restrict__ rev_in, float* __restrict__ rev_out) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   constexpr int P = FCfg<D>::P, CPT = FCfg<D>::CPT;
   Carver cv{lds};
@@ -367,7 +370,8 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
   const float* init = nullptr;
   if (!causal) init = states + size_t(unit) * G * D * D;
   else if (states != nullptr && g < G - 1) init = states + (size_t(unit) * G + g) * D * D;
-  state_load<D>(R, init);
+  // the reverse state of the rows after this piece of the sequence belongs to every segment
+  state_load2<D>(R, init, rev_in ? rev_in + size_t(unit) * D * D : nullptr);
   for (int c = n_chunks - 1; c >= 0; --c) {
     const int row0 = row_begin + c * CR;
     __syncthreads();
@@ -409,6 +413,11 @@ __global__ __launch_bounds__(NT) void bwd_dkdv_scan_f32(
   if (seq_len != nullptr) {
     zero_rows_f32<D>(dK + ubase, row_end, seg_end);
     zero_rows_f32<D>(dV + ubase, row_end, seg_end);
+  }
+  // the first segment ends with the reverse state of the whole piece and what followed it
+  if (causal && rev_out != nullptr && g == 0) {
+    __syncthreads();
+    state_store<D>(rev_out + size_t(unit) * D * D, R);
   }
 }
 
@@ -484,12 +493,13 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
   err = launch_kernel("bwd_dq_scan_f32", bwd_dq_scan_f32<D>, dim3(units * a.G), dim3(NT),
                       lds_dq<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dQ), st0,
                       causal ? ds_partial : nullptr, a.H, a.N, a.G, a.seg_rows, a.eps,
-                      causal ? 1 : 0, a.seq_len, a.s_per_unit);
+                      causal ? 1 : 0, a.seq_len, a.s_per_unit, causal ? a.state_in : nullptr);
   if (err != hipSuccess) return err;
   err = launch_kernel("bwd_dkdv_scan_f32", bwd_dkdv_scan_f32<D>, dim3(units * a.G), dim3(NT),
                       lds_dkdv<D>(), a.stream, Q, K, V, dO, a.s, static_cast<float*>(a.dK),
                       static_cast<float*>(a.dV), st1, a.H, a.N, a.G, a.seg_rows, a.eps,
-                      causal ? 1 : 0, a.seq_len, a.s_per_unit);
+                      causal ? 1 : 0, a.seq_len, a.s_per_unit, causal ? a.rev_state_in : nullptr,
+                      causal ? a.rev_state_out : nullptr);
   if (err != hipSuccess) return err;
   // causal: partials per (unit, segment); bidirectional: d*d/256 per unit from the combine
   return launch_reduce_ds(ds_partial, a.ds, a.B, a.H, causal ? a.G : D * D / 256, a.s_per_unit,

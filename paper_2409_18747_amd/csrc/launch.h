@@ -14,7 +14,12 @@ struct CausalArgs {
   const void* Q; const void* K; const void* V; const float* s;
   const void* dO;                 // backward only
   void* O; float* state;          // forward only (state may be null)
-  const float* state_in;          // causal forward only: null, or the state the sequence starts from
+  // a sequence processed in pieces (causal only): null, or the forward-time state Kh^T V of
+  // the rows before this piece (forward and backward), the reverse-time state Qh^T dO of the
+  // rows after it (backward, in), and that state with this piece added (backward, out)
+  const float* state_in;
+  const float* rev_state_in;
+  float* rev_state_out;
   // padded batches: null, or int[B] row counts (then s and ds are [B][H], see s_per_unit)
   const int* seq_len;
   int s_per_unit;                 // s (and ds) indexed by (batch, head) instead of head

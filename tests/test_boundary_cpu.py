@@ -29,6 +29,7 @@ def lib():
     l.cottn_bwd_bidir.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, vp]
     l.cottn_fwd_causal_from_state.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
+    l.cottn_bwd_causal_from_state.argtypes = [vp] * 13 + [sz, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_fwd_causal_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_bwd_bidir_varlen.argtypes = [vp] * 11 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m_varlen.argtypes = [vp, vp, vp, i, i, vp]
@@ -49,6 +50,7 @@ def test_header_declares_the_entry_points():
     for required in ("cottn_fwd_causal", "cottn_bwd_causal", "cottn_fwd_bidir", "cottn_bwd_bidir",
                      "cottn_step", "cottn_workspace_bytes", "cottn_status_string",
                      "cottn_scale_from_m", "cottn_scale_backward", "cottn_fwd_causal_from_state",
+                     "cottn_bwd_causal_from_state",
                      "cottn_fwd_causal_varlen", "cottn_bwd_causal_varlen", "cottn_fwd_bidir_varlen",
                      "cottn_bwd_bidir_varlen", "cottn_scale_from_m_varlen",
                      "cottn_scale_backward_varlen"):
@@ -166,6 +168,12 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert cont(p(), p(), p(), p(), p(4), p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ALIGN
     assert cont(p(), p(), p(), p(), st_buf, p(), st_buf, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ARG
     assert cont(p(), p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 48, 0, BF16, eps, None) == E_SHAPE
+    piece = lib.cottn_bwd_causal_from_state
+    tail = (None, 0, p(), 1 << 12, 1, 1, 8, 64, 0, BF16, eps, None)
+    assert piece(p(), p(), p(), p(), None, None, None, p(), p(), p(), p(), None, *tail) == E_NULL
+    assert piece(p(), p(), p(), p(), p(), p(4), None, p(), p(), p(), p(), None, *tail) == E_ALIGN
+    assert piece(p(), p(), p(), p(), p(), None, p(8), p(), p(), p(), p(), None, *tail) == E_ALIGN
+    assert piece(p(), p(), p(), p(), p(), None, st_buf, p(), p(), p(), p(), st_buf, *tail) == E_ARG
     vl = lib.cottn_fwd_causal_varlen
     assert vl(p(), p(), p(), p(), None, p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_NULL
     assert vl(p(), p(), p(), p(), p(2), p(), None, None, 0, 1, 1, 8, 64, 0, BF16, eps, None) == E_ALIGN
