@@ -75,10 +75,10 @@ struct BwdCfg {
 // pack a masked accumulator tile into half of an operand fragment
 __device__ __forceinline__ void put_half(frag8& frag, int half, f32x4 acc, bool k0, bool k1,
                                          bool k2, bool k3) {
-  frag[4 * half + 0] = static_cast<elem_native>(k0 ? acc[0] : 0.f);
-  frag[4 * half + 1] = static_cast<elem_native>(k1 ? acc[1] : 0.f);
-  frag[4 * half + 2] = static_cast<elem_native>(k2 ? acc[2] : 0.f);
-  frag[4 * half + 3] = static_cast<elem_native>(k3 ? acc[3] : 0.f);
+  u32x4 words = __builtin_bit_cast(u32x4, frag);
+  words[2 * half + 0] = pack2(k0 ? acc[0] : 0.f, k1 ? acc[1] : 0.f);
+  words[2 * half + 1] = pack2(k2 ? acc[2] : 0.f, k3 ? acc[3] : 0.f);
+  frag = __builtin_bit_cast(frag8, words);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -113,8 +113,11 @@ __device__ __forceinline__ float from_e16(e16_t b) {
 __device__ __forceinline__ e16_t to_e16(float f) {
   return __builtin_bit_cast(e16_t, static_cast<elem_native>(f));
 }
+// two values rounded and packed into one word (low half first): written as one vector
+// conversion so that it becomes the packed convert instruction, not two converts and a merge
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  return uint32_t(to_e16(lo)) | (uint32_t(to_e16(hi)) << 16);
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, elem2));
 }
 // the two elements of a 32-bit word (low half first)
 __device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {

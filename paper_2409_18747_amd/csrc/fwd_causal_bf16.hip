@@ -399,7 +399,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
-        frag8 pf;
+        u32x4 pw;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const int jt = 2 * p + half;
@@ -407,12 +407,16 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
 #pragma unroll
           for (int ks = 0; ks < Cfg::KS; ++ks) pacc = mma16(kr[half][ks], qf[ks], pacc);
           // pacc[v] = q_(16 rg + r) . k_(16jt + 4*q4 + v); keep key <= query
+          float kept[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const bool keep = (jt < rg) || (jt == rg && 4 * q4 + v <= r);
-            pf[4 * half + v] = static_cast<elem_native>(keep ? pacc[v] : 0.f);
+            kept[v] = keep ? pacc[v] : 0.f;
           }
+          pw[2 * half + 0] = pack2(kept[0], kept[1]);
+          pw[2 * half + 1] = pack2(kept[2], kept[3]);
         }
+        const frag8 pf = __builtin_bit_cast(frag8, pw);
 #pragma unroll
         for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(vc[nt], pf, oacc[nt]);
       }
