@@ -89,25 +89,12 @@ __device__ __forceinline__ void put_half(frag8& frag, int half, f32x4 acc, bool 
 __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_tot,
                                                        float* __restrict__ rev_tot, int G,
                                                        int elems_per_state, long total) {
-  const long idx = long(blockIdx.x) * 256 + threadIdx.x;
-  if (idx >= total || (blockIdx.y == 0 ? fwd_tot : rev_tot) == nullptr) return;
+  const long idx = (long(blockIdx.x) * 256 + threadIdx.x) * 4;  // 4 elements per thread
+  float* tot = blockIdx.y == 0 ? fwd_tot : rev_tot;
+  if (idx >= total || tot == nullptr) return;
   const long unit = idx / elems_per_state, e = idx % elems_per_state;
-  float run = 0.f;
-  if (blockIdx.y == 0) {
-    float* p = fwd_tot + unit * G * elems_per_state + e;
-    for (int g = 0; g < G; ++g) {
-      const float t = (g + 1 < G) ? p[size_t(g) * elems_per_state] : 0.f;
-      p[size_t(g) * elems_per_state] = run;
-      run += t;
-    }
-  } else {
-    float* p = rev_tot + unit * G * elems_per_state + e;
-    for (int g = G - 1; g >= 0; --g) {
-      const float t = (g > 0) ? p[size_t(g) * elems_per_state] : 0.f;
-      p[size_t(g) * elems_per_state] = run;
-      run += t;
-    }
-  }
+  exclusive_running_sum(tot + unit * G * elems_per_state + e, G, size_t(elems_per_state),
+                        blockIdx.y == 1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -700,7 +687,7 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
 hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int G, int elems,
                                   hipStream_t st) {
   const long total = long(units) * elems;
-  return launch_kernel("bwd_state_carry", bwd_state_carry, dim3(unsigned((total + 255) / 256), 2),
+  return launch_kernel("bwd_state_carry", bwd_state_carry, dim3(unsigned((total / 4 + 255) / 256), 2),
                        dim3(256), 0, st, fwd_tot, rev_tot, G, elems, total);
 }
 

@@ -236,6 +236,34 @@ __device__ __forceinline__ void store_state_words(float* dst, f32x4 v) {
 #endif
 }
 
+// In place, for 4 neighbouring elements of a stack of n matrices `stride` floats apart:
+// matrix k (in walking order: first to last, or last to first with `reverse`) <- sum of the
+// matrices walked before it.  The last matrix walked never held a value and is not read.  The
+// matrices are taken eight at a time with all loads of a batch issued before the first store:
+// the sum itself is serial, but a thread then pays one memory latency per eight matrices.
+__device__ __forceinline__ void exclusive_running_sum(float* __restrict__ p, int n, size_t stride,
+                                                      bool reverse) {
+  constexpr int BATCH = 8;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < n; k0 += BATCH) {
+    f32x4 t[BATCH];
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+      const int k = k0 + i;
+      t[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (k + 1 < n) t[i] = *reinterpret_cast<const f32x4*>(p + size_t(reverse ? n - 1 - k : k) * stride);
+    }
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+      const int k = k0 + i;
+      if (k < n) {
+        *reinterpret_cast<f32x4*>(p + size_t(reverse ? n - 1 - k : k) * stride) = run;
+        run += t[i];
+      }
+    }
+  }
+}
+
 // 1 / max(sqrt(sum_sq), eps)
 __device__ __forceinline__ float inv_norm(float sum_sq, float eps) {
   return 1.0f / fmaxf(sqrtf(sum_sq), eps);

@@ -203,16 +203,11 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
 // along the segment axis); slot n_slots-1 never held a total and only receives its prefix.
 __global__ __launch_bounds__(256) void fwd_state_carry(float* __restrict__ seg_state, int n_slots,
                                                        int elems_per_state, long total) {
-  const long idx = long(blockIdx.x) * 256 + threadIdx.x;
+  const long idx = (long(blockIdx.x) * 256 + threadIdx.x) * 4;  // 4 elements per thread
   if (idx >= total) return;
   const long unit = idx / elems_per_state, e = idx % elems_per_state;
-  float* p = seg_state + unit * n_slots * elems_per_state + e;
-  float run = 0.f;
-  for (int g = 0; g < n_slots; ++g) {
-    const float t = (g + 1 < n_slots) ? p[size_t(g) * elems_per_state] : 0.f;
-    p[size_t(g) * elems_per_state] = run;
-    run += t;
-  }
+  exclusive_running_sum(seg_state + unit * n_slots * elems_per_state + e, n_slots,
+                        size_t(elems_per_state), false);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -536,7 +531,7 @@ hipError_t COTTN_SYM(launch_fwd_segment_totals)(const CausalArgs& a, float* dst)
 #ifndef COTTN_ELEM_F16  // not specific to the element type: defined once, by the bf16 build
 hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems, hipStream_t st) {
   const long total = long(units) * elems;
-  return launch_kernel("fwd_state_carry", fwd_state_carry, dim3(unsigned((total + 255) / 256)),
+  return launch_kernel("fwd_state_carry", fwd_state_carry, dim3(unsigned((total / 4 + 255) / 256)),
                        dim3(256), 0, st, seg_state, G, elems, total);
 }
 #endif
