@@ -492,15 +492,11 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   const e16_t* X = static_cast<const e16_t*>(t.X);
   const e16_t* Y = static_cast<const e16_t*>(t.Y);
   const float inv_eps = 1.0f / t.eps;
-  // The totals kernel takes the largest row tile that does not exceed the segment: with
-  // 256-row tiles a 1024-thread workgroup has all of its loads in flight at once instead of
-  // paying one memory latency per 64-row chunk.
+  // The totals kernel takes 128-row tiles when the segment is that long: a 512-thread
+  // workgroup has all of its loads in flight at once instead of paying one memory latency per
+  // 64-row chunk, and several workgroups still fit a compute unit (two 256-row tiles of the
+  // operand-tile pitch would leave room for one: measured 0.6 us slower on the GPT shape).
   const dim3 grid(t.units * t.G);
-  constexpr int TOP = D <= 64 ? 256 : 128;  // two 256-row tiles of d = 128 exceed the LDS
-  if (t.seg_rows >= TOP)
-    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, TOP>, grid,
-                         dim3(4 * TOP), 0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows,
-                         inv_eps, t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
   if (t.seg_rows >= 128)
     return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, 128>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
