@@ -2,7 +2,10 @@
 (padded-batch variants, which contain the fixed-length ones as the case of full lengths)
 against the CPU oracle, with batch, heads, length, head dimension, segment count, chunk size
 and sequence lengths drawn from a seeded generator.  The parametrised tests elsewhere walk
-the edges on purpose; this one looks for combinations nobody thought of."""
+the edges on purpose; this one looks for combinations nobody thought of (COTTN_RANDOM_CASES in
+the environment draws more of them)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -33,7 +36,7 @@ def cases(n):
     return out
 
 
-@pytest.mark.parametrize("dtype,d,B,H,N,chunk,segments,causal,lens,saved,seed", cases(40))
+@pytest.mark.parametrize("dtype,d,B,H,N,chunk,segments,causal,lens,saved,seed", cases(int(os.environ.get("COTTN_RANDOM_CASES", "40"))))
 def test_random_shape(oracle, dtype, d, B, H, N, chunk, segments, causal, lens, saved, seed):
     import torch
     import paper_2409_18747_amd.binding as cottn
