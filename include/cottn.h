@@ -95,6 +95,23 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
                      float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                      int d, int chunk, int dtype, float eps, void* hip_stream);
 
+/* cottn_fwd_causal for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors as cottn_fwd_causal without the two workspace
+ * arguments: the segment states live in a COTTN_STATIC_WORKSPACE_BYTES array inside the
+ * library's own device code (each GPU the library runs on holds it until the process ends).
+ * Shapes whose cottn_workspace_bytes(COTTN_OP_FWD_CAUSAL, ...) exceeds that size are rejected
+ * with COTTN_E_WORKSPACE before anything is enqueued.  The call allocates and frees nothing
+ * (the array's address is looked up once per device, on the first call with that device
+ * current; hip_stream must belong to the current device).  Every call on a GPU uses that
+ * GPU's one array: calls that may overlap on one GPU (different streams, different threads)
+ * race on it and must be ordered by the caller.  Nothing in the array has to be cleared
+ * between calls. */
+#define COTTN_STATIC_WORKSPACE_BYTES (16u << 20)
+int cottn_fwd_causal_static(const void* Q, const void* K, const void* V, const float* s, void* O,
+                            float* state, int B, int H, int N, int d, int chunk, int dtype,
+                            float eps, void* hip_stream);
+
 /* The same for a sequence that continues an earlier one (a long prompt fed in pieces, Sec. 5:
  * the hidden state carries everything the later tokens need from the earlier ones).
  *   state_in: float[B][H][d][d] in, the state after the tokens before this piece (what an

@@ -40,6 +40,8 @@ def _load():
     lib.cottn_status_string.argtypes = [i]
     lib.cottn_fwd_causal.restype = i
     lib.cottn_fwd_causal.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_fwd_causal_static.restype = i
+    lib.cottn_fwd_causal_static.argtypes = [vp, vp, vp, fp, vp, fp, i, i, i, i, i, i, f, vp]
     lib.cottn_fwd_causal_from_state.restype = i
     lib.cottn_fwd_causal_from_state.argtypes = [vp, vp, vp, fp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f,
                                                 vp]
@@ -158,6 +160,21 @@ def cottn_fwd_causal(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, ep
     st = lib.cottn_fwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
                               _ptr(workspace), have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_fwd_causal")
+    return O
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20  # COTTN_STATIC_WORKSPACE_BYTES of include/cottn.h
+
+
+def cottn_fwd_causal_static(Q, K, V, s, O, state=None, chunk=0, eps=1e-6, stream=None):
+    """cottn_fwd_causal without a workspace argument, for callers that cannot allocate: the
+    segment states live in an array inside the library.  O must be given (nothing is allocated
+    here either); returns O."""
+    B, H, N, d = Q.shape
+    dt = _dtype_code(Q)
+    st = lib.cottn_fwd_causal_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state), B, H,
+                                     N, d, chunk, dt, eps, _stream(stream))
+    _check(st, "cottn_fwd_causal_static")
     return O
 
 

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -228,6 +229,53 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
                      float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                      int d, int chunk, int dtype, float eps, void* hip_stream) {
   return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, workspace, workspace_bytes, B, H, N,
+                        d, chunk, dtype, eps, hip_stream);
+}
+
+// ---- the causal forward for callers that cannot allocate ------------------------------------
+// Its workspace (the fp32 segment states) is this array, part of the library's code object: every
+// GPU the library runs on holds its own copy, at its own address, until the process ends.  In
+// host code the name below only stands for the symbol; the address kernels can use comes from
+// hipGetSymbolAddress, asked once per device with that device current.
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[COTTN_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_workspace(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return COTTN_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr)
+      return COTTN_E_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return COTTN_OK;
+}
+
+}  // namespace
+
+int cottn_fwd_causal_static(const void* Q, const void* K, const void* V, const float* s, void* O,
+                            float* state, int B, int H, int N, int d, int chunk, int dtype,
+                            float eps, void* hip_stream) {
+  const void* req[] = {Q, K, V, s, O};
+  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  if (st != COTTN_OK) return st;
+  SeqPlan plan;
+  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  const size_t need = workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, plan);
+  if (need > size_t(COTTN_STATIC_WORKSPACE_BYTES)) return COTTN_E_WORKSPACE;
+  void* ws = nullptr;
+  if (need > 0 && (st = static_workspace(&ws)) != COTTN_OK) return st;
+  // every slot of the segment-state array that a kernel reads is written earlier in the same
+  // call, so what the previous call left in the array needs no clearing
+  return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, ws, need, B, H, N,
                         d, chunk, dtype, eps, hip_stream);
 }
 

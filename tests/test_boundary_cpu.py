@@ -33,6 +33,7 @@ def lib():
     l.cottn_fwd_causal_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, vp]
     l.cottn_bwd_bidir_varlen.argtypes = [vp] * 11 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m_varlen.argtypes = [vp, vp, vp, i, i, vp]
+    l.cottn_fwd_causal_static.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m.argtypes = [vp, vp, i, f, vp]
     l.cottn_scale_backward.argtypes = [vp, vp, vp, i, f, vp]
     yield l
@@ -194,3 +195,24 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert step(p(), p(), p(), p(), p(), p(), 1, 1, 64, 3, eps, None) == E_DTYPE
     assert step(p(), p(), p(), p(), p(), p(), 1, 1, 64, BF16, -1.0, None) == E_ARG
     assert step(p(), p(8), p(), p(), p(), p(), 1, 1, 64, BF16, eps, None) == E_ALIGN
+
+
+def test_static_workspace_forward_rejects_on_the_host(lib):
+    """cottn_fwd_causal_static checks its arguments, and that the segment states fit the array
+    inside the library, before it touches HIP."""
+    E_NULL, E_SHAPE, E_WS = 1, 2, 5
+    buf = ctypes.create_string_buffer(1 << 12)
+    base = (ctypes.addressof(buf) + 255) & ~255
+    p = lambda: ctypes.c_void_p(base)
+    f = lib.cottn_fwd_causal_static
+    lib.cottn_tune_segments(0)
+    assert f(p(), None, p(), p(), p(), None, 1, 1, 8, 64, 0, BF16, 1e-6, None) == E_NULL
+    assert f(p(), p(), p(), p(), p(), None, 1, 1, 8, 72, 0, BF16, 1e-6, None) == E_SHAPE
+    limit = 16 << 20
+    # B8 H16 N65536 d64 in 32 segments: 8*16*32 fp32 64x64 states = 64 MiB
+    lib.cottn_tune_segments(32)
+    assert lib.cottn_workspace_bytes(0, 8, 16, 65536, 64, 0, BF16) == 64 << 20
+    assert f(p(), p(), p(), p(), p(), None, 8, 16, 65536, 64, 0, BF16, 1e-6, None) == E_WS
+    lib.cottn_tune_segments(0)
+    # the benchmarked shape fits
+    assert 0 < lib.cottn_workspace_bytes(0, 8, 12, 1024, 64, 0, BF16) <= limit
