@@ -17,8 +17,6 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
-# extra compiler flags for tuning builds (e.g. -DNAME to switch a kernel variant on)
-FLAGS += os.environ.get("COTTN_HIPCC_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

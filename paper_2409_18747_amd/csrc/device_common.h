@@ -31,13 +31,6 @@ typedef uint16_t e16_t;  // storage type of a 16-bit element in global memory an
 
 #define COTTN_LDS __attribute__((address_space(3)))
 
-// Optional in-kernel timeline for tuning builds: a translation unit that defines
-// COTTN_TRACE_POINT(i) before including the kernel sources gets a hook at the phase
-// boundaries of the scan kernels; the library build leaves it empty.
-#ifndef COTTN_TRACE_POINT
-#define COTTN_TRACE_POINT(i)
-#endif
-
 // Row pitches (in elements) of 16-bit LDS arrays.  The LDS moves 64 lanes x 16 bytes in 4
 // cycles and 64 x 8 bytes in 2.4 at best (4 for a transposing read of rows that are 8 apart);
 // how the 64 addresses of an instruction fall into banks decides whether it gets there.
@@ -212,28 +205,16 @@ __device__ __forceinline__ void zero_rows_e16(e16_t* __restrict__ dst, int row_l
 // so that the line does not displace input rows another kernel of the same step re-reads
 // from this XCD's L2.
 __device__ __forceinline__ void store_streaming(void* dst, uint4 v) {
-#ifdef COTTN_PLAIN_OUTPUT_STORES
-  *reinterpret_cast<uint4*>(dst) = v;
-#else
   __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(dst));
-#endif
 }
 
 // Stores of segment states to the workspace: read next by workgroups on other XCDs, which this
 // XCD's L2 cannot serve, so they are marked non-temporal as well.
 __device__ __forceinline__ void store_state_word(float* dst, float v) {
-#ifdef COTTN_PLAIN_STATE_STORES
-  *dst = v;
-#else
   __builtin_nontemporal_store(v, dst);
-#endif
 }
 __device__ __forceinline__ void store_state_words(float* dst, f32x4 v) {
-#ifdef COTTN_PLAIN_STATE_STORES
-  *reinterpret_cast<f32x4*>(dst) = v;
-#else
   __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
-#endif
 }
 
 // In place, for 4 neighbouring elements of a stack of n matrices `stride` floats apart:

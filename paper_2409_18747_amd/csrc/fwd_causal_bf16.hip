@@ -77,14 +77,9 @@ struct FwdCfg {
 // Waves per 16-row group in the scan kernel (see the kernel), chosen per shape by measurement:
 // two at d = 128, where one workgroup fills the LDS of a compute unit and four waves are too
 // few to cover latencies (+6 % on a 2048-token prefill of 4096 heads); at d = 64 and 32 the
-// two variants time the same and the smaller workgroup is kept.  COTTN_FWD_SPLIT_ALL builds
-// the two-wave variant for every chunk-64 shape (tuning).
+// two variants time the same and the smaller workgroup is kept.
 template <int D, int C> struct FwdSplit { static constexpr int CS = 1; };
 template <> struct FwdSplit<128, 64> { static constexpr int CS = 2; };
-#ifdef COTTN_FWD_SPLIT_ALL
-template <> struct FwdSplit<64, 64> { static constexpr int CS = 2; };
-template <> struct FwdSplit<32, 64> { static constexpr int CS = 2; };
-#endif
 
 // ---------------------------------------------------------------------------------------
 // Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
@@ -242,8 +237,6 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   // with two waves on a row group the q rows stay live in the other wave: own staging tile
   __shared__ __attribute__((aligned(16))) e16_t Os[CS > 1 ? Cfg::TILE : 8];
   __shared__ float rq[C];
-
-  COTTN_TRACE_POINT(7);
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
@@ -310,7 +303,6 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
   e16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * TP;
   const int col0 = 16 * NOT * cp;  // first output column of this wave
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    COTTN_TRACE_POINT(0);
     // ---- publish the state (bf16) and this chunk's tiles
     if (ST::active(rg, cp)) {
 #pragma unroll
@@ -333,7 +325,6 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       kst.commit_scaled(Ks, rk);
       vst.commit_plain(Vs);
     }
-    COTTN_TRACE_POINT(1);
     if (row0 + C < row_end) {
       qst.fetch(Qu, row0 + C, row_end, stream_q != 0);
       kst.fetch(Ku, row0 + C, row_end);
@@ -341,9 +332,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     }
     if (row0 > row_begin)
       store_row_pieces<D, NOT>(finished, Ou, row0 - C + 16 * rg, row_end, l, col0);
-    COTTN_TRACE_POINT(2);
     __syncthreads();
-    COTTN_TRACE_POINT(3);
 
     // ---- inter-chunk part: O^T += S^T Q^T (contraction over d_key = rows of Sl)
     frag8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
@@ -365,8 +354,6 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       for (int nt = 0; nt < NOT; ++nt) oacc[nt] = mma16(sf[nt], qf[ks], oacc[nt]);
       __builtin_amdgcn_sched_barrier(0);
     }
-
-    COTTN_TRACE_POINT(4);
     // ---- intra-chunk part and state update, two key tiles (32 tokens) at a time
 #pragma unroll
     for (int p = 0; p < Cfg::NP; ++p) {
@@ -425,15 +412,12 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-
-    COTTN_TRACE_POINT(5);
     // ---- O rows: factor s_h r_i, staged through the wave's own (now dead) rows of Qs, or
     // through its part of the staging tile
     const float row_factor = scale * rq[16 * rg + r];
     wave_lds_sync();
     gather_rows_transposed<D, NOT>(oacc, row_factor, stage, l, finished, col0);
     __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
-    COTTN_TRACE_POINT(6);
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
