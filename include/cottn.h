@@ -38,6 +38,10 @@
  *   - Return value: COTTN_OK or a cottn_status error code.  Argument errors are detected
  *     before anything is enqueued (so they can be exercised without a GPU); HIP launch
  *     failures return COTTN_E_HIP.  No entry point throws, aborts or prints.
+ *   - Code shared between the passes: the backward has scan kernels of its own; what it
+ *     shares with the forward is the kernel that reduces Kh^T V (or Qh^T dO) over a segment
+ *     (the backward launches it only when it is not handed the forward's saved states), the
+ *     tile staging / normalisation helpers and the small state-carry kernels.
  *   - `workspace` must hold at least cottn_workspace_bytes(op, ...) bytes for the same
  *     arguments; it may be NULL when that size is 0.  Its contents on entry are ignored
  *     and on exit unspecified.  Calls that share a workspace must be ordered on one stream.
@@ -79,8 +83,12 @@ size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int 
 /* Number of sequence segments per (batch, head) the library will scan in parallel for
  * these arguments (1 = one serial chunk scan per (b, h)); 0 if unsupported.  Informational:
  * the chunked regrouping of the cumulative sum of eq. attn_2 is exact for any value.
- * cottn_tune_segments(g) forces the value for later calls in this process (g <= 0 restores
- * the built-in heuristic); it must not be called concurrently with other entry points. */
+ * cottn_tune_segments(g) forces the value for later calls made by the CALLING THREAD (g <= 0
+ * restores the built-in heuristic); it is a knob for tests and tuning runs and the only state
+ * the library keeps between calls besides the profiling totals below.  A backward call that is
+ * handed a forward's workspace assumes the split it computes itself: do not change the tuning
+ * between a forward call and the backward call that takes its workspace (the states would be
+ * read in another layout: wrong gradients, no error). */
 int cottn_segments(int op, int B, int H, int N, int d, int chunk, int dtype);
 void cottn_tune_segments(int segments);
 
@@ -239,7 +247,9 @@ int cottn_scale_backward_varlen(const float* m, const int* seq_len, const float*
  * recording.  The three getters read the totals gathered by the last start/stop pair:
  * cottn_profile_count() distinct kernel names, and for 0 <= i < count its name (static
  * storage), number of launches and summed duration in milliseconds.  Profiling adds the
- * cost of the event records to every launch; it is off by default.  Not thread-safe. */
+ * cost of the event records (and their creation) to every launch; it is off by default.
+ * Process-wide and not thread-safe: use it from one thread, with no other thread inside the
+ * library. */
 int cottn_profile_start(void);
 int cottn_profile_stop(void);
 int cottn_profile_count(void);

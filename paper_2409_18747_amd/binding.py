@@ -121,6 +121,46 @@ def _check(status, where):
         raise CottnError(status, where)
 
 
+def _rows_like(Q, **tensors):
+    """Q is a device tensor [B, H, N, d] (_dims checked the rank); every other row tensor given (None = absent) has
+    its shape, dtype and device.  The kernels take all of that from Q alone, so a mismatch would
+    be read or written out of bounds on the device: refuse it here."""
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if tuple(t.shape) != tuple(Q.shape) or t.dtype != Q.dtype or t.device != Q.device:
+            raise ValueError("%s must match Q (%s %s on %s), got %s %s on %s" % (
+                name, tuple(Q.shape), Q.dtype, Q.device, tuple(t.shape), t.dtype, t.device))
+
+
+def _tokens_like(q, **tensors):
+    for name, t in tensors.items():
+        if tuple(t.shape) != tuple(q.shape) or t.dtype != q.dtype or t.device != q.device:
+            raise ValueError("%s must match q (%s %s on %s), got %s %s on %s" % (
+                name, tuple(q.shape), q.dtype, q.device, tuple(t.shape), t.dtype, t.device))
+
+
+def _on_gpu(t):
+    if not t.is_cuda:
+        raise ValueError("tensors must live on the GPU, got %s" % t.device)
+
+
+def _f32(name, t, numel, device, optional=False):
+    """t is a float32 tensor of `numel` elements on `device` (the kernels index it blindly)."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError("%s is required" % name)
+    if t.dtype != torch.float32 or t.numel() != numel or t.device != device:
+        raise ValueError("%s must be float32 with %d elements on %s, got %s with %d on %s" % (
+            name, numel, device, t.dtype, t.numel(), t.device))
+
+
+def _check_lengths(seq_len, B, device):
+    if seq_len.dtype != torch.int32 or seq_len.numel() != B or seq_len.device != device:
+        raise TypeError("seq_len must be an int32 tensor of B = %d elements on %s" % (B, device))
+
+
 def cottn_status_string(status: int) -> str:
     return lib.cottn_status_string(int(status)).decode()
 
@@ -140,23 +180,55 @@ def cottn_tune_segments(segments: int) -> None:
     lib.cottn_tune_segments(int(segments))
 
 
-def _workspace(op, B, H, N, d, chunk, dtype, device, workspace):
+def _workspace(op, B, H, N, d, chunk, dtype, device, workspace, stream=None):
     need = cottn_workspace_bytes(op, B, H, N, d, chunk, dtype)
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        # a temporary is dropped when the call returns, while the kernels may still be queued:
+        # tell the allocator which stream uses it, so the memory is not handed out before they ran
+        if stream is not None:
+            workspace.record_stream(stream)
+    elif workspace is not None and (not workspace.is_cuda or workspace.device != device):
+        raise ValueError("workspace must live on %s" % device)
     have = workspace.numel() * workspace.element_size() if workspace is not None else 0
     return workspace, have
+
+
+def _bytes(t, device):
+    if t is None:
+        return 0
+    if t.device != device:
+        raise ValueError("fwd_workspace must live on %s" % device)
+    return t.numel() * t.element_size()
+
+
+def _dims(Q):
+    if Q.dim() != 4:
+        raise ValueError("Q must be [B, H, N, d], got shape %s" % (tuple(Q.shape),))
+    B, H, N, d = Q.shape
+    return B, H, N, d, _dtype_code(Q)
+
+
+def _grads(Q, dQ, dK, dV, ds, ds_shape):
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    ds = torch.empty(ds_shape, dtype=torch.float32, device=Q.device) if ds is None else ds
+    return dQ, dK, dV, ds
 
 
 def cottn_fwd_causal(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, eps=1e-6,
                      stream=None):
     """O = s_h (Qhat Khat^T (.) M) V; returns O (allocated if not given).  `state`, if given,
     receives sum_j khat_j^T v_j as float32 [B, H, d, d]."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
+    B, H, N, d, dt = _dims(Q)
     if O is None:
         O = torch.empty_like(Q)
-    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    _rows_like(Q, K=K, V=V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_fwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
                               _ptr(workspace), have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_fwd_causal")
@@ -170,8 +242,11 @@ def cottn_fwd_causal_static(Q, K, V, s, O, state=None, chunk=0, eps=1e-6, stream
     """cottn_fwd_causal without a workspace argument, for callers that cannot allocate: the
     segment states live in an array inside the library.  O must be given (nothing is allocated
     here either); returns O."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
+    B, H, N, d, dt = _dims(Q)
+    _rows_like(Q, K=K, V=V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
     st = lib.cottn_fwd_causal_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state), B, H,
                                      N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_fwd_causal_static")
@@ -182,11 +257,15 @@ def cottn_fwd_causal_from_state(Q, K, V, s, state_in, O=None, state=None, worksp
                                 eps=1e-6, stream=None):
     """cottn_fwd_causal for a piece of a longer sequence: starts from `state_in` (float32
     [B, H, d, d]) and leaves the state after the piece in `state` (a different tensor)."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
+    B, H, N, d, dt = _dims(Q)
     if O is None:
         O = torch.empty_like(Q)
-    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    _rows_like(Q, K=K, V=V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state_in", state_in, B * H * d * d, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_fwd_causal_from_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(state_in), _ptr(O),
                                          _ptr(state), _ptr(workspace), have, B, H, N, d, chunk, dt,
                                          eps, _stream(stream))
@@ -200,17 +279,16 @@ def cottn_bwd_causal(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspa
 
     fwd_workspace: the workspace tensor the matching cottn_fwd_causal call used (untouched
     since), or None; see include/cottn.h."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(Q) if dK is None else dK
-    dV = torch.empty_like(Q) if dV is None else dV
-    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
-    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
-    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    B, H, N, d, dt = _dims(Q)
+    dQ, dK, dV, ds = _grads(Q, dQ, dK, dV, ds, (H,))
+    _rows_like(Q, K=K, V=V, dO=dO, dQ=dQ, dK=dK, dV=dV)
+    _f32("s", s, H, Q.device)
+    _f32("ds", ds, H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_bwd_causal(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
-                              _ptr(dV), _ptr(ds), _ptr(fwd_workspace), fwd_have, _ptr(workspace),
-                              have, B, H, N, d, chunk, dt, eps, _stream(stream))
+                              _ptr(dV), _ptr(ds), _ptr(fwd_workspace), _bytes(fwd_workspace, Q.device),
+                              _ptr(workspace), have, B, H, N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_causal")
     return dQ, dK, dV, ds
 
@@ -221,30 +299,35 @@ def cottn_bwd_causal_from_state(Q, K, V, s, dO, state_in=None, rev_state_in=None
     """cottn_bwd_causal for one piece of a sequence processed in pieces: state_in is the
     forward-time state before the piece, rev_state_in the reverse-time state after it;
     returns (dQ, dK, dV, ds) and fills rev_state_out (float32 [B, H, d, d]) when given."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(Q) if dK is None else dK
-    dV = torch.empty_like(Q) if dV is None else dV
-    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
-    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
-    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    B, H, N, d, dt = _dims(Q)
+    dQ, dK, dV, ds = _grads(Q, dQ, dK, dV, ds, (H,))
+    _rows_like(Q, K=K, V=V, dO=dO, dQ=dQ, dK=dK, dV=dV)
+    _f32("s", s, H, Q.device)
+    _f32("ds", ds, H, Q.device)
+    for name, t in (("state_in", state_in), ("rev_state_in", rev_state_in),
+                    ("rev_state_out", rev_state_out)):
+        _f32(name, t, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_bwd_causal_from_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(state_in),
                                          _ptr(rev_state_in), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds),
-                                         _ptr(rev_state_out), _ptr(fwd_workspace), fwd_have,
-                                         _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
-                                         _stream(stream))
+                                         _ptr(rev_state_out), _ptr(fwd_workspace),
+                                         _bytes(fwd_workspace, Q.device), _ptr(workspace), have, B, H,
+                                         N, d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_causal_from_state")
     return dQ, dK, dV, ds
 
 
 def cottn_fwd_bidir(Q, K, V, s, O=None, state=None, workspace=None, eps=1e-6, stream=None):
     """O = s_h Qhat (Khat^T V); returns O."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
+    B, H, N, d, dt = _dims(Q)
     if O is None:
         O = torch.empty_like(Q)
-    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    _rows_like(Q, K=K, V=V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace, stream)
     st = lib.cottn_fwd_bidir(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
                              _ptr(workspace), have, B, H, N, d, dt, eps, _stream(stream))
     _check(st, "cottn_fwd_bidir")
@@ -255,35 +338,32 @@ def cottn_bwd_bidir(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspac
                     stream=None, fwd_workspace=None):
     """Gradients of cottn_fwd_bidir; returns (dQ, dK, dV, ds).  fwd_workspace: the workspace
     tensor of the matching cottn_fwd_bidir call (untouched since), or None."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(Q) if dK is None else dK
-    dV = torch.empty_like(Q) if dV is None else dV
-    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
-    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
-    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    B, H, N, d, dt = _dims(Q)
+    dQ, dK, dV, ds = _grads(Q, dQ, dK, dV, ds, (H,))
+    _rows_like(Q, K=K, V=V, dO=dO, dQ=dQ, dK=dK, dV=dV)
+    _f32("s", s, H, Q.device)
+    _f32("ds", ds, H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace, stream)
     st = lib.cottn_bwd_bidir(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
-                             _ptr(dV), _ptr(ds), _ptr(fwd_workspace), fwd_have, _ptr(workspace),
-                             have, B, H, N, d, dt, eps, _stream(stream))
+                             _ptr(dV), _ptr(ds), _ptr(fwd_workspace), _bytes(fwd_workspace, Q.device),
+                             _ptr(workspace), have, B, H, N, d, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_bidir")
     return dQ, dK, dV, ds
-
-
-def _check_lengths(seq_len, B):
-    if seq_len.dtype != torch.int32 or seq_len.numel() != B:
-        raise TypeError("seq_len must be an int32 tensor of B elements")
 
 
 def cottn_fwd_causal_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=None, chunk=0,
                             eps=1e-6, stream=None):
     """cottn_fwd_causal for a padded batch: seq_len int32 [B], s float32 [B, H]."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    _check_lengths(seq_len, B)
+    B, H, N, d, dt = _dims(Q)
     if O is None:
         O = torch.empty_like(Q)
-    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
+    _rows_like(Q, K=K, V=V, O=O)
+    _check_lengths(seq_len, B, Q.device)
+    _f32("s", s, B * H, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_FWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_fwd_causal_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(O),
                                      _ptr(state), _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
                                      _stream(stream))
@@ -294,19 +374,18 @@ def cottn_fwd_causal_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=N
 def cottn_bwd_causal_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, ds=None,
                             workspace=None, chunk=0, eps=1e-6, stream=None, fwd_workspace=None):
     """cottn_bwd_causal for a padded batch; returns (dQ, dK, dV, ds) with ds float32 [B, H]."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    _check_lengths(seq_len, B)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(Q) if dK is None else dK
-    dV = torch.empty_like(Q) if dV is None else dV
-    ds = torch.empty(B, H, dtype=torch.float32, device=Q.device) if ds is None else ds
-    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace)
-    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    B, H, N, d, dt = _dims(Q)
+    dQ, dK, dV, ds = _grads(Q, dQ, dK, dV, ds, (B, H))
+    _rows_like(Q, K=K, V=V, dO=dO, dQ=dQ, dK=dK, dV=dV)
+    _check_lengths(seq_len, B, Q.device)
+    _f32("s", s, B * H, Q.device)
+    _f32("ds", ds, B * H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_BWD_CAUSAL, B, H, N, d, chunk, dt, Q.device, workspace, stream)
     st = lib.cottn_bwd_causal_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(dO),
                                      _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
-                                     fwd_have, _ptr(workspace), have, B, H, N, d, chunk, dt, eps,
-                                     _stream(stream))
+                                     _bytes(fwd_workspace, Q.device), _ptr(workspace), have, B, H, N,
+                                     d, chunk, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_causal_varlen")
     return dQ, dK, dV, ds
 
@@ -314,12 +393,15 @@ def cottn_bwd_causal_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, 
 def cottn_fwd_bidir_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=None, eps=1e-6,
                            stream=None):
     """cottn_fwd_bidir for a padded batch: seq_len int32 [B], s float32 [B, H]."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    _check_lengths(seq_len, B)
+    B, H, N, d, dt = _dims(Q)
     if O is None:
         O = torch.empty_like(Q)
-    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
+    _rows_like(Q, K=K, V=V, O=O)
+    _check_lengths(seq_len, B, Q.device)
+    _f32("s", s, B * H, Q.device)
+    _f32("state", state, B * H * d * d, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_FWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace, stream)
     st = lib.cottn_fwd_bidir_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(O),
                                     _ptr(state), _ptr(workspace), have, B, H, N, d, dt, eps,
                                     _stream(stream))
@@ -330,19 +412,18 @@ def cottn_fwd_bidir_varlen(Q, K, V, s, seq_len, O=None, state=None, workspace=No
 def cottn_bwd_bidir_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, ds=None,
                            workspace=None, eps=1e-6, stream=None, fwd_workspace=None):
     """cottn_bwd_bidir for a padded batch; returns (dQ, dK, dV, ds) with ds float32 [B, H]."""
-    B, H, N, d = Q.shape
-    dt = _dtype_code(Q)
-    _check_lengths(seq_len, B)
-    dQ = torch.empty_like(Q) if dQ is None else dQ
-    dK = torch.empty_like(Q) if dK is None else dK
-    dV = torch.empty_like(Q) if dV is None else dV
-    ds = torch.empty(B, H, dtype=torch.float32, device=Q.device) if ds is None else ds
-    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace)
-    fwd_have = 0 if fwd_workspace is None else fwd_workspace.numel() * fwd_workspace.element_size()
+    B, H, N, d, dt = _dims(Q)
+    dQ, dK, dV, ds = _grads(Q, dQ, dK, dV, ds, (B, H))
+    _rows_like(Q, K=K, V=V, dO=dO, dQ=dQ, dK=dK, dV=dV)
+    _check_lengths(seq_len, B, Q.device)
+    _f32("s", s, B * H, Q.device)
+    _f32("ds", ds, B * H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace(OP_BWD_BIDIR, B, H, N, d, 0, dt, Q.device, workspace, stream)
     st = lib.cottn_bwd_bidir_varlen(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(seq_len), _ptr(dO),
                                     _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
-                                    fwd_have, _ptr(workspace), have, B, H, N, d, dt, eps,
-                                    _stream(stream))
+                                    _bytes(fwd_workspace, Q.device), _ptr(workspace), have, B, H, N,
+                                    d, dt, eps, _stream(stream))
     _check(st, "cottn_bwd_bidir_varlen")
     return dQ, dK, dV, ds
 
@@ -350,8 +431,11 @@ def cottn_bwd_bidir_varlen(Q, K, V, s, seq_len, dO, dQ=None, dK=None, dV=None, d
 def cottn_scale_from_m_varlen(m, seq_len, s=None, stream=None):
     """s[b, h] = seq_len[b]^(-sigmoid(m[h]))."""
     B, H = seq_len.numel(), m.numel()
-    _check_lengths(seq_len, B)
+    _f32("m", m, H, m.device)
+    _check_lengths(seq_len, B, m.device)
     s = torch.empty(B, H, dtype=torch.float32, device=m.device) if s is None else s
+    _f32("s", s, B * H, m.device)
+    _on_gpu(m)
     _check(lib.cottn_scale_from_m_varlen(_ptr(m), _ptr(seq_len), _ptr(s), B, H, _stream(stream)),
            "cottn_scale_from_m_varlen")
     return s
@@ -360,8 +444,12 @@ def cottn_scale_from_m_varlen(m, seq_len, s=None, stream=None):
 def cottn_scale_backward_varlen(m, seq_len, ds, dm=None, stream=None):
     """dm[h] = sum_b ds[b, h] * d s[b, h] / d m[h]."""
     B, H = seq_len.numel(), m.numel()
-    _check_lengths(seq_len, B)
+    _f32("m", m, H, m.device)
+    _check_lengths(seq_len, B, m.device)
+    _f32("ds", ds, B * H, m.device)
     dm = torch.empty(H, dtype=torch.float32, device=m.device) if dm is None else dm
+    _f32("dm", dm, H, m.device)
+    _on_gpu(m)
     _check(lib.cottn_scale_backward_varlen(_ptr(m), _ptr(seq_len), _ptr(ds), _ptr(dm), B, H,
                                            _stream(stream)), "cottn_scale_backward_varlen")
     return dm
@@ -369,10 +457,16 @@ def cottn_scale_backward_varlen(m, seq_len, ds, dm=None, stream=None):
 
 def cottn_step(q, k, v, s, state, o=None, eps=1e-6, stream=None):
     """state += khat^T v (in place); returns o = s_h qhat state.  q, k, v are [B, H, d]."""
+    if q.dim() != 3:
+        raise ValueError("q must be [B, H, d], got shape %s" % (tuple(q.shape),))
     B, H, d = q.shape
     dt = _dtype_code(q)
     if o is None:
         o = torch.empty_like(q)
+    _tokens_like(q, k=k, v=v, o=o)
+    _f32("s", s, H, q.device)
+    _f32("state", state, B * H * d * d, q.device)
+    _on_gpu(q)
     st = lib.cottn_step(_ptr(q), _ptr(k), _ptr(v), _ptr(s), _ptr(state), _ptr(o), B, H, d, dt,
                         eps, _stream(stream))
     _check(st, "cottn_step")
@@ -382,7 +476,10 @@ def cottn_step(q, k, v, s, state, o=None, eps=1e-6, stream=None):
 def cottn_scale_from_m(m, n, s=None, stream=None):
     """s[h] = n^(-sigmoid(m[h])): the stabiliser of Sec. 3.3 as the factor the attention calls take."""
     H = m.numel()
+    _f32("m", m, H, m.device)
     s = torch.empty(H, dtype=torch.float32, device=m.device) if s is None else s
+    _f32("s", s, H, m.device)
+    _on_gpu(m)
     _check(lib.cottn_scale_from_m(_ptr(m), _ptr(s), H, float(n), _stream(stream)), "cottn_scale_from_m")
     return s
 
@@ -390,7 +487,11 @@ def cottn_scale_from_m(m, n, s=None, stream=None):
 def cottn_scale_backward(m, n, ds, dm=None, stream=None):
     """dm[h] = ds[h] * ds_h/dm_h for s_h = n^(-sigmoid(m_h))."""
     H = m.numel()
+    _f32("m", m, H, m.device)
+    _f32("ds", ds, H, m.device)
     dm = torch.empty(H, dtype=torch.float32, device=m.device) if dm is None else dm
+    _f32("dm", dm, H, m.device)
+    _on_gpu(m)
     _check(lib.cottn_scale_backward(_ptr(m), _ptr(ds), _ptr(dm), H, float(n), _stream(stream)),
            "cottn_scale_backward")
     return dm

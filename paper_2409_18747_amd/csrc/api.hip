@@ -16,7 +16,8 @@
 namespace cottn {
 namespace {
 
-int g_tuned_segments = 0;  // <= 0: heuristic
+// <= 0: heuristic.  Per thread: a thread that tunes does not change what other threads get.
+thread_local int g_tuned_segments = 0;
 
 // ---- profiling state -------------------------------------------------------------------
 struct PendingSpan { const char* name; hipEvent_t begin, end; };

@@ -55,8 +55,11 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
                                                      float* __restrict__ state,
                                                      float* __restrict__ ds_partial) {
   __shared__ float red[4];
-  const int unit = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
+  // one grid dimension: (unit, 256-element block of the matrix), so that B*H is not limited to
+  // the 65535 of the other grid dimensions
+  const int blocks_per_unit = elems / 256;
+  const int unit = blockIdx.x / blocks_per_unit, blk = blockIdx.x % blocks_per_unit;
+  const int e = blk * 256 + threadIdx.x;
   float* p0 = totals + size_t(unit) * G * elems;
   float* p1 = p0 + pair_stride;
   float a = 0.f;
@@ -71,7 +74,7 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
     if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = prod;
     __syncthreads();
     if (threadIdx.x == 0)
-      ds_partial[size_t(unit) * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+      ds_partial[size_t(unit) * blocks_per_unit + blk] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
 
@@ -389,7 +392,7 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
 #ifndef COTTN_ELEM_F16  // not specific to the element type: defined once, by the bf16 build
 hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, int units, int G,
                                 int elems, float* state, float* ds_partial, hipStream_t st) {
-  return launch_kernel("bidir_combine", bidir_combine, dim3(elems / 256, units), dim3(256), 0, st,
+  return launch_kernel("bidir_combine", bidir_combine, dim3(unsigned(elems / 256) * units), dim3(256), 0, st,
                        totals, pair_stride, n_pairs, G, elems, state, ds_partial);
 }
 #endif

@@ -39,8 +39,10 @@ def to_host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def ds_terms_rss(oracle, x, causal=True):
-    """Root-sum-square, per head, of the terms P_ij * A_ij whose (signed) sum is ds[h].
+def ds_terms_rss(oracle, x, causal=True, lens=None, per_unit=False):
+    """Root-sum-square of the terms P_ij * A_ij whose (signed) sum is ds: per head (summed over
+    the batch, as ds[h] is), or per (batch, head) with per_unit (as ds[b][h] of the padded-batch
+    calls is).  lens: rows at or beyond lens[b] do not exist.
 
     ds is a long sum of terms of both signs; when it happens to cancel, |ds| is far below the
     size of what was added up and a relative error against |ds| alone measures the
@@ -51,21 +53,33 @@ def ds_terms_rss(oracle, x, causal=True):
     """
     Q, K, V, dO = (np.asarray(x[k], dtype=np.float64) for k in ("Q", "K", "V", "dO"))
     B, H, N, d = Q.shape
-    acc = np.zeros(H)
+    acc = np.zeros((B, H))
     for b in range(B):
+        n = N if lens is None else int(lens[b])
+        if n == 0:
+            continue
         for h in range(H):
-            P = oracle.similarity(Q[b, h], K[b, h])
-            A = dO[b, h] @ V[b, h].T
+            P = oracle.similarity(Q[b, h, :n], K[b, h, :n])
+            A = dO[b, h, :n] @ V[b, h, :n].T
             T = P * A
             if causal:
                 T = np.tril(T)
-            acc[h] += (T ** 2).sum()
-    return np.sqrt(acc)
+            acc[b, h] = (T ** 2).sum()
+    return np.sqrt(acc) if per_unit else np.sqrt(acc.sum(0))
 
 
 def rel_err_ds(got, ref, rss):
-    """max_h |got - ref| / max(max_h |ref|, max_h rss_h)."""
+    """max |got - ref| / max(max |ref|, max rss): the stated tensor-relative metric whenever ds
+    does not cancel below the size of its own terms (then the two denominators coincide)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     den = max(np.abs(ref).max(), float(np.max(rss)))
     return float(np.abs(got - ref).max() / den) if den > 0 else float(np.abs(got).max())
+
+
+def ds_errors(got, ref, rss):
+    """{"ds": the asserted metric (rel_err_ds), "ds_plain": max|got-ref|/max|ref|, reported, and
+    "ds_cancels": whether the two differ (max|ref| below the scale of the terms)}."""
+    ref = np.asarray(ref, dtype=np.float64)
+    return {"ds": rel_err_ds(got, ref, rss), "ds_plain": rel_err(got, ref),
+            "ds_cancels": bool(np.abs(ref).max() < float(np.max(rss)))}
