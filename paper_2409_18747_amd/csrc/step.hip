@@ -25,13 +25,21 @@ template <typename T> struct Elem {
   }
 };
 
-__device__ __forceinline__ float4 load_state_row(const float* p) {
+// Cache policy of the state stream.  The updated state is always written with non-temporal
+// stores: nothing reads a written line again before the whole set of states has passed through
+// the caches.  The loads are non-temporal too (`stream`, uniform over the launch) when the
+// states of the call exceed what the L2s hold (32 MB): a decoder has a set of states per layer,
+// so by the time a step comes back to this set it has left the caches, every step reads it from
+// HBM, and lines left behind only get in the way (4096 states of 128 x 128, rotating over three
+// such sets: 89.6 us per step against 107.8 us with plain loads).  A small set of states is
+// re-read from the L2 by the next step, and there plain loads win.
+__device__ __forceinline__ float4 load_state_row(const float* p, bool stream) {
+  if (stream) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return float4{v[0], v[1], v[2], v[3]};
+  }
   return *reinterpret_cast<const float4*>(p);
 }
-// The updated state is written with non-temporal stores: by the time the next step reads a
-// state again, 512 MiB have passed through the caches, so keeping the written lines only costs
-// (measured: 79.4 us per step against 83.4 us with plain stores; non-temporal loads on top of
-// that are slower, 90 us).
 __device__ __forceinline__ void store_state_row(float* p, float4 x) {
   __builtin_nontemporal_store(f32x4{x.x, x.y, x.z, x.w}, reinterpret_cast<f32x4*>(p));
 }
@@ -39,7 +47,8 @@ __device__ __forceinline__ void store_state_row(float* p, float4 x) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_step_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
-    const float* __restrict__ s, float* __restrict__ state, T* __restrict__ o, int H, float eps) {
+    const float* __restrict__ s, float* __restrict__ state, T* __restrict__ o, int H, float eps,
+    int stream_state) {
   constexpr int TPR = D / 4;          // threads per state row
   constexpr int RPP = 256 / TPR;      // rows per pass
   constexpr int PASSES = D / RPP;
@@ -84,7 +93,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(
   float4 rows[PASSES];
 #pragma unroll
   for (int p = 0; p < PASSES; ++p)
-    rows[p] = load_state_row(Su + size_t(p * RPP + row_in_pass) * D + col);
+    rows[p] = load_state_row(Su + size_t(p * RPP + row_in_pass) * D + col, stream_state != 0);
   __syncthreads();
 
   float4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -121,16 +130,17 @@ hipError_t run_step(const StepArgs& a) {
   const T* v = static_cast<const T*>(a.v);
   T* o = static_cast<T*>(a.o);
   const dim3 grid(units), block(256);
+  const int stream_state = double(units) * a.d * a.d * sizeof(float) > 32.0 * 1024 * 1024 ? 1 : 0;
   switch (a.d) {
     case 32:
       return launch_kernel("decode_step_kernel", decode_step_kernel<T, 32>, grid, block, 0, a.stream,
-                           q, k, v, a.s, a.state, o, a.H, a.eps);
+                           q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
     case 64:
       return launch_kernel("decode_step_kernel", decode_step_kernel<T, 64>, grid, block, 0, a.stream,
-                           q, k, v, a.s, a.state, o, a.H, a.eps);
+                           q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
     case 128:
       return launch_kernel("decode_step_kernel", decode_step_kernel<T, 128>, grid, block, 0,
-                           a.stream, q, k, v, a.s, a.state, o, a.H, a.eps);
+                           a.stream, q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
     default:
       return hipErrorInvalidValue;
   }
