@@ -34,7 +34,13 @@
  *     nothing but define the outputs that do not depend on rows); chunk in {0, 64, 128, 256}
  *     for the 16-bit types (0 = library default, 64; d = 128 supports 64 only), and chunk in
  *     {0, 32} for fp32.
- *     N need not be a multiple of chunk.
+ *     N need not be a multiple of chunk.  64 is the tuned chunk size: 128 and 256 are exact
+ *     and tested but slower in this design (more registers than two workgroups per compute
+ *     unit leave a wave), and are kept for experiments with the state traffic.
+ *   - The paper keeps two head dimensions apart (Sec. 2.1: d_H_key for queries and keys,
+ *     d_H_value for values and outputs; its experiments use equal ones).  The entry points
+ *     with one `d` take d_key = d_value = d; the *_dkdv entry points at the end of this header
+ *     take both.
  *   - Return value: COTTN_OK or a cottn_status error code.  Argument errors are detected
  *     before anything is enqueued (so they can be exercised without a GPU); HIP launch
  *     failures return COTTN_E_HIP.  No entry point throws, aborts or prints.
@@ -220,6 +226,36 @@ int cottn_bwd_bidir_varlen(const void* Q, const void* K, const void* V, const fl
  * (the state is read AFTER the update).  q, k, v, o are [B][H][d] in `dtype`. */
 int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
                void* o, int B, int H, int d, int dtype, float eps, void* hip_stream);
+
+/* ---- d_key != d_value (Sec. 2.1: d_H_key, d_H_value) ----------------------------------------
+ * The same operations with queries and keys of dk features and values of dv features:
+ *   Q, K, dQ, dK are [B][H][N][dk];  V, O, dO, dV are [B][H][N][dv];  q, k are [B][H][dk] and
+ *   v, o [B][H][dv];  every state is float[B][H][dk][dv] = sum_j kh_j^T v_j.
+ * dk and dv are each one of 32, 64, 128.  With dk == dv these calls are the ones above.  With
+ * dk != dv: the 16-bit types only (COTTN_F32 gives COTTN_E_SHAPE) and chunk 0 or 64.
+ * Everything else (workspaces, fwd_workspace, errors, conventions) is as for the functions
+ * without the suffix; sizes and splits come from the *_dkdv variants of the two queries. */
+size_t cottn_workspace_bytes_dkdv(int op, int B, int H, int N, int dk, int dv, int chunk,
+                                  int dtype);
+int cottn_segments_dkdv(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype);
+int cottn_fwd_causal_dkdv(const void* Q, const void* K, const void* V, const float* s, void* O,
+                          float* state, void* workspace, size_t workspace_bytes, int B, int H,
+                          int N, int dk, int dv, int chunk, int dtype, float eps, void* hip_stream);
+int cottn_bwd_causal_dkdv(const void* Q, const void* K, const void* V, const float* s,
+                          const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                          const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                          size_t workspace_bytes, int B, int H, int N, int dk, int dv, int chunk,
+                          int dtype, float eps, void* hip_stream);
+int cottn_fwd_bidir_dkdv(const void* Q, const void* K, const void* V, const float* s, void* O,
+                         float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                         int dk, int dv, int dtype, float eps, void* hip_stream);
+int cottn_bwd_bidir_dkdv(const void* Q, const void* K, const void* V, const float* s,
+                         const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                         const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                         size_t workspace_bytes, int B, int H, int N, int dk, int dv, int dtype,
+                         float eps, void* hip_stream);
+int cottn_step_dkdv(const void* q, const void* k, const void* v, const float* s, float* state,
+                    void* o, int B, int H, int dk, int dv, int dtype, float eps, void* hip_stream);
 
 /* The learned stabiliser of Sec. 3.3 (eq. cosine2): scores are divided by n^sigma(m_h), n the
  * sequence length, m_h a learned scalar per head (the paper starts it at 0.5).  The entry

@@ -5,8 +5,9 @@ TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke`` a
 imports the product package.  Every function converts its inputs to contiguous float64
 (bf16/fp32 values convert exactly) and returns fresh float64 arrays.
 
-Shapes: Q, K, V, dO are [B, H, N, d]; s is [H]; states are [B, H, d, d] stored
-[d_key][d_value] and do not contain the scale s.
+Shapes: Q, K (and dQ, dK) are [B, H, N, d_key]; V, dO (and O, dV) are [B, H, N, d_value]
+(Sec. 2.1 keeps the two head dimensions apart; every configuration of the paper has them
+equal); s is [H]; states are [B, H, d_key, d_value] and do not contain the scale s.
 """
 import ctypes
 import os
@@ -45,9 +46,12 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
-def _dims(Q):
+def _dims(Q, V):
+    """B, H, N, d_key (of Q, K), d_value (of V, O, dO) as C ints."""
     B, H, N, d = Q.shape
-    return ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(N), ctypes.c_int(d)
+    e = V.shape[-1]
+    assert V.shape[:-1] == Q.shape[:-1], (Q.shape, V.shape)
+    return ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(N), ctypes.c_int(d), ctypes.c_int(e)
 
 
 def normalize_rows(X, eps=1e-6):
@@ -74,8 +78,8 @@ def similarity(Q, K, eps=1e-6):
 def fwd_quadratic(Q, K, V, s, eps=1e-6, causal=True):
     """The definition: s_h (Qhat Khat^T (.) M) V, or without mask (Sec. 4)."""
     Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
-    O = np.empty_like(Q)
-    _load().oracle_fwd_quadratic(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+    O = np.empty_like(V)
+    _load().oracle_fwd_quadratic(_p(Q), _p(K), _p(V), _p(s), *_dims(Q, V), ctypes.c_double(eps),
                                  ctypes.c_int(1 if causal else 0), _p(O))
     return O
 
@@ -85,39 +89,40 @@ def fwd_recurrent(Q, K, V, s, eps=1e-6, S0=None):
     Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
     B, H, N, d = Q.shape
     S0 = _f64(S0) if S0 is not None else None
-    O = np.empty_like(Q)
-    S = np.empty((B, H, d, d), dtype=np.float64)
-    _load().oracle_fwd_recurrent(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+    O = np.empty_like(V)
+    S = np.empty((B, H, d, V.shape[-1]), dtype=np.float64)
+    _load().oracle_fwd_recurrent(_p(Q), _p(K), _p(V), _p(s), *_dims(Q, V), ctypes.c_double(eps),
                                  _p(S0), _p(O), _p(S))
     return O, S
 
 
 def state_total(K, V, eps=1e-6):
-    """Khat^T V over the whole sequence, [B, H, d, d] (Sec. 4, eq. subQuadCos right bracket)."""
+    """Khat^T V over the whole sequence, [B, H, d_key, d_value] (Sec. 4, eq. subQuadCos right bracket)."""
     K, V = _f64(K), _f64(V)
     B, H, N, d = K.shape
-    S = np.empty((B, H, d, d), dtype=np.float64)
-    _load().oracle_state_total(_p(K), _p(V), *_dims(K), ctypes.c_double(eps), _p(S))
+    S = np.empty((B, H, d, V.shape[-1]), dtype=np.float64)
+    _load().oracle_state_total(_p(K), _p(V), *_dims(K, V), ctypes.c_double(eps), _p(S))
     return S
 
 
 def step(q, k, v, s, S, eps=1e-6):
-    """One decode step; q, k, v are [B, H, d]; returns (o, new state) without touching S."""
+    """One decode step; q, k are [B, H, d_key], v [B, H, d_value]; returns (o, new state)
+    without touching S."""
     q, k, v, s = _f64(q), _f64(k), _f64(v), _f64(s)
     S = _f64(S).copy()
     B, H, d = q.shape
-    o = np.empty_like(q)
+    o = np.empty_like(v)
     _load().oracle_step(_p(q), _p(k), _p(v), _p(s), _p(S), ctypes.c_int(B), ctypes.c_int(H),
-                        ctypes.c_int(d), ctypes.c_double(eps), _p(o))
+                        ctypes.c_int(d), ctypes.c_int(v.shape[-1]), ctypes.c_double(eps), _p(o))
     return o, S
 
 
 def bwd_quadratic(Q, K, V, s, dO, eps=1e-6, causal=True):
     """Brute-force gradients wrt raw Q, K, V and s; returns (dQ, dK, dV, ds)."""
     Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
-    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(V)
     ds = np.empty_like(s)
-    _load().oracle_bwd_quadratic(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q),
+    _load().oracle_bwd_quadratic(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q, V),
                                  ctypes.c_double(eps), ctypes.c_int(1 if causal else 0),
                                  _p(dQ), _p(dK), _p(dV), _p(ds))
     return dQ, dK, dV, ds
@@ -126,9 +131,9 @@ def bwd_quadratic(Q, K, V, s, dO, eps=1e-6, causal=True):
 def bwd_recurrent(Q, K, V, s, dO, eps=1e-6):
     """Linear-time causal gradients (forward and reverse cumulative sums, Sec. 4)."""
     Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
-    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(V)
     ds = np.empty_like(s)
-    _load().oracle_bwd_recurrent(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q),
+    _load().oracle_bwd_recurrent(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q, V),
                                  ctypes.c_double(eps), _p(dQ), _p(dK), _p(dV), _p(ds))
     return dQ, dK, dV, ds
 
@@ -139,23 +144,23 @@ def _rows(rows):
 
 
 def fwd_rows(Q, K, V, s, rows, eps=1e-6, causal=True):
-    """Rows (b, h, i) of the definition, each from its own sum; returns [len(rows), d]."""
+    """Rows (b, h, i) of the definition, each from its own sum; returns [len(rows), d_value]."""
     Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
     r, rp, n = _rows(rows)
-    out = np.empty((r.shape[0], Q.shape[-1]), dtype=np.float64)
-    _load().oracle_fwd_rows(_p(Q), _p(K), _p(V), _p(s), *_dims(Q), ctypes.c_double(eps),
+    out = np.empty((r.shape[0], V.shape[-1]), dtype=np.float64)
+    _load().oracle_fwd_rows(_p(Q), _p(K), _p(V), _p(s), *_dims(Q, V), ctypes.c_double(eps),
                             ctypes.c_int(1 if causal else 0), rp, n, _p(out))
     return out
 
 
 def bwd_rows(Q, K, V, s, dO, rows, eps=1e-6, causal=True):
-    """Rows (b, h, t) of the brute-force dQ, dK, dV; returns three [len(rows), d] arrays."""
+    """Rows (b, h, t) of the brute-force dQ, dK ([len(rows), d_key]) and dV ([len(rows), d_value])."""
     Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
     r, rp, n = _rows(rows)
     d = Q.shape[-1]
     dQ = np.empty((r.shape[0], d), dtype=np.float64)
-    dK, dV = np.empty_like(dQ), np.empty_like(dQ)
-    _load().oracle_bwd_rows(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q), ctypes.c_double(eps),
+    dK, dV = np.empty_like(dQ), np.empty((r.shape[0], V.shape[-1]), dtype=np.float64)
+    _load().oracle_bwd_rows(_p(Q), _p(K), _p(V), _p(s), _p(dO), *_dims(Q, V), ctypes.c_double(eps),
                             ctypes.c_int(1 if causal else 0), rp, n, _p(dQ), _p(dK), _p(dV))
     return dQ, dK, dV
 
@@ -188,8 +193,8 @@ def fwd_varlen(Q, K, V, s, seq_len, eps=1e-6, causal=True):
     """Returns (O, state): O zero on rows that do not exist; state [B, H, d, d] over the rows that do."""
     Q, K, V, s = _f64(Q), _f64(K), _f64(V), _f64(s)
     B, H, N, d = Q.shape
-    O = np.zeros_like(Q)
-    S = np.zeros((B, H, d, d))
+    O = np.zeros_like(V)
+    S = np.zeros((B, H, d, V.shape[-1]))
     for b in range(B):
         n = int(min(N, max(0, seq_len[b])))
         if n == 0:
@@ -204,7 +209,7 @@ def bwd_varlen(Q, K, V, s, dO, seq_len, eps=1e-6, causal=True):
     """Returns (dQ, dK, dV, ds) with ds [B, H]; gradients are zero on rows that do not exist."""
     Q, K, V, s, dO = _f64(Q), _f64(K), _f64(V), _f64(s), _f64(dO)
     B, H, N, d = Q.shape
-    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(Q)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(V)
     ds = np.zeros((B, H))
     for b in range(B):
         n = int(min(N, max(0, seq_len[b])))

@@ -73,6 +73,22 @@ def _load():
     lib.cottn_scale_backward_varlen.argtypes = [fp, ip, fp, fp, i, i, vp]
     lib.cottn_step.restype = i
     lib.cottn_step.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, f, vp]
+    lib.cottn_workspace_bytes_dkdv.restype = sz
+    lib.cottn_workspace_bytes_dkdv.argtypes = [i] * 8
+    lib.cottn_segments_dkdv.restype = i
+    lib.cottn_segments_dkdv.argtypes = [i] * 8
+    lib.cottn_fwd_causal_dkdv.restype = i
+    lib.cottn_fwd_causal_dkdv.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_causal_dkdv.restype = i
+    lib.cottn_bwd_causal_dkdv.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i,
+                                          i, i, i, f, vp]
+    lib.cottn_fwd_bidir_dkdv.restype = i
+    lib.cottn_fwd_bidir_dkdv.argtypes = [vp, vp, vp, fp, vp, fp, vp, sz, i, i, i, i, i, i, f, vp]
+    lib.cottn_bwd_bidir_dkdv.restype = i
+    lib.cottn_bwd_bidir_dkdv.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, fp, vp, sz, vp, sz, i, i, i, i,
+                                         i, i, f, vp]
+    lib.cottn_step_dkdv.restype = i
+    lib.cottn_step_dkdv.argtypes = [vp, vp, vp, fp, fp, vp, i, i, i, i, i, f, vp]
     lib.cottn_scale_from_m.restype = i
     lib.cottn_scale_from_m.argtypes = [fp, fp, i, f, vp]
     lib.cottn_scale_backward.restype = i
@@ -495,6 +511,147 @@ def cottn_scale_backward(m, n, ds, dm=None, stream=None):
     _check(lib.cottn_scale_backward(_ptr(m), _ptr(ds), _ptr(dm), H, float(n), _stream(stream)),
            "cottn_scale_backward")
     return dm
+
+
+# ---- d_key != d_value: Q, K (dQ, dK) are [B, H, N, dk]; V, dO (O, dV) are [B, H, N, dv] ----------
+
+def cottn_workspace_bytes_dkdv(op, B, H, N, dk, dv, chunk=0, dtype=COTTN_BF16) -> int:
+    n = lib.cottn_workspace_bytes_dkdv(op, B, H, N, dk, dv, chunk, dtype)
+    if n == ctypes.c_size_t(-1).value:
+        raise CottnError(2, "cottn_workspace_bytes_dkdv")
+    return n
+
+
+def cottn_segments_dkdv(op, B, H, N, dk, dv, chunk=0, dtype=COTTN_BF16) -> int:
+    return lib.cottn_segments_dkdv(op, B, H, N, dk, dv, chunk, dtype)
+
+
+def _dims_dkdv(Q, V):
+    """B, H, N, dk (of Q), dv (of V), dtype code; V must agree with Q in everything but width."""
+    B, H, N, dk, dt = _dims(Q)
+    if V.dim() != 4 or tuple(V.shape[:3]) != (B, H, N) or V.dtype != Q.dtype or V.device != Q.device:
+        raise ValueError("V must be [%d, %d, %d, d_value] %s on %s, got %s %s on %s" % (
+            B, H, N, Q.dtype, Q.device, tuple(V.shape), V.dtype, V.device))
+    return B, H, N, dk, V.shape[-1], dt
+
+
+def _workspace_dkdv(op, B, H, N, dk, dv, chunk, dtype, device, workspace, stream):
+    need = cottn_workspace_bytes_dkdv(op, B, H, N, dk, dv, chunk, dtype)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        if stream is not None:
+            workspace.record_stream(stream)
+    elif workspace is not None and (not workspace.is_cuda or workspace.device != device):
+        raise ValueError("workspace must live on %s" % device)
+    have = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    return workspace, have
+
+
+def cottn_fwd_causal_dkdv(Q, K, V, s, O=None, state=None, workspace=None, chunk=0, eps=1e-6,
+                          stream=None):
+    """cottn_fwd_causal with d_key = Q.shape[-1] and d_value = V.shape[-1]; returns O (like V).
+    `state`, if given, receives float32 [B, H, d_key, d_value]."""
+    B, H, N, dk, dv, dt = _dims_dkdv(Q, V)
+    if O is None:
+        O = torch.empty_like(V)
+    _rows_like(Q, K=K)
+    _rows_like(V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state", state, B * H * dk * dv, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace_dkdv(OP_FWD_CAUSAL, B, H, N, dk, dv, chunk, dt, Q.device, workspace, stream)
+    st = lib.cottn_fwd_causal_dkdv(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
+                                   _ptr(workspace), have, B, H, N, dk, dv, chunk, dt, eps,
+                                   _stream(stream))
+    _check(st, "cottn_fwd_causal_dkdv")
+    return O
+
+
+def _grads_dkdv(Q, V, dQ, dK, dV, ds, H):
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    ds = torch.empty(H, dtype=torch.float32, device=Q.device) if ds is None else ds
+    return dQ, dK, dV, ds
+
+
+def cottn_bwd_causal_dkdv(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None,
+                          chunk=0, eps=1e-6, stream=None, fwd_workspace=None):
+    """cottn_bwd_causal with d_key = Q.shape[-1] and d_value = V.shape[-1] (dO like V);
+    returns (dQ, dK, dV, ds)."""
+    B, H, N, dk, dv, dt = _dims_dkdv(Q, V)
+    dQ, dK, dV, ds = _grads_dkdv(Q, V, dQ, dK, dV, ds, H)
+    _rows_like(Q, K=K, dQ=dQ, dK=dK)
+    _rows_like(V, dO=dO, dV=dV)
+    _f32("s", s, H, Q.device)
+    _f32("ds", ds, H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace_dkdv(OP_BWD_CAUSAL, B, H, N, dk, dv, chunk, dt, Q.device, workspace, stream)
+    st = lib.cottn_bwd_causal_dkdv(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
+                                   _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
+                                   _bytes(fwd_workspace, Q.device), _ptr(workspace), have, B, H, N, dk,
+                                   dv, chunk, dt, eps, _stream(stream))
+    _check(st, "cottn_bwd_causal_dkdv")
+    return dQ, dK, dV, ds
+
+
+def cottn_fwd_bidir_dkdv(Q, K, V, s, O=None, state=None, workspace=None, eps=1e-6, stream=None):
+    """cottn_fwd_bidir with d_key = Q.shape[-1] and d_value = V.shape[-1]; returns O (like V)."""
+    B, H, N, dk, dv, dt = _dims_dkdv(Q, V)
+    if O is None:
+        O = torch.empty_like(V)
+    _rows_like(Q, K=K)
+    _rows_like(V, O=O)
+    _f32("s", s, H, Q.device)
+    _f32("state", state, B * H * dk * dv, Q.device, optional=True)
+    _on_gpu(Q)
+    workspace, have = _workspace_dkdv(OP_FWD_BIDIR, B, H, N, dk, dv, 0, dt, Q.device, workspace, stream)
+    st = lib.cottn_fwd_bidir_dkdv(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(O), _ptr(state),
+                                  _ptr(workspace), have, B, H, N, dk, dv, dt, eps, _stream(stream))
+    _check(st, "cottn_fwd_bidir_dkdv")
+    return O
+
+
+def cottn_bwd_bidir_dkdv(Q, K, V, s, dO, dQ=None, dK=None, dV=None, ds=None, workspace=None,
+                         eps=1e-6, stream=None, fwd_workspace=None):
+    """cottn_bwd_bidir with d_key = Q.shape[-1] and d_value = V.shape[-1]; returns (dQ, dK, dV, ds)."""
+    B, H, N, dk, dv, dt = _dims_dkdv(Q, V)
+    dQ, dK, dV, ds = _grads_dkdv(Q, V, dQ, dK, dV, ds, H)
+    _rows_like(Q, K=K, dQ=dQ, dK=dK)
+    _rows_like(V, dO=dO, dV=dV)
+    _f32("s", s, H, Q.device)
+    _f32("ds", ds, H, Q.device)
+    _on_gpu(Q)
+    workspace, have = _workspace_dkdv(OP_BWD_BIDIR, B, H, N, dk, dv, 0, dt, Q.device, workspace, stream)
+    st = lib.cottn_bwd_bidir_dkdv(_ptr(Q), _ptr(K), _ptr(V), _ptr(s), _ptr(dO), _ptr(dQ), _ptr(dK),
+                                  _ptr(dV), _ptr(ds), _ptr(fwd_workspace),
+                                  _bytes(fwd_workspace, Q.device), _ptr(workspace), have, B, H, N, dk,
+                                  dv, dt, eps, _stream(stream))
+    _check(st, "cottn_bwd_bidir_dkdv")
+    return dQ, dK, dV, ds
+
+
+def cottn_step_dkdv(q, k, v, s, state, o=None, eps=1e-6, stream=None):
+    """cottn_step with q, k [B, H, d_key] and v [B, H, d_value]; state float32 [B, H, d_key, d_value]
+    updated in place; returns o (like v)."""
+    if q.dim() != 3 or v.dim() != 3:
+        raise ValueError("q and v must be [B, H, d], got shapes %s and %s" % (tuple(q.shape), tuple(v.shape)))
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    dt = _dtype_code(q)
+    if tuple(v.shape[:2]) != (B, H) or v.dtype != q.dtype or v.device != q.device:
+        raise ValueError("v must be [%d, %d, d_value] %s on %s" % (B, H, q.dtype, q.device))
+    if o is None:
+        o = torch.empty_like(v)
+    _tokens_like(q, k=k)
+    _tokens_like(v, o=o)
+    _f32("s", s, H, q.device)
+    _f32("state", state, B * H * dk * dv, q.device)
+    _on_gpu(q)
+    st = lib.cottn_step_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(s), _ptr(state), _ptr(o), B, H, dk, dv,
+                             dt, eps, _stream(stream))
+    _check(st, "cottn_step_dkdv")
+    return o
 
 
 def profile_start():

@@ -28,29 +28,33 @@ std::vector<KernelTotal> g_totals;
 
 bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-bool dims_ok(int B, int H, int N, int d) {
+bool dim_ok(int d) { return d == 32 || d == 64 || d == 128; }
+
+bool dims_ok(int B, int H, int N, int dk, int dv) {
   if (B < 1 || H < 1 || N < 0) return false;
-  if (d != 32 && d != 64 && d != 128) return false;
+  if (!dim_ok(dk) || !dim_ok(dv)) return false;
   // element counts must fit comfortably in 64-bit offsets and the grid in 31 bits
   if (double(B) * H > 16777216.0) return false;
-  if (double(B) * H * double(N) * d > 9.0e15) return false;
+  if (double(B) * H * double(N) * (dk > dv ? dk : dv) > 9.0e15) return false;
   return true;
 }
 
 }  // namespace
 
 // Split of one (batch, head) sequence into segments; see workspace.h.
-bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan* plan) {
+bool make_plan(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype, SeqPlan* plan) {
   if (dtype != COTTN_F32 && dtype != COTTN_BF16 && dtype != COTTN_F16) return false;
-  if (!dims_ok(B, H, N, d)) return false;
+  if (!dims_ok(B, H, N, dk, dv)) return false;
   int C;
   if (dtype != COTTN_F32) {
     C = chunk == 0 ? 64 : chunk;
     if (C != 64 && C != 128 && C != 256) return false;
-    if (d == 128 && C != 64) return false;
+    // the larger chunks are built for d_key = d_value in {32, 64}
+    if ((dk == 128 || dv == 128 || dk != dv) && C != 64) return false;
   } else {
     C = chunk == 0 ? 32 : chunk;
     if (C != 32) return false;
+    if (dk != dv) return false;  // the fp32 kernels are written for d_key = d_value
   }
   const long units = long(B) * H;
   const long n_chunks = (long(N) + C - 1) / C;
@@ -58,7 +62,7 @@ bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan
   if (g_tuned_segments > 0) {
     want = g_tuned_segments;
   } else {
-    if (dtype != COTTN_F32 && d == 128) {
+    if (dtype != COTTN_F32 && dk == 128 && dv == 128) {
       // one workgroup fills the LDS of a compute unit at d = 128: a second round of
       // workgroups costs more than shorter segments gain, so never more than one per unit
       // (measured on B8 H12 N1024: 2 segments 143 us, 4 segments 178 us per step)
@@ -112,12 +116,12 @@ hipError_t zero_f32(float* p, long n, hipStream_t st) {
                        0, st, p, n);
 }
 
-int check_common(const void* const* ptrs, int n_ptrs, int B, int H, int N, int d, int dtype,
-                 float eps) {
+int check_common(const void* const* ptrs, int n_ptrs, int B, int H, int N, int dk, int dv,
+                 int dtype, float eps) {
   for (int i = 0; i < n_ptrs; ++i)
     if (ptrs[i] == nullptr) return COTTN_E_NULL;
   if (dtype != COTTN_F32 && dtype != COTTN_BF16 && dtype != COTTN_F16) return COTTN_E_DTYPE;
-  if (!dims_ok(B, H, N, d)) return COTTN_E_SHAPE;
+  if (!dims_ok(B, H, N, dk, dv)) return COTTN_E_SHAPE;
   if (!(eps > 0.f)) return COTTN_E_ARG;
   for (int i = 0; i < n_ptrs; ++i)
     if (!is_aligned(ptrs[i], 16)) return COTTN_E_ALIGN;
@@ -140,23 +144,33 @@ using namespace cottn;
 
 extern "C" {
 
-size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int dtype) {
+size_t cottn_workspace_bytes_dkdv(int op, int B, int H, int N, int dk, int dv, int chunk,
+                                  int dtype) {
   if (op == COTTN_OP_STEP) {
-    return (dtype == COTTN_F32 || dtype == COTTN_BF16 || dtype == COTTN_F16) && dims_ok(B, H, 1, d)
+    return (dtype == COTTN_F32 || dtype == COTTN_BF16 || dtype == COTTN_F16) &&
+                   dims_ok(B, H, 1, dk, dv)
                ? 0
                : size_t(-1);
   }
   if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_STEP) return size_t(-1);
   SeqPlan plan;
-  if (!make_plan(op, B, H, N, d, chunk, dtype, &plan)) return size_t(-1);
-  return workspace_bytes_for(op, B, H, d, plan);
+  if (!make_plan(op, B, H, N, dk, dv, chunk, dtype, &plan)) return size_t(-1);
+  return workspace_bytes_for(op, B, H, dk, dv, plan);
+}
+
+size_t cottn_workspace_bytes(int op, int B, int H, int N, int d, int chunk, int dtype) {
+  return cottn_workspace_bytes_dkdv(op, B, H, N, d, d, chunk, dtype);
+}
+
+int cottn_segments_dkdv(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype) {
+  if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_BWD_BIDIR) return 0;
+  SeqPlan plan;
+  if (!make_plan(op, B, H, N, dk, dv, chunk, dtype, &plan)) return 0;
+  return plan.G;
 }
 
 int cottn_segments(int op, int B, int H, int N, int d, int chunk, int dtype) {
-  if (op < COTTN_OP_FWD_CAUSAL || op > COTTN_OP_BWD_BIDIR) return 0;
-  SeqPlan plan;
-  if (!make_plan(op, B, H, N, d, chunk, dtype, &plan)) return 0;
-  return plan.G;
+  return cottn_segments_dkdv(op, B, H, N, d, d, chunk, dtype);
 }
 
 void cottn_tune_segments(int segments) { g_tuned_segments = segments; }
@@ -165,8 +179,9 @@ const char* cottn_status_string(int status) {
   switch (status) {
     case COTTN_OK: return "ok";
     case COTTN_E_NULL: return "a required pointer is NULL";
-    case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d in {32,64,128}, "
-                               "chunk in {0,64,128,256} (16-bit; 64 only when d = 128) or {0,32} (fp32)";
+    case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d (d_key, d_value) in "
+                               "{32,64,128}, chunk in {0,64,128,256} (16-bit; 64 only when a "
+                               "dimension is 128 or d_key != d_value) or {0,32} (fp32, d_key = d_value)";
     case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0), COTTN_BF16 (1) or COTTN_F16 (2)";
     case COTTN_E_ALIGN: return "tensor pointers must be 16-byte aligned, the workspace 256-byte aligned";
     case COTTN_E_WORKSPACE: return "workspace is NULL or smaller than cottn_workspace_bytes()";
@@ -195,23 +210,23 @@ int check_lengths(const int* seq_len) {
 
 int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
                    const float* state_in, void* O, float* state, void* workspace,
-                   size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                   size_t workspace_bytes, int B, int H, int N, int dk, int dv, int chunk, int dtype,
                    float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, O};
-  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  int st = check_common(req, 5, B, H, N, dk, dv, dtype, eps);
   if (st != COTTN_OK) return st;
   if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
   if (state_in != nullptr && !is_aligned(state_in, 16)) return COTTN_E_ALIGN;
   if (state_in != nullptr && state_in == state) return COTTN_E_ARG;
   if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
-  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, dk, dv, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
-                       workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, plan));
+                       workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, dk, dv, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (N == 0) {
-    const long n = long(B) * H * d * d;
+    const long n = long(B) * H * dk * dv;
     if (state == nullptr) return COTTN_OK;
     if (state_in == nullptr) return map_hip(zero_f32(state, n, stream));
     return map_hip(copy_state(state, state_in, n, stream));
@@ -219,7 +234,7 @@ int fwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.state_in = state_in;
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
-  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.B = B; a.H = H; a.N = N; a.dk = dk; a.dv = dv; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   return map_hip(dtype == COTTN_BF16 ? fwd_causal_bf16(a) : dtype == COTTN_F16 ? fwd_causal_f16(a) : fwd_causal_f32(a));
 }
@@ -230,7 +245,7 @@ int cottn_fwd_causal(const void* Q, const void* K, const void* V, const float* s
                      float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                      int d, int chunk, int dtype, float eps, void* hip_stream) {
   return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, workspace, workspace_bytes, B, H, N,
-                        d, chunk, dtype, eps, hip_stream);
+                        d, d, chunk, dtype, eps, hip_stream);
 }
 
 // ---- the causal forward for callers that cannot allocate ------------------------------------
@@ -266,18 +281,18 @@ int cottn_fwd_causal_static(const void* Q, const void* K, const void* V, const f
                             float* state, int B, int H, int N, int d, int chunk, int dtype,
                             float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, O};
-  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  int st = check_common(req, 5, B, H, N, d, d, dtype, eps);
   if (st != COTTN_OK) return st;
   SeqPlan plan;
-  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
-  const size_t need = workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, plan);
+  if (!make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  const size_t need = workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, d, plan);
   if (need > size_t(COTTN_STATIC_WORKSPACE_BYTES)) return COTTN_E_WORKSPACE;
   void* ws = nullptr;
   if (need > 0 && (st = static_workspace(&ws)) != COTTN_OK) return st;
   // every slot of the segment-state array that a kernel reads is written earlier in the same
   // call, so what the previous call left in the array needs no clearing
   return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, ws, need, B, H, N,
-                        d, chunk, dtype, eps, hip_stream);
+                        d, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
@@ -286,7 +301,7 @@ int cottn_fwd_causal_from_state(const void* Q, const void* K, const void* V, con
                                 int dtype, float eps, void* hip_stream) {
   if (state_in == nullptr) return COTTN_E_NULL;
   return fwd_causal_any(Q, K, V, s, nullptr, state_in, O, state, workspace, workspace_bytes, B, H, N,
-                        d, chunk, dtype, eps, hip_stream);
+                        d, d, chunk, dtype, eps, hip_stream);
 }
 
 namespace {
@@ -295,10 +310,10 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
                    const void* dO, const float* state_in, const float* rev_state_in, void* dQ,
                    void* dK, void* dV, float* ds, float* rev_state_out,
                    const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
-                   size_t workspace_bytes, int B, int H, int N, int d, int chunk, int dtype,
+                   size_t workspace_bytes, int B, int H, int N, int dk, int dv, int chunk, int dtype,
                    float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
-  int st = check_common(req, 9, B, H, N, d, dtype, eps);
+  int st = check_common(req, 9, B, H, N, dk, dv, dtype, eps);
   if (st != COTTN_OK) return st;
   if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   if (!is_aligned(state_in, 16) || !is_aligned(rev_state_in, 16) || !is_aligned(rev_state_out, 16))
@@ -306,13 +321,13 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   // workgroups read the one while others write the other
   if (rev_state_out != nullptr && rev_state_out == rev_state_in) return COTTN_E_ARG;
   SeqPlan plan;
-  if (!make_plan(COTTN_OP_BWD_CAUSAL, B, H, N, d, chunk, dtype, &plan)) return COTTN_E_SHAPE;
+  if (!make_plan(COTTN_OP_BWD_CAUSAL, B, H, N, dk, dv, chunk, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
-                       workspace_bytes_for(COTTN_OP_BWD_CAUSAL, B, H, d, plan));
+                       workspace_bytes_for(COTTN_OP_BWD_CAUSAL, B, H, dk, dv, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (N == 0) {
-    const long n = long(B) * H * d * d;
+    const long n = long(B) * H * dk * dv;
     hipError_t e = zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream);
     if (e == hipSuccess && rev_state_out != nullptr)
       e = rev_state_in != nullptr ? copy_state(rev_state_out, rev_state_in, n, stream)
@@ -323,16 +338,16 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
   a.state_in = state_in; a.rev_state_in = rev_state_in; a.rev_state_out = rev_state_out;
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
-  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.B = B; a.H = H; a.N = N; a.dk = dk; a.dv = dv; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   // the forward's segment states are taken over only if the forward split the sequence as
   // the backward does
   if (fwd_workspace != nullptr && dtype != COTTN_F32 && plan.G > 1) {
     SeqPlan fwd_plan;
-    if (make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, d, chunk, dtype, &fwd_plan) &&
+    if (make_plan(COTTN_OP_FWD_CAUSAL, B, H, N, dk, dv, chunk, dtype, &fwd_plan) &&
         fwd_plan.C == plan.C && fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
       st = check_workspace(fwd_workspace, fwd_workspace_bytes,
-                           workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, d, fwd_plan));
+                           workspace_bytes_for(COTTN_OP_FWD_CAUSAL, B, H, dk, dv, fwd_plan));
       if (st != COTTN_OK) return st;
       a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
     }
@@ -342,23 +357,23 @@ int bwd_causal_any(const void* Q, const void* K, const void* V, const float* s, 
 
 int fwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
                   void* O, float* state, void* workspace, size_t workspace_bytes, int B, int H,
-                  int N, int d, int dtype, float eps, void* hip_stream) {
+                  int N, int dk, int dv, int dtype, float eps, void* hip_stream) {
   const void* req[] = {Q, K, V, s, O};
-  int st = check_common(req, 5, B, H, N, d, dtype, eps);
+  int st = check_common(req, 5, B, H, N, dk, dv, dtype, eps);
   if (st != COTTN_OK) return st;
   if (state != nullptr && !is_aligned(state, 16)) return COTTN_E_ALIGN;
   if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
-  if (!make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
+  if (!make_plan(COTTN_OP_FWD_BIDIR, B, H, N, dk, dv, 0, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
-                       workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, d, plan));
+                       workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, dk, dv, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (N == 0) return map_hip(zero_f32(state, long(B) * H * d * d, stream));
+  if (N == 0) return map_hip(zero_f32(state, long(B) * H * dk * dv, stream));
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.O = O; a.state = state; a.workspace = workspace;
   a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
-  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.B = B; a.H = H; a.N = N; a.dk = dk; a.dv = dv; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   return map_hip(dtype == COTTN_BF16 ? fwd_bidir_bf16(a) : dtype == COTTN_F16 ? fwd_bidir_f16(a) : fwd_bidir_f32(a));
 }
@@ -366,30 +381,30 @@ int fwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, c
 int bwd_bidir_any(const void* Q, const void* K, const void* V, const float* s, const int* seq_len,
                   const void* dO, void* dQ, void* dK, void* dV, float* ds,
                   const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
-                  size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
+                  size_t workspace_bytes, int B, int H, int N, int dk, int dv, int dtype, float eps,
                   void* hip_stream) {
   const void* req[] = {Q, K, V, s, dO, dQ, dK, dV, ds};
-  int st = check_common(req, 9, B, H, N, d, dtype, eps);
+  int st = check_common(req, 9, B, H, N, dk, dv, dtype, eps);
   if (st != COTTN_OK) return st;
   if ((st = check_lengths(seq_len)) != COTTN_OK) return st;
   SeqPlan plan;
-  if (!make_plan(COTTN_OP_BWD_BIDIR, B, H, N, d, 0, dtype, &plan)) return COTTN_E_SHAPE;
+  if (!make_plan(COTTN_OP_BWD_BIDIR, B, H, N, dk, dv, 0, dtype, &plan)) return COTTN_E_SHAPE;
   st = check_workspace(workspace, workspace_bytes,
-                       workspace_bytes_for(COTTN_OP_BWD_BIDIR, B, H, d, plan));
+                       workspace_bytes_for(COTTN_OP_BWD_BIDIR, B, H, dk, dv, plan));
   if (st != COTTN_OK) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (N == 0) return map_hip(zero_f32(ds, seq_len != nullptr ? long(B) * H : H, stream));
   CausalArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.s = s; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ds = ds;
   a.workspace = workspace; a.seq_len = seq_len; a.s_per_unit = seq_len != nullptr;
-  a.B = B; a.H = H; a.N = N; a.d = d; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
+  a.B = B; a.H = H; a.N = N; a.dk = dk; a.dv = dv; a.C = plan.C; a.G = plan.G; a.seg_rows = plan.seg_rows;
   a.eps = eps; a.stream = stream;
   if (fwd_workspace != nullptr && dtype != COTTN_F32 && plan.G <= kMaxSegmentsSummedInScan) {
     SeqPlan fwd_plan;
-    if (make_plan(COTTN_OP_FWD_BIDIR, B, H, N, d, 0, dtype, &fwd_plan) && fwd_plan.C == plan.C &&
+    if (make_plan(COTTN_OP_FWD_BIDIR, B, H, N, dk, dv, 0, dtype, &fwd_plan) && fwd_plan.C == plan.C &&
         fwd_plan.G == plan.G && fwd_plan.seg_rows == plan.seg_rows) {
       st = check_workspace(fwd_workspace, fwd_workspace_bytes,
-                           workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, d, fwd_plan));
+                           workspace_bytes_for(COTTN_OP_FWD_BIDIR, B, H, dk, dv, fwd_plan));
       if (st != COTTN_OK) return st;
       a.saved_fwd_states = static_cast<const float*>(fwd_workspace);
     }
@@ -405,7 +420,7 @@ int cottn_bwd_causal(const void* Q, const void* K, const void* V, const float* s
                      int H, int N, int d, int chunk, int dtype, float eps, void* hip_stream) {
   return bwd_causal_any(Q, K, V, s, nullptr, dO, nullptr, nullptr, dQ, dK, dV, ds, nullptr,
                         fwd_workspace, fwd_workspace_bytes,
-                        workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+                        workspace, workspace_bytes, B, H, N, d, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_bwd_causal_from_state(const void* Q, const void* K, const void* V, const float* s,
@@ -416,13 +431,13 @@ int cottn_bwd_causal_from_state(const void* Q, const void* K, const void* V, con
                                 int chunk, int dtype, float eps, void* hip_stream) {
   return bwd_causal_any(Q, K, V, s, nullptr, dO, state_in, rev_state_in, dQ, dK, dV, ds,
                         rev_state_out, fwd_workspace, fwd_workspace_bytes, workspace,
-                        workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+                        workspace_bytes, B, H, N, d, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_fwd_bidir(const void* Q, const void* K, const void* V, const float* s, void* O,
                     float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
                     int d, int dtype, float eps, void* hip_stream) {
-  return fwd_bidir_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, d, dtype,
+  return fwd_bidir_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, d, d, dtype,
                        eps, hip_stream);
 }
 
@@ -431,7 +446,7 @@ int cottn_bwd_bidir(const void* Q, const void* K, const void* V, const float* s,
                     size_t fwd_workspace_bytes, void* workspace, size_t workspace_bytes, int B,
                     int H, int N, int d, int dtype, float eps, void* hip_stream) {
   return bwd_bidir_any(Q, K, V, s, nullptr, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
-                       workspace, workspace_bytes, B, H, N, d, dtype, eps, hip_stream);
+                       workspace, workspace_bytes, B, H, N, d, d, dtype, eps, hip_stream);
 }
 
 // ---- padded batches: seq_len[B] rows exist per sequence; s and ds are [B][H] -------------------
@@ -441,7 +456,7 @@ int cottn_fwd_causal_varlen(const void* Q, const void* K, const void* V, const f
                             int dtype, float eps, void* hip_stream) {
   if (seq_len == nullptr) return COTTN_E_NULL;
   return fwd_causal_any(Q, K, V, s, seq_len, nullptr, O, state, workspace, workspace_bytes, B, H, N,
-                        d, chunk, dtype, eps, hip_stream);
+                        d, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_bwd_causal_varlen(const void* Q, const void* K, const void* V, const float* s,
@@ -452,7 +467,7 @@ int cottn_bwd_causal_varlen(const void* Q, const void* K, const void* V, const f
   if (seq_len == nullptr) return COTTN_E_NULL;
   return bwd_causal_any(Q, K, V, s, seq_len, dO, nullptr, nullptr, dQ, dK, dV, ds, nullptr,
                         fwd_workspace, fwd_workspace_bytes,
-                        workspace, workspace_bytes, B, H, N, d, chunk, dtype, eps, hip_stream);
+                        workspace, workspace_bytes, B, H, N, d, d, chunk, dtype, eps, hip_stream);
 }
 
 int cottn_fwd_bidir_varlen(const void* Q, const void* K, const void* V, const float* s,
@@ -460,7 +475,7 @@ int cottn_fwd_bidir_varlen(const void* Q, const void* K, const void* V, const fl
                            size_t workspace_bytes, int B, int H, int N, int d, int dtype, float eps,
                            void* hip_stream) {
   if (seq_len == nullptr) return COTTN_E_NULL;
-  return fwd_bidir_any(Q, K, V, s, seq_len, O, state, workspace, workspace_bytes, B, H, N, d, dtype,
+  return fwd_bidir_any(Q, K, V, s, seq_len, O, state, workspace, workspace_bytes, B, H, N, d, d, dtype,
                        eps, hip_stream);
 }
 
@@ -471,7 +486,7 @@ int cottn_bwd_bidir_varlen(const void* Q, const void* K, const void* V, const fl
                            int dtype, float eps, void* hip_stream) {
   if (seq_len == nullptr) return COTTN_E_NULL;
   return bwd_bidir_any(Q, K, V, s, seq_len, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
-                       workspace, workspace_bytes, B, H, N, d, dtype, eps, hip_stream);
+                       workspace, workspace_bytes, B, H, N, d, d, dtype, eps, hip_stream);
 }
 
 int cottn_scale_from_m(const float* m, float* s, int H, float n, void* hip_stream) {
@@ -510,13 +525,52 @@ int cottn_scale_backward_varlen(const float* m, const int* seq_len, const float*
                                               static_cast<hipStream_t>(hip_stream)));
 }
 
+int cottn_step_dkdv(const void* q, const void* k, const void* v, const float* s, float* state,
+                    void* o, int B, int H, int dk, int dv, int dtype, float eps, void* hip_stream) {
+  const void* req[] = {q, k, v, s, state, o};
+  int st = check_common(req, 6, B, H, 1, dk, dv, dtype, eps);
+  if (st != COTTN_OK) return st;
+  StepArgs a{q, k, v, s, state, o, B, H, dk, dv, eps, static_cast<hipStream_t>(hip_stream)};
+  return map_hip(step_any(a, dtype));
+}
+
 int cottn_step(const void* q, const void* k, const void* v, const float* s, float* state,
                void* o, int B, int H, int d, int dtype, float eps, void* hip_stream) {
-  const void* req[] = {q, k, v, s, state, o};
-  int st = check_common(req, 6, B, H, 1, d, dtype, eps);
-  if (st != COTTN_OK) return st;
-  StepArgs a{q, k, v, s, state, o, B, H, d, eps, static_cast<hipStream_t>(hip_stream)};
-  return map_hip(step_any(a, dtype));
+  return cottn_step_dkdv(q, k, v, s, state, o, B, H, d, d, dtype, eps, hip_stream);
+}
+
+// ---- d_key != d_value (Sec. 2.1): Q, K, dQ, dK are [B][H][N][dk]; V, O, dO, dV [B][H][N][dv] ----
+int cottn_fwd_causal_dkdv(const void* Q, const void* K, const void* V, const float* s, void* O,
+                          float* state, void* workspace, size_t workspace_bytes, int B, int H,
+                          int N, int dk, int dv, int chunk, int dtype, float eps, void* hip_stream) {
+  return fwd_causal_any(Q, K, V, s, nullptr, nullptr, O, state, workspace, workspace_bytes, B, H, N,
+                        dk, dv, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_bwd_causal_dkdv(const void* Q, const void* K, const void* V, const float* s,
+                          const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                          const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                          size_t workspace_bytes, int B, int H, int N, int dk, int dv, int chunk,
+                          int dtype, float eps, void* hip_stream) {
+  return bwd_causal_any(Q, K, V, s, nullptr, dO, nullptr, nullptr, dQ, dK, dV, ds, nullptr,
+                        fwd_workspace, fwd_workspace_bytes, workspace, workspace_bytes, B, H, N, dk,
+                        dv, chunk, dtype, eps, hip_stream);
+}
+
+int cottn_fwd_bidir_dkdv(const void* Q, const void* K, const void* V, const float* s, void* O,
+                         float* state, void* workspace, size_t workspace_bytes, int B, int H, int N,
+                         int dk, int dv, int dtype, float eps, void* hip_stream) {
+  return fwd_bidir_any(Q, K, V, s, nullptr, O, state, workspace, workspace_bytes, B, H, N, dk, dv,
+                       dtype, eps, hip_stream);
+}
+
+int cottn_bwd_bidir_dkdv(const void* Q, const void* K, const void* V, const float* s,
+                         const void* dO, void* dQ, void* dK, void* dV, float* ds,
+                         const void* fwd_workspace, size_t fwd_workspace_bytes, void* workspace,
+                         size_t workspace_bytes, int B, int H, int N, int dk, int dv, int dtype,
+                         float eps, void* hip_stream) {
+  return bwd_bidir_any(Q, K, V, s, nullptr, dO, dQ, dK, dV, ds, fwd_workspace, fwd_workspace_bytes,
+                       workspace, workspace_bytes, B, H, N, dk, dv, dtype, eps, hip_stream);
 }
 
 int cottn_profile_start(void) {

@@ -32,18 +32,23 @@
 namespace cottn {
 namespace {
 
-template <int D, int C>
+// DK, DV: head dimensions of queries / keys and of values / outputs (Sec. 2.1); the matrices
+// S = Kh^T V and G = Qh^T dO are DK x DV.
+template <int DK, int DV, int C>
 struct BiCfg {
   static constexpr int NW = C / 16;
   static constexpr int NT = NW * 64;
-  static constexpr int DT = D / 16;
-  static constexpr int KS = D / 32;
-  static constexpr int TP = tile_pitch(D, C);   // operand tiles
-  // the d x d matrices are written once per workgroup and then only read, as row fragments
+  static constexpr int DTK = DK / 16, DTV = DV / 16;
+  static constexpr int KSK = DK / 32, KSV = DV / 32;
+  static constexpr int TPK = tile_pitch(DK, C), TPV = tile_pitch(DV, C);   // operand tiles
+  // the DK x DV matrices are written once per workgroup and then only read, as row fragments
   // too: they take the operand tiles' pitch
-  static constexpr int SP = tile_pitch(D, C);
-  static constexpr int TILE = C * TP;
-  static constexpr int STATE = D * SP;
+  static constexpr int SP = tile_pitch(DV, C);
+  static constexpr int TILEK = C * TPK, TILEV = C * TPV;
+  static constexpr int STATE = DK * SP;
+  // the forward stages finished output rows (DV wide) in the wave's own dead query rows when
+  // those are wide enough, else in a tile of their own
+  static constexpr bool FWD_OWN_STAGE = lds_pitch(DV) > TPK;
 };
 
 // Slot 0 of each pair <- sum over g of the slots, one matrix element per thread (grid:
@@ -78,15 +83,15 @@ __global__ __launch_bounds__(256) void bidir_combine(float* __restrict__ totals,
   }
 }
 
-// dst (LDS, bf16, row-major [D][D] with row pitch SP) <- sum of the first n_sum of the
-// [D][D] fp32 matrices at src; the fp32 sum also goes to `copy` when that is not null.
-template <int D, int NT, int SP>
+// dst (LDS, bf16, row-major [DK][DV] with row pitch SP) <- sum of the first n_sum of the
+// [DK][DV] fp32 matrices at src; the fp32 sum also goes to `copy` when that is not null.
+template <int DK, int DV, int NT, int SP>
 __device__ __forceinline__ void stage_summed_matrix(e16_t* dst, const float* __restrict__ src,
                                                     int n_sum, float* __restrict__ copy) {
-  for (int e = 4 * threadIdx.x; e < D * D; e += 4 * NT) {
+  for (int e = 4 * threadIdx.x; e < DK * DV; e += 4 * NT) {
     f32x4 a = *reinterpret_cast<const f32x4*>(src + e);
     for (int j = 1; j < n_sum; ++j) {
-      const f32x4 b = *reinterpret_cast<const f32x4*>(src + size_t(j) * D * D + e);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(src + size_t(j) * DK * DV + e);
 #pragma unroll
       for (int v = 0; v < 4; ++v) a[v] += b[v];
     }
@@ -94,31 +99,31 @@ __device__ __forceinline__ void stage_summed_matrix(e16_t* dst, const float* __r
     uint2 pk;
     pk.x = pack2(a[0], a[1]);
     pk.y = pack2(a[2], a[3]);
-    *reinterpret_cast<uint2*>(dst + (e / D) * SP + e % D) = pk;
+    *reinterpret_cast<uint2*>(dst + (e / DV) * SP + e % DV) = pk;
   }
 }
 
 // O rows of one segment: O_i = s r_i (q_i S), accumulated as O^T = S^T Q^T.  `totals` holds
 // n_sum stored matrices per unit at a stride of `slots` matrices; the workgroup of segment 0
 // writes their sum to `state` when that is asked for.
-template <int D, int C>
+template <int DK, int DV, int C>
 __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
     const e16_t* __restrict__ Q, const float* __restrict__ s, e16_t* __restrict__ O,
     const float* __restrict__ totals, int slots, int n_sum, float* __restrict__ state, int H, int N,
     int G, int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
-  using Cfg = BiCfg<D, C>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int TP = Cfg::TP, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
+  using Cfg = BiCfg<DK, DV, C>;
+  using Stage = TileStage<DK, C, Cfg::NT>;
+  constexpr int TP = Cfg::TPK, SP = Cfg::SP;
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];  // raw q
   __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // [d_key][d_value]
+  __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::FWD_OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const e16_t* Qu = Q + ubase;
-  e16_t* Ou = O + ubase;
+  const e16_t* Qu = Q + size_t(unit) * N * DK;
+  e16_t* Ou = O + size_t(unit) * N * DV;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -126,13 +131,14 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
 
   Stage qst;
   qst.fetch(Qu, row_begin, row_end);
-  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Sl, totals + size_t(unit) * slots * D * D, n_sum,
-                                  (state != nullptr && g == 0) ? state + size_t(unit) * D * D
+  stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Sl, totals + size_t(unit) * slots * DK * DV, n_sum,
+                                  (state != nullptr && g == 0) ? state + size_t(unit) * DK * DV
                                                                : nullptr);
 
-  RowPieces<D> finished;  // output rows of the previous chunk, stored one chunk late
+  RowPieces<DV> finished;  // output rows of the previous chunk, stored one chunk late
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<DV>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  e16_t* stage = Cfg::FWD_OWN_STAGE ? Os + 16 * w * Cfg::TPV : Qs + 16 * w * TP;
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     {
       float rqv[Stage::PASSES];
@@ -141,43 +147,43 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
       qst.store_rinv(rq, rqv);
     }
     if (row0 + C < row_end) qst.fetch(Qu, row0 + C, row_end);
-    if (row0 > row_begin) store_row_pieces<D>(finished, Ou, row0 - C + 16 * w, row_end, l);
+    if (row0 > row_begin) store_row_pieces<DV>(finished, Ou, row0 - C + 16 * w, row_end, l);
     __syncthreads();
     // oacc[nt][v] = (q S)[query 16w + r][value 16 nt + 4 q4 + v]
-    f32x4 oacc[Cfg::DT];
+    f32x4 oacc[Cfg::DTV];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    frag8 qf[Cfg::KS], sf[Cfg::KS][Cfg::DT];
+    for (int nt = 0; nt < Cfg::DTV; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    frag8 qf[Cfg::KSK], sf[Cfg::KSK][Cfg::DTV];
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
+    for (int ks = 0; ks < Cfg::KSK; ++ks) {
       qf[ks] = lds_row_frag(Qs + (16 * w + r) * TP + 32 * ks + 8 * q4);
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt)
+      for (int nt = 0; nt < Cfg::DTV; ++nt)
         sf[ks][nt] = lds_col_frag(Sl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
     }
     __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks)
+    for (int ks = 0; ks < Cfg::KSK; ++ks)
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) oacc[nt] = mma16(sf[ks][nt], qf[ks], oacc[nt]);
+      for (int nt = 0; nt < Cfg::DTV; ++nt) oacc[nt] = mma16(sf[ks][nt], qf[ks], oacc[nt]);
     __builtin_amdgcn_sched_barrier(0);
     const float row_factor = scale * rq[16 * w + r];
     wave_lds_sync();  // this wave's reads of its Qs rows precede the staging writes
-    gather_rows_transposed<D>(oacc, row_factor, Qs + 16 * w * TP, l, finished);
+    gather_rows_transposed<DV>(oacc, row_factor, stage, l, finished);
     __syncthreads();
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<D>(finished, Ou, last + 16 * w, row_end, l);
+    store_row_pieces<DV>(finished, Ou, last + 16 * w, row_end, l);
   }
-  if (seq_len != nullptr) zero_rows_e16<D>(Ou, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<DV>(Ou, row_end, seg_end);  // rows that do not exist
 }
 
 // dQ, dK, dV rows of one segment; the first H workgroups also finish ds from the n_ds
 // partial sums per (batch, head).  All products are accumulated transposed:
 //   dqh^T = S dO^T (over d_value),  dkh^T = G V^T (over d_value),  (k G)^T = G^T k^T (over
 //   d_key), then dq_i = s r_i (dqh_i - qh_i (qh_i . dqh_i)), dk_j likewise, dv_j = s r_j (k_j G).
-template <int D, int C>
+template <int DK, int DV, int C>
 __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
     const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
@@ -185,13 +191,14 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     const float* __restrict__ g_totals, int slots, int n_sum, const float* __restrict__ ds_partial,
     int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps,
     const int* __restrict__ seq_len, int s_per_unit) {
-  using Cfg = BiCfg<D, C>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int TP = Cfg::TP, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
+  using Cfg = BiCfg<DK, DV, C>;
+  using StageK = TileStage<DK, C, Cfg::NT>;
+  using StageV = TileStage<DV, C, Cfg::NT>;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SP;
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // raw q
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILEV];   // dO
   __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // Kh^T V,  [d_key][d_value]
   __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
   __shared__ float rq[C], rk[C];
@@ -199,20 +206,20 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const e16_t* Qu = Q + ubase;
-  const e16_t* Ku = K + ubase;
-  const e16_t* Vu = V + ubase;
-  const e16_t* Gu = dO + ubase;
-  e16_t* dQu = dQ + ubase;
-  e16_t* dKu = dK + ubase;
-  e16_t* dVu = dV + ubase;
+  const e16_t* Qu = Q + size_t(unit) * N * DK;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
+  const e16_t* Gu = dO + size_t(unit) * N * DV;
+  e16_t* dQu = dQ + size_t(unit) * N * DK;
+  e16_t* dKu = dK + size_t(unit) * N * DK;
+  e16_t* dVu = dV + size_t(unit) * N * DV;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
   const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
-  Stage qst, kst, vst, gst;
+  StageK qst, kst;
+  StageV vst, gst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
@@ -228,16 +235,18 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     t = group_sum<64>(t);
     if (l == 0) ds[blockIdx.x] = t;
   }
-  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Sl, s_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
-  stage_summed_matrix<D, Cfg::NT, Cfg::SP>(Gl, g_totals + size_t(unit) * slots * D * D, n_sum, nullptr);
+  stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Sl, s_totals + size_t(unit) * slots * DK * DV, n_sum, nullptr);
+  stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Gl, g_totals + size_t(unit) * slots * DK * DV, n_sum, nullptr);
 
-  RowPieces<D> done_q, done_k, done_v;  // rows of the previous chunk, stored one chunk late
+  RowPieces<DK> done_q, done_k;  // rows of the previous chunk, stored one chunk late
+  RowPieces<DV> done_v;
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j)
-    done_q.v[j] = done_k.v[j] = done_v.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) done_q.v[j] = done_k.v[j] = uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int j = 0; j < RowPieces<DV>::PER_LANE; ++j) done_v.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     {
-      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      float rqv[StageK::PASSES], rkv[StageK::PASSES];
       qst.row_rinv(inv_eps, rqv);
       kst.row_rinv(inv_eps, rkv);
       qst.commit_plain(Qs);
@@ -254,79 +263,91 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
       gst.fetch(Gu, row0 + C, row_end);
     }
     if (row0 > row_begin) {
-      store_row_pieces<D>(done_q, dQu, row0 - C + 16 * w, row_end, l);
-      store_row_pieces<D>(done_k, dKu, row0 - C + 16 * w, row_end, l);
-      store_row_pieces<D>(done_v, dVu, row0 - C + 16 * w, row_end, l);
+      store_row_pieces<DK>(done_q, dQu, row0 - C + 16 * w, row_end, l);
+      store_row_pieces<DK>(done_k, dKu, row0 - C + 16 * w, row_end, l);
+      store_row_pieces<DV>(done_v, dVu, row0 - C + 16 * w, row_end, l);
     }
     __syncthreads();
 
     // d*[nt][v] = result[row 16w + r][feature 16 nt + 4 q4 + v]
-    f32x4 dq[Cfg::DT], dk[Cfg::DT], dv[Cfg::DT];
+    f32x4 dq[Cfg::DTK], dk[Cfg::DTK], dv[Cfg::DTV];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt) {
+    for (int nt = 0; nt < Cfg::DTK; ++nt) {
       dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
       dk[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
-      const int off = (16 * w + r) * TP + 32 * ks + 8 * q4;
-      const frag8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off),
-                   kf = lds_row_frag(Ks + off);
-      frag8 srow[Cfg::DT], grow[Cfg::DT], gcol[Cfg::DT];
+    for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // S dO^T and G V^T contract over d_value (row fragments of Sl / Gl along their rows)
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) {
+    for (int ks = 0; ks < Cfg::KSV; ++ks) {
+      const int off = (16 * w + r) * TPV + 32 * ks + 8 * q4;
+      const frag8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off);
+      frag8 srow[Cfg::DTK], grow[Cfg::DTK];
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DTK; ++nt) {
         const int soff = (16 * nt + r) * SP + 32 * ks + 8 * q4;
         srow[nt] = lds_row_frag(Sl + soff);
         grow[nt] = lds_row_frag(Gl + soff);
-        gcol[nt] = lds_col_frag(Gl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       }
       __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) {
+      for (int nt = 0; nt < Cfg::DTK; ++nt) {
         dq[nt] = mma16(srow[nt], gf, dq[nt]);   // S dO^T   (over d_value)
         dk[nt] = mma16(grow[nt], vf, dk[nt]);   // G V^T    (over d_value)
-        dv[nt] = mma16(gcol[nt], kf, dv[nt]);   // G^T k^T  (over d_key)
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    // G^T k^T contracts over d_key (fragments down the rows of Gl)
+#pragma unroll
+    for (int ks = 0; ks < Cfg::KSK; ++ks) {
+      const frag8 kf = lds_row_frag(Ks + (16 * w + r) * TPK + 32 * ks + 8 * q4);
+      frag8 gcol[Cfg::DTV];
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DTV; ++nt)
+        gcol[nt] = lds_col_frag(Gl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = mma16(gcol[nt], kf, dv[nt]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // every tile row is private to its wave here: chain rule on the raw rows, then the
-    // results are staged in place (dO rows for dQ, K rows for dK, V rows for dV)
+    // results are staged in place (Q rows for dQ, K rows for dK, V rows for dV)
     const float ri = rq[16 * w + r], rj = rk[16 * w + r];
-    project_out_row<D, TP, false>(dq, Qs + 16 * w * TP, ri, inv_eps, r, q4);
-    project_out_row<D, TP, false>(dk, Ks + 16 * w * TP, rj, inv_eps, r, q4);
-    wave_lds_sync();  // own rows of Gs, Ks, Vs were read before the staging writes
-    gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * TP, l, done_q);
-    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * TP, l, done_k);
-    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * TP, l, done_v);
+    project_out_row<DK, TPK, false>(dq, Qs + 16 * w * TPK, ri, inv_eps, r, q4);
+    project_out_row<DK, TPK, false>(dk, Ks + 16 * w * TPK, rj, inv_eps, r, q4);
+    wave_lds_sync();  // own rows of Qs, Ks, Vs were read before the staging writes
+    gather_rows_transposed<DK>(dq, scale * ri, Qs + 16 * w * TPK, l, done_q);
+    gather_rows_transposed<DK>(dk, scale * rj, Ks + 16 * w * TPK, l, done_k);
+    gather_rows_transposed<DV>(dv, scale * rj, Vs + 16 * w * TPV, l, done_v);
     __syncthreads();
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<D>(done_q, dQu, last + 16 * w, row_end, l);
-    store_row_pieces<D>(done_k, dKu, last + 16 * w, row_end, l);
-    store_row_pieces<D>(done_v, dVu, last + 16 * w, row_end, l);
+    store_row_pieces<DK>(done_q, dQu, last + 16 * w, row_end, l);
+    store_row_pieces<DK>(done_k, dKu, last + 16 * w, row_end, l);
+    store_row_pieces<DV>(done_v, dVu, last + 16 * w, row_end, l);
   }
   if (seq_len != nullptr) {  // rows that do not exist
-    zero_rows_e16<D>(dQu, row_end, seg_end);
-    zero_rows_e16<D>(dKu, row_end, seg_end);
-    zero_rows_e16<D>(dVu, row_end, seg_end);
+    zero_rows_e16<DK>(dQu, row_end, seg_end);
+    zero_rows_e16<DK>(dKu, row_end, seg_end);
+    zero_rows_e16<DV>(dVu, row_end, seg_end);
   }
 }
 
 SegmentTotalsArgs totals_args(const CausalArgs& a, const void* X, const void* Y, float* dst) {
   SegmentTotalsArgs t{};
   t.X = X; t.Y = Y; t.dst = dst;
-  t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G;
+  t.units = a.B * a.H; t.N = a.N; t.dk = a.dk; t.dv = a.dv; t.G = a.G; t.n_compute = a.G;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
   t.seq_len = a.seq_len; t.H = a.H;
   return t;
 }
 
-template <int D>
+template <int DK, int DV>
 hipError_t run_fwd_bidir(const CausalArgs& a) {
   constexpr int C = 64;
-  using Cfg = BiCfg<D, C>;
+  using Cfg = BiCfg<DK, DV, C>;
   const int units = a.B * a.H;
   float* totals = static_cast<float*>(a.workspace);
   hipError_t err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.K, a.V, totals));
@@ -334,26 +355,26 @@ hipError_t run_fwd_bidir(const CausalArgs& a) {
   // few segments: the apply workgroups add the totals up themselves (and write `state`)
   const bool sum_in_apply = a.G <= kMaxSegmentsSummedInScan;
   if (!sum_in_apply) {
-    err = launch_bidir_combine(totals, 0, 1, units, a.G, D * D, a.state, nullptr, a.stream);
+    err = launch_bidir_combine(totals, 0, 1, units, a.G, DK * DV, a.state, nullptr, a.stream);
     if (err != hipSuccess) return err;
   }
-  return launch_kernel(COTTN_SYM_STR(fwd_bidir_apply), COTTN_SYM(fwd_bidir_apply)<D, C>, dim3(units * a.G),
+  return launch_kernel(COTTN_SYM_STR(fwd_bidir_apply), COTTN_SYM(fwd_bidir_apply)<DK, DV, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q), a.s,
                        static_cast<e16_t*>(a.O), totals, a.G, sum_in_apply ? a.G : 1,
                        sum_in_apply ? a.state : nullptr, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
                        a.seq_len, a.s_per_unit);
 }
 
-template <int D>
+template <int DK, int DV>
 hipError_t run_bwd_bidir(const CausalArgs& a) {
   constexpr int C = 64;
-  using Cfg = BiCfg<D, C>;
+  using Cfg = BiCfg<DK, DV, C>;
   const int units = a.B * a.H;
   char* ws = static_cast<char*>(a.workspace);
   float* s_totals = reinterpret_cast<float*>(ws);
-  const size_t pair_stride = state_array_bytes(a.B, a.H, D, a.G) / sizeof(float);
+  const size_t pair_stride = state_array_bytes(a.B, a.H, DK, DV, a.G) / sizeof(float);
   float* g_totals = s_totals + pair_stride;
-  float* ds_partial = reinterpret_cast<float*>(ws + 2 * state_array_bytes(a.B, a.H, D, a.G));
+  float* ds_partial = reinterpret_cast<float*>(ws + 2 * state_array_bytes(a.B, a.H, DK, DV, a.G));
   const bool few = a.G <= kMaxSegmentsSummedInScan;
   hipError_t err;
   const float* s_src = s_totals;
@@ -373,12 +394,12 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
     if (err != hipSuccess) return err;
     err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.Q, a.dO, g_totals));
     if (err != hipSuccess) return err;
-    err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, D * D, nullptr, ds_partial,
+    err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, DK * DV, nullptr, ds_partial,
                                a.stream);
     if (err != hipSuccess) return err;
-    n_ds = D * D / 256;  // the combine kernel's partial sums per (batch, head)
+    n_ds = DK * DV / 256;  // the combine kernel's partial sums per (batch, head)
   }
-  return launch_kernel(COTTN_SYM_STR(bwd_bidir_apply), COTTN_SYM(bwd_bidir_apply)<D, C>, dim3(units * a.G),
+  return launch_kernel(COTTN_SYM_STR(bwd_bidir_apply), COTTN_SYM(bwd_bidir_apply)<DK, DV, C>, dim3(units * a.G),
                        dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q),
                        static_cast<const e16_t*>(a.K), static_cast<const e16_t*>(a.V),
                        static_cast<const e16_t*>(a.dO), a.s, static_cast<e16_t*>(a.dQ),
@@ -397,22 +418,22 @@ hipError_t launch_bidir_combine(float* totals, size_t pair_stride, int n_pairs, 
 }
 #endif
 
-hipError_t COTTN_SYM(fwd_bidir)(const CausalArgs& a) {
-  switch (a.d) {
-    case 32: return run_fwd_bidir<32>(a);
-    case 64: return run_fwd_bidir<64>(a);
-    case 128: return run_fwd_bidir<128>(a);
-    default: return hipErrorInvalidValue;
+#define COTTN_FOR_EACH_DK_DV(CALL)                                                              \
+  switch (a.dk * 1000 + a.dv) {                                                                 \
+    case 32032: return CALL<32, 32>(a);                                                         \
+    case 32064: return CALL<32, 64>(a);                                                         \
+    case 32128: return CALL<32, 128>(a);                                                        \
+    case 64032: return CALL<64, 32>(a);                                                         \
+    case 64064: return CALL<64, 64>(a);                                                         \
+    case 64128: return CALL<64, 128>(a);                                                        \
+    case 128032: return CALL<128, 32>(a);                                                       \
+    case 128064: return CALL<128, 64>(a);                                                       \
+    case 128128: return CALL<128, 128>(a);                                                      \
+    default: return hipErrorInvalidValue;                                                       \
   }
-}
 
-hipError_t COTTN_SYM(bwd_bidir)(const CausalArgs& a) {
-  switch (a.d) {
-    case 32: return run_bwd_bidir<32>(a);
-    case 64: return run_bwd_bidir<64>(a);
-    case 128: return run_bwd_bidir<128>(a);
-    default: return hipErrorInvalidValue;
-  }
-}
+hipError_t COTTN_SYM(fwd_bidir)(const CausalArgs& a) { COTTN_FOR_EACH_DK_DV(run_fwd_bidir) }
+
+hipError_t COTTN_SYM(bwd_bidir)(const CausalArgs& a) { COTTN_FOR_EACH_DK_DV(run_bwd_bidir) }
 
 }  // namespace cottn

@@ -50,26 +50,36 @@
 namespace cottn {
 namespace {
 
-template <int D, int C>
+// DK, DV: the head dimensions of the keys / queries and of the values / outputs (Sec. 2.1:
+// d_H_key and d_H_value); Q, K, dQ, dK rows are DK wide, V, dO, dV rows DV wide, and both
+// running states (Kh^T V forward in time, Qh^T dO backward in time) are DK x DV.
+template <int DK, int DV, int C>
 struct BwdCfg {
   static constexpr int NW = C / 16;
   static constexpr int NT = NW * 64;
-  static constexpr int DT = D / 16;
-  static constexpr int KS = D / 32;
+  static constexpr int DTK = DK / 16, DTV = DV / 16;
+  static constexpr int KSK = DK / 32, KSV = DV / 32;
   static constexpr int NP = C / 32;
-  static constexpr int TP = tile_pitch(D, C);   // operand tiles
-  static constexpr int SP = lds_pitch(D);    // state copies
-  static constexpr int TILE = C * TP;
-  static constexpr int STATE = D * SP;
-  static constexpr int LDS_BYTES = 2 * (4 * TILE + STATE) + 4 * C + 64;
+  static constexpr int TPK = tile_pitch(DK, C), TPV = tile_pitch(DV, C);   // operand tiles
+  static constexpr int SPK = lds_pitch(DK), SPV = lds_pitch(DV);   // state copies
+  static constexpr int TILEK = C * TPK, TILEV = C * TPV;
+  // the larger of the two state copies ([d_value][d_key] in the dQ scan, [d_key][d_value] in
+  // the dK/dV scan)
+  static constexpr int STATE = DV * SPK > DK * SPV ? DV * SPK : DK * SPV;
+  static constexpr int LDS_BYTES = 2 * (2 * TILEK + 2 * TILEV + STATE) + 4 * C + 64;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
-  // the dQ kernel adds a staging tile when that does not lower the workgroups per compute unit
+  // the dQ kernel adds a staging tile when that does not lower the workgroups per compute
+  // unit, and must when the finished rows (DK wide) do not fit the rows of the dO tile
   static constexpr bool DQ_OWN_STAGE =
-      LDS_BYTES + 2 * TILE <= 160 * 1024 && (160 * 1024) / (LDS_BYTES + 2 * TILE) == WG_PER_CU;
+      lds_pitch(DK) > TPV ||
+      (LDS_BYTES + 2 * TILEK <= 160 * 1024 && (160 * 1024) / (LDS_BYTES + 2 * TILEK) == WG_PER_CU);
   static constexpr int WAVES_RAW = (WG_PER_CU >= 2 ? 2 : 1) * NW / 4;
   // never budget registers for more than two waves per SIMD unless one workgroup alone needs
   // it: spilling costs more than the second workgroup of a large chunk gains
-  static constexpr int WAVES_PER_EU = NW / 4 > 2 ? NW / 4 : (WAVES_RAW > 2 ? 2 : WAVES_RAW);
+  // (DK = 128 with DV = 64: the dQ scan's two states and its result need more than the 256
+  // registers that two waves per SIMD leave each wave)
+  static constexpr int WAVES_PER_EU =
+      (DK == 128 && DV == 64) ? 1 : NW / 4 > 2 ? NW / 4 : (WAVES_RAW > 2 ? 2 : WAVES_RAW);
 };
 
 // pack a masked accumulator tile into half of an operand fragment
@@ -104,39 +114,40 @@ __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_t
 // lane thus holds 4 consecutive keys of one value column and publishes them with one 8-byte
 // write to the transposed LDS copy St[d_value][d_key]; the update's row-side operand is the
 // K fragment already read for the intra-chunk product.
-template <int D, int C>
-__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dq_scan)(
+template <int DK, int DV, int C>
+__global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dq_scan)(
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
     const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
     const float* __restrict__ fwd_states, float* __restrict__ rev_totals,
     float* __restrict__ ds_partial, int H, int N, int G, int seg_rows, float inv_eps,
     int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
     const float* __restrict__ state_in) {
-  using Cfg = BwdCfg<D, C>;
-  using AT = AccTiles<D, Cfg::NW>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int TP = Cfg::TP, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // qh = r_i q_i
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
-  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
-  __shared__ __attribute__((aligned(16))) e16_t St[Cfg::STATE];  // state, [d_value][d_key]
+  using Cfg = BwdCfg<DK, DV, C>;
+  using AT = AccTiles<DK, DV, Cfg::NW>;   // forward-time state: key rows, value columns
+  using RT = AccTiles<DV, DK, Cfg::NW>;   // reverse-time total: value rows, key columns
+  using StageK = TileStage<DK, C, Cfg::NT>;
+  using StageV = TileStage<DV, C, Cfg::NT>;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SPK;
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // qh = r_i q_i
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // kh = r_j k_j
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];   // raw v
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILEV];   // dO
+  __shared__ __attribute__((aligned(16))) e16_t St[DV * Cfg::SPK];  // state, [d_value][d_key]
   // Every wave reads all rows of all four tiles until the end of a chunk (the reverse total
   // contracts Qs and Gs over the tokens), so finished dQ rows are staged in a tile of their
   // own when LDS has room for one; otherwise behind a barrier in the dead dO tile.
-  __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::DQ_OWN_STAGE ? Cfg::TILE : 8];
+  __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::DQ_OWN_STAGE ? Cfg::TILEK : 8];
   __shared__ float rq[C];
   __shared__ float ds_wave[Cfg::NW];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const e16_t* Qu = Q + ubase;
-  const e16_t* Ku = K + ubase;
-  const e16_t* Vu = V + ubase;
-  const e16_t* Gu = dO + ubase;
-  e16_t* dQu = dQ + ubase;
+  const e16_t* Qu = Q + size_t(unit) * N * DK;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
+  const e16_t* Gu = dO + size_t(unit) * N * DV;
+  e16_t* dQu = dQ + size_t(unit) * N * DK;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -148,46 +159,48 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
   // By-product for the dK/dV kernel: this segment's total of qh^T dO (segments after the
   // first; earlier segments need it), accumulated in that kernel's layout: element [v] of
   // lane (r, q4) of tile (y, x) is R[key 16 ct + r][value 16 rt + 4 q4 + v].
-  f32x4 racc[AT::NCT][AT::NRT];
+  f32x4 racc[RT::NCT][RT::NRT];
   const bool with_rev = rev_totals != nullptr && g > 0;
 #pragma unroll
   for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
-    for (int y = 0; y < AT::NRT; ++y) {
-      sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-      racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int y = 0; y < AT::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int x = 0; x < RT::NCT; ++x)
+#pragma unroll
+    for (int y = 0; y < RT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
   // the first chunk's rows and the stored states are all requested before anything waits
   float ds_lane = 0.f;
-  Stage qst, kst, vst, gst;
+  StageK qst, kst;
+  StageV vst, gst;
   qst.fetch(Qu, row_begin, row_end);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   gst.fetch(Gu, row_begin, row_end);
   if (fwd_states != nullptr && g > 0 && AT::active(w)) {
-    const float* src = fwd_states + size_t(unit) * G * D * D;
+    const float* src = fwd_states + size_t(unit) * G * DK * DV;
     add_stored_states<AT::STATE_BATCH>(
         sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
-          const float* p = src + size_t(gp) * D * D + (16 * AT::row_tile(w, y) + 4 * q4) * D +
+          const float* p = src + size_t(gp) * DK * DV + (16 * AT::row_tile(w, y) + 4 * q4) * DV +
                            16 * AT::col_tile(w, x) + r;
-          return f32x4{p[0], p[D], p[2 * D], p[3 * D]};
+          return f32x4{p[0], p[DV], p[2 * DV], p[3 * DV]};
         });
   }
   // the state of the rows before this piece of the sequence belongs to every segment's start
   if (state_in != nullptr && AT::active(w)) {
-    const float* src = state_in + size_t(unit) * D * D;
+    const float* src = state_in + size_t(unit) * DK * DV;
 #pragma unroll
     for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < AT::NRT; ++y) {
-        const float* p = src + (16 * AT::row_tile(w, y) + 4 * q4) * D + 16 * AT::col_tile(w, x) + r;
-        sacc[x][y] += f32x4{p[0], p[D], p[2 * D], p[3 * D]};
+        const float* p = src + (16 * AT::row_tile(w, y) + 4 * q4) * DV + 16 * AT::col_tile(w, x) + r;
+        sacc[x][y] += f32x4{p[0], p[DV], p[2 * DV], p[3 * DV]};
       }
   }
 
-  RowPieces<D> finished;  // dQ rows of the previous chunk, stored one chunk late
+  RowPieces<DK> finished;  // dQ rows of the previous chunk, stored one chunk late
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     if (AT::active(w)) {
 #pragma unroll
@@ -202,7 +215,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
         }
     }
     {
-      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      float rqv[StageK::PASSES], rkv[StageK::PASSES];
       qst.row_rinv(inv_eps, rqv);
       kst.row_rinv(inv_eps, rkv);
       qst.commit_scaled(Qs, rqv);
@@ -217,27 +230,27 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       vst.fetch(Vu, row0 + C, row_end);
       gst.fetch(Gu, row0 + C, row_end);
     }
-    if (row0 > row_begin) store_row_pieces<D>(finished, dQu, row0 - C + 16 * w, row_end, l);
+    if (row0 > row_begin) store_row_pieces<DK>(finished, dQu, row0 - C + 16 * w, row_end, l);
     __syncthreads();
 
     // earlier chunks: dqh^T += S dO^T (contraction over d_value = rows of St)
-    frag8 gf[Cfg::KS];  // dO rows of this wave: column-side operand of every product
+    frag8 gf[Cfg::KSV];  // dO rows of this wave: column-side operand of every product
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks)
-      gf[ks] = lds_row_frag(Gs + (16 * w + r) * TP + 32 * ks + 8 * q4);
+    for (int ks = 0; ks < Cfg::KSV; ++ks)
+      gf[ks] = lds_row_frag(Gs + (16 * w + r) * TPV + 32 * ks + 8 * q4);
     // dq[nt][v] = dqh[query 16w + r][key feature 16 nt + 4 q4 + v]
-    f32x4 dq[Cfg::DT];
+    f32x4 dq[Cfg::DTK];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
-      frag8 sf[Cfg::DT];
+    for (int ks = 0; ks < Cfg::KSV; ++ks) {
+      frag8 sf[Cfg::DTK];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt)
+      for (int nt = 0; nt < Cfg::DTK; ++nt)
         sf[nt] = lds_col_frag(St, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(sf[nt], gf[ks], dq[nt]);
+      for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = mma16(sf[nt], gf[ks], dq[nt]);
       __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -247,32 +260,32 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_below = 2 * p <= w;
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the A slots
-      frag8 kc[Cfg::DT], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KS];
-      frag8 qcol[AT::NCT], grow[AT::NRT];
+      frag8 kc[Cfg::DTK], vcol[AT::NCT], krow[AT::NRT], vr[2][Cfg::KSV];
+      frag8 qcol[RT::NCT], grow[RT::NRT];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) kc[nt] = lds_col_frag(Ks, TP, t0, t1, 16 * nt, r);
+      for (int nt = 0; nt < Cfg::DTK; ++nt) kc[nt] = lds_col_frag(Ks, TPK, t0, t1, 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
-        vcol[x] = lds_col_frag(Vs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
+        vcol[x] = lds_col_frag(Vs, TPV, t0, t1, 16 * AT::col_tile(w, x), r);
       if (AT::WPC != 1) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
-          krow[y] = lds_col_frag(Ks, TP, t0, t1, 16 * AT::row_tile(w, y), r);
+          krow[y] = lds_col_frag(Ks, TPK, t0, t1, 16 * AT::row_tile(w, y), r);
       }
-      if (with_rev && AT::active(w)) {
+      if (with_rev && RT::active(w)) {
 #pragma unroll
-        for (int x = 0; x < AT::NCT; ++x)
-          qcol[x] = lds_col_frag(Qs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
+        for (int x = 0; x < RT::NCT; ++x)
+          qcol[x] = lds_col_frag(Qs, TPK, t0, t1, 16 * RT::col_tile(w, x), r);
 #pragma unroll
-        for (int y = 0; y < AT::NRT; ++y)
-          grow[y] = lds_col_frag(Gs, TP, t0, t1, 16 * AT::row_tile(w, y), r);
+        for (int y = 0; y < RT::NRT; ++y)
+          grow[y] = lds_col_frag(Gs, TPV, t0, t1, 16 * RT::row_tile(w, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks)
-            vr[half][ks] = lds_row_frag(Vs + (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4);
+          for (int ks = 0; ks < Cfg::KSV; ++ks)
+            vr[half][ks] = lds_row_frag(Vs + (16 * (2 * p + half) + r) * TPV + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
@@ -282,14 +295,14 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           const int jt = 2 * p + half;
           f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks) t = mma16(vr[half][ks], gf[ks], t);
+          for (int ks = 0; ks < Cfg::KSV; ++ks) t = mma16(vr[half][ks], gf[ks], t);
           // t[v] = dO_(16w + r) . v_(16jt + 4 q4 + v); keep key <= query
           const bool full = jt < w, diag = jt == w;
           put_half(af, half, t, full || (diag && 4 * q4 + 0 <= r), full || (diag && 4 * q4 + 1 <= r),
                    full || (diag && 4 * q4 + 2 <= r), full || (diag && 4 * q4 + 3 <= r));
         }
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) dq[nt] = mma16(kc[nt], af, dq[nt]);
+        for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = mma16(kc[nt], af, dq[nt]);
       }
       // state update: S += kh^T v over these 32 tokens
       if (AT::active(w)) {
@@ -298,43 +311,43 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
 #pragma unroll
           for (int x = 0; x < AT::NCT; ++x)
             sacc[x][y] = mma16(AT::WPC == 1 ? kc[y] : krow[y], vcol[x], sacc[x][y]);
-        // reverse total: R^T += dO^T qh over the same tokens
-        if (with_rev) {
+      }
+      // reverse total: R^T += dO^T qh over the same tokens
+      if (with_rev && RT::active(w)) {
 #pragma unroll
-          for (int y = 0; y < AT::NRT; ++y)
+        for (int y = 0; y < RT::NRT; ++y)
 #pragma unroll
-            for (int x = 0; x < AT::NCT; ++x) racc[x][y] = mma16(grow[y], qcol[x], racc[x][y]);
-        }
+          for (int x = 0; x < RT::NCT; ++x) racc[x][y] = mma16(grow[y], qcol[x], racc[x][y]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 
     // epilogue: normalisation chain rule on the rows (Qs holds qh), then s r_i and the store
     const float ri = rq[16 * w + r];
-    const float rho = project_out_row<D, TP, true>(dq, Qs + 16 * w * TP, ri, inv_eps, r, q4);
+    const float rho = project_out_row<DK, TPK, true>(dq, Qs + 16 * w * TPK, ri, inv_eps, r, q4);
     if (q4 == 0) ds_lane += rho;
     if (Cfg::DQ_OWN_STAGE) {
-      gather_rows_transposed<D>(dq, scale * ri, Os + 16 * w * TP, l, finished);
+      gather_rows_transposed<DK>(dq, scale * ri, Os + 16 * w * TPK, l, finished);
     } else {
       __syncthreads();  // every wave is done with the dO tile
-      gather_rows_transposed<D>(dq, scale * ri, Gs + 16 * w * TP, l, finished);
+      gather_rows_transposed<DK>(dq, scale * ri, Gs + 16 * w * TPV, l, finished);
     }
     __syncthreads();
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<D>(finished, dQu, last + 16 * w, row_end, l);
+    store_row_pieces<DK>(finished, dQu, last + 16 * w, row_end, l);
   }
 
-  if (seq_len != nullptr) zero_rows_e16<D>(dQu, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<DK>(dQu, row_end, seg_end);  // rows that do not exist
 
-  if (with_rev && AT::active(w)) {
-    float* out = rev_totals + (size_t(unit) * G + g) * D * D;
+  if (with_rev && RT::active(w)) {
+    float* out = rev_totals + (size_t(unit) * G + g) * DK * DV;
 #pragma unroll
-    for (int x = 0; x < AT::NCT; ++x)
+    for (int x = 0; x < RT::NCT; ++x)
 #pragma unroll
-      for (int y = 0; y < AT::NRT; ++y)
-        store_state_words(out + (16 * AT::col_tile(w, x) + r) * D + 16 * AT::row_tile(w, y) + 4 * q4,
+      for (int y = 0; y < RT::NRT; ++y)
+        store_state_words(out + (16 * RT::col_tile(w, x) + r) * DV + 16 * RT::row_tile(w, y) + 4 * q4,
                           racc[x][y]);
   }
 
@@ -357,35 +370,35 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
 // is R[16 ct + r][16 rt + 4 q4 + v], published with one 8-byte write to the row-major LDS
 // copy Rl[d_key][d_value]; the update's row-side operand is the dO fragment already read
 // for the intra-chunk dV product.
-template <int D, int C>
-__global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dkdv_scan)(
+template <int DK, int DV, int C>
+__global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dkdv_scan)(
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
     const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dK,
     e16_t* __restrict__ dV, const float* __restrict__ rev_states,
     const float* __restrict__ ds_partial, float* __restrict__ ds, int B, int H, int N, int G,
     int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
     const float* __restrict__ rev_in, float* __restrict__ rev_out) {
-  using Cfg = BwdCfg<D, C>;
-  using AT = AccTiles<D, Cfg::NW>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  constexpr int TP = Cfg::TP, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // r_i q_i
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // raw k
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v
-  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILE];   // dO
-  __shared__ __attribute__((aligned(16))) e16_t Rl[Cfg::STATE];  // reverse state, [d_key][d_value]
+  using Cfg = BwdCfg<DK, DV, C>;
+  using AT = AccTiles<DV, DK, Cfg::NW>;   // value rows, key columns (the state is held transposed)
+  using StageK = TileStage<DK, C, Cfg::NT>;
+  using StageV = TileStage<DV, C, Cfg::NT>;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SPV;
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // r_i q_i
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];   // raw v
+  __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILEV];   // dO
+  __shared__ __attribute__((aligned(16))) e16_t Rl[DK * Cfg::SPV];  // reverse state, [d_key][d_value]
   __shared__ float rk[C];
 
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const size_t ubase = size_t(unit) * N * D;
-  const e16_t* Qu = Q + ubase;
-  const e16_t* Ku = K + ubase;
-  const e16_t* Vu = V + ubase;
-  const e16_t* Gu = dO + ubase;
-  e16_t* dKu = dK + ubase;
-  e16_t* dVu = dV + ubase;
+  const e16_t* Qu = Q + size_t(unit) * N * DK;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
+  const e16_t* Gu = dO + size_t(unit) * N * DV;
+  e16_t* dKu = dK + size_t(unit) * N * DK;
+  e16_t* dVu = dV + size_t(unit) * N * DV;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -413,7 +426,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
 #pragma unroll
     for (int y = 0; y < AT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
   // the last chunk's rows and the stored states are all requested before anything waits
-  Stage qst, kst, vst, gst;
+  StageK qst, kst;
+  StageV vst, gst;
   if (n_chunks > 0) {  // (a segment of a padded batch can be empty)
     const int first = row_begin + (n_chunks - 1) * C;
     qst.fetch(Qu, first, row_end);
@@ -422,29 +436,31 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     gst.fetch(Gu, first, row_end);
   }
   if (rev_states != nullptr && g < G - 1 && AT::active(w)) {
-    const float* src = rev_states + size_t(unit) * G * D * D;
+    const float* src = rev_states + size_t(unit) * G * DK * DV;
     add_stored_states<AT::STATE_BATCH>(
         racc, sum_totals ? g + 1 : g, sum_totals ? G - 1 : g, [&](int gp, int x, int y) {
-          return *reinterpret_cast<const f32x4*>(src + size_t(gp) * D * D +
-                                                 (16 * AT::col_tile(w, x) + r) * D +
+          return *reinterpret_cast<const f32x4*>(src + size_t(gp) * DK * DV +
+                                                 (16 * AT::col_tile(w, x) + r) * DV +
                                                  16 * AT::row_tile(w, y) + 4 * q4);
         });
   }
   // the reverse state of the rows after this piece of the sequence belongs to every segment
   if (rev_in != nullptr && AT::active(w)) {
-    const float* src = rev_in + size_t(unit) * D * D;
+    const float* src = rev_in + size_t(unit) * DK * DV;
 #pragma unroll
     for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < AT::NRT; ++y)
-        racc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::col_tile(w, x) + r) * D +
+        racc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::col_tile(w, x) + r) * DV +
                                                       16 * AT::row_tile(w, y) + 4 * q4);
   }
 
-  RowPieces<D> done_k, done_v;  // dK and dV rows of the previous chunk, stored one chunk late
+  RowPieces<DK> done_k;  // dK and dV rows of the previous chunk, stored one chunk late
+  RowPieces<DV> done_v;
 #pragma unroll
-  for (int j = 0; j < RowPieces<D>::PER_LANE; ++j)
-    done_k.v[j] = done_v.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) done_k.v[j] = uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int j = 0; j < RowPieces<DV>::PER_LANE; ++j) done_v.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int c = n_chunks - 1; c >= 0; --c) {
     const int row0 = row_begin + c * C;
     if (AT::active(w)) {
@@ -460,7 +476,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
         }
     }
     {
-      float rqv[Stage::PASSES], rkv[Stage::PASSES];
+      float rqv[StageK::PASSES], rkv[StageK::PASSES];
       qst.row_rinv(inv_eps, rqv);
       kst.row_rinv(inv_eps, rkv);
       qst.commit_scaled(Qs, rqv);
@@ -476,39 +492,56 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
       gst.fetch(Gu, row0 - C, row_end);
     }
     if (c < n_chunks - 1) {
-      store_row_pieces<D>(done_k, dKu, row0 + C + 16 * w, row_end, l);
-      store_row_pieces<D>(done_v, dVu, row0 + C + 16 * w, row_end, l);
+      store_row_pieces<DK>(done_k, dKu, row0 + C + 16 * w, row_end, l);
+      store_row_pieces<DV>(done_v, dVu, row0 + C + 16 * w, row_end, l);
     }
     __syncthreads();
 
-    frag8 kf[Cfg::KS], vf[Cfg::KS];  // this wave's key rows and value rows (column side)
+    frag8 kf[Cfg::KSK], vf[Cfg::KSV];  // this wave's key rows and value rows (column side)
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
-      kf[ks] = lds_row_frag(Ks + (16 * w + r) * TP + 32 * ks + 8 * q4);
-      vf[ks] = lds_row_frag(Vs + (16 * w + r) * TP + 32 * ks + 8 * q4);
-    }
+    for (int ks = 0; ks < Cfg::KSK; ++ks)
+      kf[ks] = lds_row_frag(Ks + (16 * w + r) * TPK + 32 * ks + 8 * q4);
+#pragma unroll
+    for (int ks = 0; ks < Cfg::KSV; ++ks)
+      vf[ks] = lds_row_frag(Vs + (16 * w + r) * TPV + 32 * ks + 8 * q4);
     // dk[nt][v] = dkh[key 16w + r][feature 16 nt + 4 q4 + v]; dv likewise before s r_j
-    f32x4 dk[Cfg::DT], dv[Cfg::DT];
+    f32x4 dk[Cfg::DTK], dv[Cfg::DTV];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DT; ++nt) {
-      dk[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int nt = 0; nt < Cfg::DTK; ++nt) dk[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // later chunks: dv^T += R^T k^T (over d_key), dkh^T += R v^T (over d_value)
+    constexpr int KS_BOTH = Cfg::KSK < Cfg::KSV ? Cfg::KSK : Cfg::KSV;
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
-      frag8 rcol[Cfg::DT], rrow[Cfg::DT];
+    for (int ks = 0; ks < (Cfg::KSK > Cfg::KSV ? Cfg::KSK : Cfg::KSV); ++ks) {
+      frag8 rcol[Cfg::DTV], rrow[Cfg::DTK];
+      if (ks < Cfg::KSK) {
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) {
-        rcol[nt] = lds_col_frag(Rl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
-        rrow[nt] = lds_row_frag(Rl + (16 * nt + r) * SP + 32 * ks + 8 * q4);
+        for (int nt = 0; nt < Cfg::DTV; ++nt)
+          rcol[nt] = lds_col_frag(Rl, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+      }
+      if (ks < Cfg::KSV) {
+#pragma unroll
+        for (int nt = 0; nt < Cfg::DTK; ++nt)
+          rrow[nt] = lds_row_frag(Rl + (16 * nt + r) * SP + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
+      if (ks < KS_BOTH && Cfg::DTK == Cfg::DTV) {
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) {
-        dv[nt] = mma16(rcol[nt], kf[ks], dv[nt]);
-        dk[nt] = mma16(rrow[nt], vf[ks], dk[nt]);
+        for (int nt = 0; nt < Cfg::DTK; ++nt) {
+          dv[nt] = mma16(rcol[nt], kf[ks], dv[nt]);
+          dk[nt] = mma16(rrow[nt], vf[ks], dk[nt]);
+        }
+      } else {
+        if (ks < Cfg::KSK) {
+#pragma unroll
+          for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = mma16(rcol[nt], kf[ks], dv[nt]);
+        }
+        if (ks < Cfg::KSV) {
+#pragma unroll
+          for (int nt = 0; nt < Cfg::DTK; ++nt) dk[nt] = mma16(rrow[nt], vf[ks], dk[nt]);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -518,16 +551,16 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     for (int p = 0; p < Cfg::NP; ++p) {
       const bool diag_or_above = 2 * p + 1 >= w;
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;  // token order of the slots
-      frag8 gc[Cfg::DT], qcol[AT::NCT], grow[AT::NRT];
+      frag8 gc[Cfg::DTV], qcol[AT::NCT], grow[AT::NRT];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DT; ++nt) gc[nt] = lds_col_frag(Gs, TP, t0, t1, 16 * nt, r);
+      for (int nt = 0; nt < Cfg::DTV; ++nt) gc[nt] = lds_col_frag(Gs, TPV, t0, t1, 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < AT::NCT; ++x)
-        qcol[x] = lds_col_frag(Qs, TP, t0, t1, 16 * AT::col_tile(w, x), r);
+        qcol[x] = lds_col_frag(Qs, TPK, t0, t1, 16 * AT::col_tile(w, x), r);
       if (AT::WPC != 1) {
 #pragma unroll
         for (int y = 0; y < AT::NRT; ++y)
-          grow[y] = lds_col_frag(Gs, TP, t0, t1, 16 * AT::row_tile(w, y), r);
+          grow[y] = lds_col_frag(Gs, TPV, t0, t1, 16 * AT::row_tile(w, y), r);
       }
       __builtin_amdgcn_sched_barrier(0);
       // reverse state update: R^T += dO^T (r q) over these 32 tokens
@@ -539,17 +572,18 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
             racc[x][y] = mma16(AT::WPC == 1 ? gc[y] : grow[y], qcol[x], racc[x][y]);
       }
       if (diag_or_above) {
-        frag8 qr[2][Cfg::KS], gr[2][Cfg::KS], qc[Cfg::DT];
+        frag8 qr[2][Cfg::KSK], gr[2][Cfg::KSV], qc[Cfg::DTK];
 #pragma unroll
-        for (int half = 0; half < 2; ++half)
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks) {
-            const int off = (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4;
-            qr[half][ks] = lds_row_frag(Qs + off);
-            gr[half][ks] = lds_row_frag(Gs + off);
-          }
+          for (int ks = 0; ks < Cfg::KSK; ++ks)
+            qr[half][ks] = lds_row_frag(Qs + (16 * (2 * p + half) + r) * TPK + 32 * ks + 8 * q4);
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) qc[nt] = lds_col_frag(Qs, TP, t0, t1, 16 * nt, r);
+          for (int ks = 0; ks < Cfg::KSV; ++ks)
+            gr[half][ks] = lds_row_frag(Gs + (16 * (2 * p + half) + r) * TPV + 32 * ks + 8 * q4);
+        }
+#pragma unroll
+        for (int nt = 0; nt < Cfg::DTK; ++nt) qc[nt] = lds_col_frag(Qs, TPK, t0, t1, 16 * nt, r);
         __builtin_amdgcn_sched_barrier(0);
         frag8 pf, af;
 #pragma unroll
@@ -557,10 +591,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           const int it = 2 * p + half;
           f32x4 tp = {0.f, 0.f, 0.f, 0.f}, ta = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks) {
-            tp = mma16(qr[half][ks], kf[ks], tp);
-            ta = mma16(gr[half][ks], vf[ks], ta);
-          }
+          for (int ks = 0; ks < Cfg::KSK; ++ks) tp = mma16(qr[half][ks], kf[ks], tp);
+#pragma unroll
+          for (int ks = 0; ks < Cfg::KSV; ++ks) ta = mma16(gr[half][ks], vf[ks], ta);
           // t*[v]: query 16 it + 4 q4 + v, key 16 w + r; keep key <= query
           const bool full = it > w, diag = it == w;
           const bool k0 = full || (diag && r <= 4 * q4 + 0), k1 = full || (diag && r <= 4 * q4 + 1),
@@ -569,10 +602,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
           put_half(af, half, ta, k0, k1, k2, k3);
         }
 #pragma unroll
-        for (int nt = 0; nt < Cfg::DT; ++nt) {
-          dv[nt] = mma16(gc[nt], pf, dv[nt]);
-          dk[nt] = mma16(qc[nt], af, dk[nt]);
-        }
+        for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = mma16(gc[nt], pf, dv[nt]);
+#pragma unroll
+        for (int nt = 0; nt < Cfg::DTK; ++nt) dk[nt] = mma16(qc[nt], af, dk[nt]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -580,28 +612,28 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<D, C>::WAVES_PER_EU)) void COTTN_SYM
     // epilogue: dv_j = s r_j dv; dk_j through the normalisation chain rule; both staged in
     // this wave's own (dead) rows of Vs and Ks
     const float rj = rk[16 * w + r];
-    project_out_row<D, TP, false>(dk, Ks + 16 * w * TP, rj, inv_eps, r, q4);
+    project_out_row<DK, TPK, false>(dk, Ks + 16 * w * TPK, rj, inv_eps, r, q4);
     wave_lds_sync();  // own Ks / Vs rows (kf, vf, raw k) were read before the staging writes
-    gather_rows_transposed<D>(dk, scale * rj, Ks + 16 * w * TP, l, done_k);
-    gather_rows_transposed<D>(dv, scale * rj, Vs + 16 * w * TP, l, done_v);
+    gather_rows_transposed<DK>(dk, scale * rj, Ks + 16 * w * TPK, l, done_k);
+    gather_rows_transposed<DV>(dv, scale * rj, Vs + 16 * w * TPV, l, done_v);
     __syncthreads();
   }
   if (n_chunks > 0) {
-    store_row_pieces<D>(done_k, dKu, row_begin + 16 * w, row_end, l);
-    store_row_pieces<D>(done_v, dVu, row_begin + 16 * w, row_end, l);
+    store_row_pieces<DK>(done_k, dKu, row_begin + 16 * w, row_end, l);
+    store_row_pieces<DV>(done_v, dVu, row_begin + 16 * w, row_end, l);
   }
   if (seq_len != nullptr) {  // rows that do not exist
-    zero_rows_e16<D>(dKu, row_end, seg_end);
-    zero_rows_e16<D>(dVu, row_end, seg_end);
+    zero_rows_e16<DK>(dKu, row_end, seg_end);
+    zero_rows_e16<DV>(dVu, row_end, seg_end);
   }
   // the first segment ends with the reverse state of the whole piece and what followed it
   if (rev_out != nullptr && g == 0 && AT::active(w)) {
-    float* out = rev_out + size_t(unit) * D * D;
+    float* out = rev_out + size_t(unit) * DK * DV;
 #pragma unroll
     for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < AT::NRT; ++y)
-        *reinterpret_cast<f32x4*>(out + (16 * AT::col_tile(w, x) + r) * D +
+        *reinterpret_cast<f32x4*>(out + (16 * AT::col_tile(w, x) + r) * DV +
                                   16 * AT::row_tile(w, y) + 4 * q4) = racc[x][y];
   }
 }
@@ -628,9 +660,9 @@ __global__ __launch_bounds__(256) void bwd_reduce_ds(const float* __restrict__ p
   if (threadIdx.x == 0) ds[h] = red[0];
 }
 
-template <int D, int C>
+template <int DK, int DV, int C>
 hipError_t run_bwd_causal(const CausalArgs& a) {
-  using Cfg = BwdCfg<D, C>;
+  using Cfg = BwdCfg<DK, DV, C>;
   const int units = a.B * a.H;
   const e16_t* Q = static_cast<const e16_t*>(a.Q);
   const e16_t* K = static_cast<const e16_t*>(a.K);
@@ -648,15 +680,15 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
     // Forward-time states: taken over from the forward call when it left them behind (raw
     // totals or carried prefixes, by the same rule as here), else recomputed from K and V.
     float* own_fwd = reinterpret_cast<float*>(ws);
-    rev_states = reinterpret_cast<float*>(ws + state_array_bytes(a.B, a.H, D, a.G));
-    ws += 2 * state_array_bytes(a.B, a.H, D, a.G);
+    rev_states = reinterpret_cast<float*>(ws + state_array_bytes(a.B, a.H, DK, DV, a.G));
+    ws += 2 * state_array_bytes(a.B, a.H, DK, DV, a.G);
     if (a.saved_fwd_states != nullptr) {
       fwd_states = a.saved_fwd_states;
     } else {
       err = COTTN_SYM(launch_fwd_segment_totals)(a, own_fwd);
       if (err != hipSuccess) return err;
       if (!sum_in_scan) {
-        err = launch_bwd_state_carry(own_fwd, nullptr, units, a.G, D * D, a.stream);
+        err = launch_bwd_state_carry(own_fwd, nullptr, units, a.G, DK * DV, a.stream);
         if (err != hipSuccess) return err;
       }
       fwd_states = own_fwd;
@@ -664,17 +696,17 @@ hipError_t run_bwd_causal(const CausalArgs& a) {
   }
   float* ds_partial = reinterpret_cast<float*>(ws);
   // the dQ scan leaves the reverse-time segment totals (of qh^T dO) behind for the dK/dV scan
-  err = launch_kernel(COTTN_SYM_STR(bwd_dq_scan), COTTN_SYM(bwd_dq_scan)<D, C>, grid, block, 0, a.stream, Q, K, V,
+  err = launch_kernel(COTTN_SYM_STR(bwd_dq_scan), COTTN_SYM(bwd_dq_scan)<DK, DV, C>, grid, block, 0, a.stream, Q, K, V,
                       dO, a.s, static_cast<e16_t*>(a.dQ), fwd_states, rev_states, ds_partial, a.H,
                       a.N, a.G, a.seg_rows, inv_eps, sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit,
                       a.state_in);
   if (err != hipSuccess) return err;
   if (a.G > 1 && !sum_in_scan) {
-    err = launch_bwd_state_carry(nullptr, rev_states, units, a.G, D * D, a.stream);
+    err = launch_bwd_state_carry(nullptr, rev_states, units, a.G, DK * DV, a.stream);
     if (err != hipSuccess) return err;
   }
   // the dK/dV kernel also reduces the ds partial sums written by the dQ kernel
-  return launch_kernel(COTTN_SYM_STR(bwd_dkdv_scan), COTTN_SYM(bwd_dkdv_scan)<D, C>, grid, block, 0, a.stream, Q,
+  return launch_kernel(COTTN_SYM_STR(bwd_dkdv_scan), COTTN_SYM(bwd_dkdv_scan)<DK, DV, C>, grid, block, 0, a.stream, Q,
                        K, V, dO, a.s, static_cast<e16_t*>(a.dK), static_cast<e16_t*>(a.dV),
                        rev_states, ds_partial, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit, a.rev_state_in,
@@ -699,14 +731,21 @@ hipError_t launch_reduce_ds(const float* partial, float* ds, int B, int H, int G
 #endif
 
 hipError_t COTTN_SYM(bwd_causal)(const CausalArgs& a) {
-  switch (a.d * 1000 + a.C) {
-    case 32064: return run_bwd_causal<32, 64>(a);
-    case 32128: return run_bwd_causal<32, 128>(a);
-    case 32256: return run_bwd_causal<32, 256>(a);
-    case 64064: return run_bwd_causal<64, 64>(a);
-    case 64128: return run_bwd_causal<64, 128>(a);
-    case 64256: return run_bwd_causal<64, 256>(a);
-    case 128064: return run_bwd_causal<128, 64>(a);
+  // d_key != d_value: chunks of 64 rows
+  switch ((a.dk * 1000 + a.dv) * 1000 + a.C) {
+    case 32032064: return run_bwd_causal<32, 32, 64>(a);
+    case 32032128: return run_bwd_causal<32, 32, 128>(a);
+    case 32032256: return run_bwd_causal<32, 32, 256>(a);
+    case 64064064: return run_bwd_causal<64, 64, 64>(a);
+    case 64064128: return run_bwd_causal<64, 64, 128>(a);
+    case 64064256: return run_bwd_causal<64, 64, 256>(a);
+    case 128128064: return run_bwd_causal<128, 128, 64>(a);
+    case 32064064: return run_bwd_causal<32, 64, 64>(a);
+    case 32128064: return run_bwd_causal<32, 128, 64>(a);
+    case 64032064: return run_bwd_causal<64, 32, 64>(a);
+    case 64128064: return run_bwd_causal<64, 128, 64>(a);
+    case 128032064: return run_bwd_causal<128, 32, 64>(a);
+    case 128064064: return run_bwd_causal<128, 64, 64>(a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -471,7 +471,7 @@ hipError_t run_bwd(const CausalArgs& a, bool causal) {
   const float* V = static_cast<const float*>(a.V);
   const float* dO = static_cast<const float*>(a.dO);
   char* ws = static_cast<char*>(a.workspace);
-  const size_t arr = state_array_bytes(a.B, a.H, D, a.G);
+  const size_t arr = state_array_bytes(a.B, a.H, D, D, a.G);
   const bool have_states = !causal || a.G > 1;
   float* st0 = have_states ? reinterpret_cast<float*>(ws) : nullptr;
   float* st1 = have_states ? reinterpret_cast<float*>(ws + arr) : nullptr;
@@ -519,16 +519,16 @@ hipError_t by_d(int d, F&& f) {
 }  // namespace
 
 hipError_t fwd_causal_f32(const CausalArgs& a) {
-  return by_d(a.d, [&](auto D) { return run_fwd<decltype(D)::value>(a, true); });
+  return by_d(a.dk, [&](auto D) { return run_fwd<decltype(D)::value>(a, true); });
 }
 hipError_t fwd_bidir_f32(const CausalArgs& a) {
-  return by_d(a.d, [&](auto D) { return run_fwd<decltype(D)::value>(a, false); });
+  return by_d(a.dk, [&](auto D) { return run_fwd<decltype(D)::value>(a, false); });
 }
 hipError_t bwd_causal_f32(const CausalArgs& a) {
-  return by_d(a.d, [&](auto D) { return run_bwd<decltype(D)::value>(a, true); });
+  return by_d(a.dk, [&](auto D) { return run_bwd<decltype(D)::value>(a, true); });
 }
 hipError_t bwd_bidir_f32(const CausalArgs& a) {
-  return by_d(a.d, [&](auto D) { return run_bwd<decltype(D)::value>(a, false); });
+  return by_d(a.dk, [&](auto D) { return run_bwd<decltype(D)::value>(a, false); });
 }
 
 }  // namespace cottn

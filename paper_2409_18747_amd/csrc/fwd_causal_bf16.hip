@@ -44,18 +44,23 @@
 namespace cottn {
 namespace {
 
-template <int D, int C>
+// DK, DV: the head dimensions of the keys / queries and of the values / outputs (Sec. 2.1:
+// d_H_key and d_H_value); the state Kh^T V is DK x DV.
+template <int DK, int DV, int C>
 struct FwdCfg {
   static constexpr int NW = C / 16;
   static constexpr int NT = NW * 64;
-  static constexpr int DT = D / 16;
-  static constexpr int KS = D / 32;     // k steps of a contraction over the feature dim
+  static constexpr int DTK = DK / 16, DTV = DV / 16;
+  static constexpr int KSK = DK / 32;   // k steps of a contraction over the key features
   static constexpr int NP = C / 32;     // pairs of 16-token tiles in a chunk
-  static constexpr int TP = tile_pitch(D, C);   // operand tiles
-  static constexpr int SP = lds_pitch(D);    // state copies
-  static constexpr int TILE = C * TP;            // elements of one [C][D] LDS tile
-  static constexpr int STATE = D * SP;           // elements of the [D][D] bf16 state copy
-  static constexpr int LDS_BYTES = 2 * (3 * TILE + STATE) + 4 * C;
+  static constexpr int TPK = tile_pitch(DK, C), TPV = tile_pitch(DV, C);   // operand tiles
+  static constexpr int SP = lds_pitch(DV);   // state copy [d_key][d_value]
+  static constexpr int TILEK = C * TPK, TILEV = C * TPV;   // elements of one LDS tile
+  static constexpr int STATE = DK * SP;          // elements of the bf16 state copy
+  // finished output rows (DV wide) are staged in the wave's own dead query rows when those are
+  // wide enough, else in a tile of their own
+  static constexpr bool OWN_STAGE = lds_pitch(DV) > TPK;
+  static constexpr int LDS_BYTES = 2 * (2 * TILEK + TILEV + STATE + (OWN_STAGE ? TILEV : 0)) + 4 * C;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
   // waves per SIMD the register allocation is capped for (two workgroups per compute unit
   // when LDS allows, never more than the hardware needs for one workgroup)
@@ -69,7 +74,7 @@ struct FwdCfg {
   static constexpr int waves_per_eu() {
     if (CS == 1) return WAVES_PER_EU;
     const int own = NW * CS / 4;
-    const int wg = (160 * 1024) / (LDS_BYTES + 2 * TILE) >= 2 ? 2 : 1;
+    const int wg = (160 * 1024) / (LDS_BYTES + 2 * TILEV) >= 2 ? 2 : 1;
     return own * wg > 4 ? (own > 4 ? own : 4) : own * wg;
   }
 };
@@ -78,11 +83,12 @@ struct FwdCfg {
 // two at d = 128, where one workgroup fills the LDS of a compute unit and four waves are too
 // few to cover latencies (+6 % on a 2048-token prefill of 4096 heads); at d = 64 and 32 the
 // two variants time the same and the smaller workgroup is kept.
-template <int D, int C> struct FwdSplit { static constexpr int CS = 1; };
-template <> struct FwdSplit<128, 64> { static constexpr int CS = 2; };
+template <int DK, int DV, int C> struct FwdSplit { static constexpr int CS = 1; };
+template <> struct FwdSplit<128, 128, 64> { static constexpr int CS = 2; };
 
 // ---------------------------------------------------------------------------------------
-// Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value])
+// Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value];
+// K rows are DK wide, V rows DV wide)
 // grid = units * n_slots workgroups, workgroup (unit, g) as in the scan kernels: workgroups are
 // dealt to the XCDs by their index, and what this kernel reads stays in that XCD's L2 for the
 // scan workgroup of the same (unit, g) in the next launch.  Segment g of a unit writes slot g
@@ -91,25 +97,26 @@ template <> struct FwdSplit<128, 64> { static constexpr int CS = 2; };
 // path uses it for Kh^T V and, with (K, V) := (Q, dO), for Qh^T dO; there, given the stored
 // segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
 // also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
-template <int D, int C>
+template <int DK, int DV, int C>
 __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     const e16_t* __restrict__ K, const e16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
     const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out,
     const int* __restrict__ seq_len, int H) {
-  using Cfg = FwdCfg<D, C>;
-  using ST = AccTiles<D, Cfg::NW>;
-  using Stage = TileStage<D, C, Cfg::NT>;
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];
+  using Cfg = FwdCfg<DK, DV, C>;
+  using ST = AccTiles<DK, DV, Cfg::NW>;   // key rows, value columns
+  using StageK = TileStage<DK, C, Cfg::NT>;
+  using StageV = TileStage<DV, C, Cfg::NT>;
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
   __shared__ float dot_wave[Cfg::NW];
 
   const int unit = blockIdx.x / n_slots, g = blockIdx.x % n_slots;
   if (g >= n_compute) return;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
-  const e16_t* Ku = K + size_t(unit) * N * D;
-  const e16_t* Vu = V + size_t(unit) * N * D;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
   const int row_begin = g * seg_rows;
   const int row_end = min(valid_rows(seq_len, unit, H, N), row_begin + seg_rows);
 
@@ -120,11 +127,12 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
 #pragma unroll
     for (int y = 0; y < ST::NRT; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  Stage kst, vst;
+  StageK kst;
+  StageV vst;
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
-    float rk[Stage::PASSES];
+    float rk[StageK::PASSES];
     kst.row_rinv(inv_eps, rk);
     __syncthreads();  // previous chunk's reads of Ks/Vs are done
     kst.commit_scaled(Ks, rk);
@@ -141,10 +149,10 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
         frag8 bv[ST::NCT], ak[ST::NRT];
 #pragma unroll
         for (int x = 0; x < ST::NCT; ++x)
-          bv[x] = lds_col_frag(Vs, Cfg::TP, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
+          bv[x] = lds_col_frag(Vs, Cfg::TPV, k0, k0 + 4, 16 * ST::col_tile(w, x), r);
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
-          ak[y] = lds_col_frag(Ks, Cfg::TP, k0, k0 + 4, 16 * ST::row_tile(w, y), r);
+          ak[y] = lds_col_frag(Ks, Cfg::TPK, k0, k0 + 4, 16 * ST::row_tile(w, y), r);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
@@ -155,29 +163,29 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     }
   }
   if (ST::active(w)) {
-    float* out = seg_state + (size_t(unit) * n_slots + g) * D * D;
+    float* out = seg_state + (size_t(unit) * n_slots + g) * DK * DV;
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          store_state_word(out + (16 * ST::row_tile(w, y) + 4 * q4 + v) * D +
+          store_state_word(out + (16 * ST::row_tile(w, y) + 4 * q4 + v) * DV +
                                16 * ST::col_tile(w, x) + r, acc[x][y][v]);
   }
   if (dot_with != nullptr) {  // workgroup-uniform
     float dot = 0.f;
     if (ST::active(w)) {
-      const float* other = dot_with + size_t(unit) * dot_slots * D * D;
+      const float* other = dot_with + size_t(unit) * dot_slots * DK * DV;
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const int e = (16 * ST::row_tile(w, y) + 4 * q4 + v) * D + 16 * ST::col_tile(w, x) + r;
+            const int e = (16 * ST::row_tile(w, y) + 4 * q4 + v) * DV + 16 * ST::col_tile(w, x) + r;
             float o = 0.f;
-            for (int j = 0; j < dot_slots; ++j) o += other[size_t(j) * D * D + e];
+            for (int j = 0; j < dot_slots; ++j) o += other[size_t(j) * DK * DV + e];
             dot += acc[x][y][v] * o;
           }
     }
@@ -217,35 +225,37 @@ __global__ __launch_bounds__(256) void fwd_state_carry(float* __restrict__ seg_s
 // group, each accumulates one half of the output columns and owns the state tiles whose
 // value side is that half.  Per-wave work and registers shrink; the workgroup has twice the
 // waves to cover latencies with.
-template <int D, int C, int CS>
-__global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS>())) void COTTN_SYM(fwd_causal_scan)(
+template <int DK, int DV, int C, int CS>
+__global__ __launch_bounds__(C * 4 * CS, (FwdCfg<DK, DV, C>::template waves_per_eu<CS>())) void COTTN_SYM(fwd_causal_scan)(
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
     const float* __restrict__ s, e16_t* __restrict__ O, float* __restrict__ state_out,
     const float* __restrict__ seg_states, const float* __restrict__ state_in, int H, int N, int G,
     int seg_rows, float inv_eps, int sum_totals, const int* __restrict__ seq_len, int s_per_unit,
     int stream_q) {
-  using Cfg = FwdCfg<D, C>;
+  using Cfg = FwdCfg<DK, DV, C>;
   constexpr int RG = C / 16;           // row groups of a chunk
-  constexpr int NOT = Cfg::DT / CS;    // output column tiles per wave
-  using ST = SplitTiles<D, RG, CS>;
-  using Stage = TileStage<D, C, Cfg::NT * CS>;
-  constexpr int TP = Cfg::TP, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILE];   // raw q rows
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILE];   // kh = r_j k_j
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILE];   // raw v rows
-  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // state, [d_key][d_value]
-  // with two waves on a row group the q rows stay live in the other wave: own staging tile
-  __shared__ __attribute__((aligned(16))) e16_t Os[CS > 1 ? Cfg::TILE : 8];
+  constexpr int NOT = Cfg::DTV / CS;   // output column tiles per wave
+  using ST = SplitTiles<DV, DK, RG, CS>;   // value rows, key columns (the state is held transposed)
+  using StageK = TileStage<DK, C, Cfg::NT * CS>;
+  using StageV = TileStage<DV, C, Cfg::NT * CS>;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SP;
+  constexpr bool OWN_STAGE = CS > 1 || Cfg::OWN_STAGE;
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // raw q rows
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // kh = r_j k_j
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];   // raw v rows
+  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];   // state, [d_key][d_value]
+  // with two waves on a row group the q rows stay live in the other wave, and with outputs
+  // wider than the queries they do not fit the q rows: own staging tile
+  __shared__ __attribute__((aligned(16))) e16_t Os[OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
   const int unit = blockIdx.x / G, g = blockIdx.x % G;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const int rg = w % RG, cp = w / RG;  // row group, column part
-  const size_t ubase = size_t(unit) * N * D;
-  const e16_t* Qu = Q + ubase;
-  const e16_t* Ku = K + ubase;
-  const e16_t* Vu = V + ubase;
-  e16_t* Ou = O + ubase;
+  const e16_t* Qu = Q + size_t(unit) * N * DK;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
+  e16_t* Ou = O + size_t(unit) * N * DV;
   const float scale = unit_scale(s, unit, H, s_per_unit);
   const int row_begin = g * seg_rows;
   const int seg_end = min(N, row_begin + seg_rows);
@@ -261,29 +271,30 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
 #pragma unroll
     for (int y = 0; y < ST::NRT; ++y) sacc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
   // the first chunk's rows and the stored states are all requested before anything waits
-  Stage qst, kst, vst;
+  StageK qst, kst;
+  StageV vst;
   qst.fetch(Qu, row_begin, row_end, stream_q != 0);
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
   // the state the sequence starts from (chunked prefill) belongs to every segment's start state
   f32x4 start[ST::NCT][ST::NRT];
   if (state_in != nullptr && ST::active(rg, cp)) {
-    const float* src = state_in + size_t(unit) * D * D;
+    const float* src = state_in + size_t(unit) * DK * DV;
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-        start[x][y] = *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(rg, cp, x) + r) * D +
+        start[x][y] = *reinterpret_cast<const f32x4*>(src + (16 * ST::col_tile(rg, cp, x) + r) * DV +
                                                       16 * ST::row_tile(rg, cp, y) + 4 * q4);
   }
   if (seg_states != nullptr && g > 0 && ST::active(rg, cp)) {
-    const float* src = seg_states + size_t(unit) * G * D * D + (16 * ST::col_tile(rg, cp, 0) + r) * D +
+    const float* src = seg_states + size_t(unit) * G * DK * DV + (16 * ST::col_tile(rg, cp, 0) + r) * DV +
                        16 * ST::row_tile(rg, cp, 0) + 4 * q4;
     add_stored_states<ST::STATE_BATCH>(
         sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
           return *reinterpret_cast<const f32x4*>(
-              src + size_t(gp) * D * D +
-              16 * (ST::col_tile(rg, cp, x) - ST::col_tile(rg, cp, 0)) * D +
+              src + size_t(gp) * DK * DV +
+              16 * (ST::col_tile(rg, cp, x) - ST::col_tile(rg, cp, 0)) * DV +
               16 * (ST::row_tile(rg, cp, y) - ST::row_tile(rg, cp, 0)));
         });
   }
@@ -297,10 +308,10 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
         for (int v = 0; v < 4; ++v) sacc[x][y][v] += start[x][y][v];
   }
 
-  RowPieces<D, NOT> finished;  // output rows of the previous chunk, stored one chunk late
+  RowPieces<DV, NOT> finished;  // output rows of the previous chunk, stored one chunk late
 #pragma unroll
-  for (int j = 0; j < RowPieces<D, NOT>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
-  e16_t* stage = (CS > 1 ? Os : Qs) + 16 * rg * TP;
+  for (int j = 0; j < RowPieces<DV, NOT>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  e16_t* stage = OWN_STAGE ? Os + 16 * rg * TPV : Qs + 16 * rg * TPK;
   const int col0 = 16 * NOT * cp;  // first output column of this wave
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     // ---- publish the state (bf16) and this chunk's tiles
@@ -317,7 +328,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
         }
     }
     {
-      float rk[Stage::PASSES], rqv[Stage::PASSES];
+      float rk[StageK::PASSES], rqv[StageK::PASSES];
       qst.row_rinv(inv_eps, rqv);
       kst.row_rinv(inv_eps, rk);
       qst.commit_plain(Qs);
@@ -331,20 +342,20 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       vst.fetch(Vu, row0 + C, row_end);
     }
     if (row0 > row_begin)
-      store_row_pieces<D, NOT>(finished, Ou, row0 - C + 16 * rg, row_end, l, col0);
+      store_row_pieces<DV, NOT>(finished, Ou, row0 - C + 16 * rg, row_end, l, col0);
     __syncthreads();
 
     // ---- inter-chunk part: O^T += S^T Q^T (contraction over d_key = rows of Sl)
-    frag8 qf[Cfg::KS];  // q rows of this wave: column-side operand of every product
+    frag8 qf[Cfg::KSK];  // q rows of this wave: column-side operand of every product
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks)
-      qf[ks] = lds_row_frag(Qs + (16 * rg + r) * TP + 32 * ks + 8 * q4);
+    for (int ks = 0; ks < Cfg::KSK; ++ks)
+      qf[ks] = lds_row_frag(Qs + (16 * rg + r) * TPK + 32 * ks + 8 * q4);
     // oacc[nt][v] = O[query 16 rg + r][value col0 + 16 nt + 4 q4 + v] before the row factor
     f32x4 oacc[NOT];
 #pragma unroll
     for (int nt = 0; nt < NOT; ++nt) oacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < Cfg::KS; ++ks) {
+    for (int ks = 0; ks < Cfg::KSK; ++ks) {
       frag8 sf[NOT];
 #pragma unroll
       for (int nt = 0; nt < NOT; ++nt)
@@ -361,23 +372,23 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
       // k slot (q4, e) of the P fragment is token 32p + 16*(e/4) + 4*q4 + e%4; V and K are
       // read down their rows in the same order
       const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
-      frag8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KS];
+      frag8 vc[NOT], kcol[ST::NCT], vrow[ST::NRT], kr[2][Cfg::KSK];
 #pragma unroll
-      for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, TP, t0, t1, col0 + 16 * nt, r);
+      for (int nt = 0; nt < NOT; ++nt) vc[nt] = lds_col_frag(Vs, TPV, t0, t1, col0 + 16 * nt, r);
 #pragma unroll
       for (int x = 0; x < ST::NCT; ++x)
-        kcol[x] = lds_col_frag(Ks, TP, t0, t1, 16 * ST::col_tile(rg, cp, x), r);
+        kcol[x] = lds_col_frag(Ks, TPK, t0, t1, 16 * ST::col_tile(rg, cp, x), r);
       if (!ST::ROW_OPERAND_IS_OUTPUT_V) {
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
-          vrow[y] = lds_col_frag(Vs, TP, t0, t1, 16 * ST::row_tile(rg, cp, y), r);
+          vrow[y] = lds_col_frag(Vs, TPV, t0, t1, 16 * ST::row_tile(rg, cp, y), r);
       }
       if (diag_or_below) {
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks)
-            kr[half][ks] = lds_row_frag(Ks + (16 * (2 * p + half) + r) * TP + 32 * ks + 8 * q4);
+          for (int ks = 0; ks < Cfg::KSK; ++ks)
+            kr[half][ks] = lds_row_frag(Ks + (16 * (2 * p + half) + r) * TPK + 32 * ks + 8 * q4);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (diag_or_below) {
@@ -387,7 +398,7 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
           const int jt = 2 * p + half;
           f32x4 pacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ks = 0; ks < Cfg::KS; ++ks) pacc = mma16(kr[half][ks], qf[ks], pacc);
+          for (int ks = 0; ks < Cfg::KSK; ++ks) pacc = mma16(kr[half][ks], qf[ks], pacc);
           // pacc[v] = q_(16 rg + r) . k_(16jt + 4*q4 + v); keep key <= query
           float kept[4];
 #pragma unroll
@@ -416,30 +427,30 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<D, C>::template waves_per_eu<CS
     // through its part of the staging tile
     const float row_factor = scale * rq[16 * rg + r];
     wave_lds_sync();
-    gather_rows_transposed<D, NOT>(oacc, row_factor, stage, l, finished, col0);
+    gather_rows_transposed<DV, NOT>(oacc, row_factor, stage, l, finished, col0);
     __syncthreads();  // all reads of Ks, Vs, Sl done before the next chunk overwrites them
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<D, NOT>(finished, Ou, last + 16 * rg, row_end, l, col0);
+    store_row_pieces<DV, NOT>(finished, Ou, last + 16 * rg, row_end, l, col0);
   }
 
-  if (seq_len != nullptr) zero_rows_e16<D>(Ou, row_end, seg_end);  // rows that do not exist
+  if (seq_len != nullptr) zero_rows_e16<DV>(Ou, row_end, seg_end);  // rows that do not exist
 
   if (state_out != nullptr && g == G - 1 && ST::active(rg, cp)) {
-    float* out = state_out + size_t(unit) * D * D;
+    float* out = state_out + size_t(unit) * DK * DV;
 #pragma unroll
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-        *reinterpret_cast<f32x4*>(out + (16 * ST::col_tile(rg, cp, x) + r) * D +
+        *reinterpret_cast<f32x4*>(out + (16 * ST::col_tile(rg, cp, x) + r) * DV +
                                   16 * ST::row_tile(rg, cp, y) + 4 * q4) = sacc[x][y];
   }
 }
 
-template <int D, int C>
+template <int DK, int DV, int C>
 hipError_t run_fwd_causal(const CausalArgs& a) {
-  using Cfg = FwdCfg<D, C>;
+  using Cfg = FwdCfg<DK, DV, C>;
   const int units = a.B * a.H;
   const e16_t* Q = static_cast<const e16_t*>(a.Q);
   const e16_t* K = static_cast<const e16_t*>(a.K);
@@ -453,17 +464,17 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
     err = COTTN_SYM(launch_fwd_segment_totals)(a, ws);
     if (err != hipSuccess) return err;
     if (!sum_in_scan) {
-      err = launch_fwd_state_carry(ws, units, a.G, D * D, a.stream);
+      err = launch_fwd_state_carry(ws, units, a.G, DK * DV, a.stream);
       if (err != hipSuccess) return err;
     }
   }
-  constexpr int CS = FwdSplit<D, C>::CS;
+  constexpr int CS = FwdSplit<DK, DV, C>::CS;
   // Q rows are read once here.  When the call's four tensors exceed the 256 MB last-level cache
   // nothing of them survives until a backward call either, and loading them non-temporally
   // keeps the K, V rows the totals kernel left in the L2 in place (long context: scan 98 ->
   // 87 us); below that size a backward that follows finds the rows cached, and plain loads win.
-  const bool stream_q = 4.0 * units * double(a.N) * D * sizeof(e16_t) > 256.0 * 1024 * 1024;
-  return launch_kernel(COTTN_SYM_STR(fwd_causal_scan), COTTN_SYM(fwd_causal_scan)<D, C, CS>, dim3(units * a.G),
+  const bool stream_q = 2.0 * units * double(a.N) * (DK + DV) * sizeof(e16_t) > 256.0 * 1024 * 1024;
+  return launch_kernel(COTTN_SYM_STR(fwd_causal_scan), COTTN_SYM(fwd_causal_scan)<DK, DV, C, CS>, dim3(units * a.G),
                        dim3(Cfg::NT * CS), 0, a.stream, Q, K, V, a.s, static_cast<e16_t*>(a.O), a.state,
                        a.G > 1 ? ws : nullptr, a.state_in, a.H, a.N, a.G, a.seg_rows, inv_eps,
                        sum_in_scan ? 1 : 0, a.seq_len, a.s_per_unit, stream_q ? 1 : 0);
@@ -471,7 +482,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 
 }  // namespace
 
-template <int D>
+template <int DK, int DV>
 static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   const e16_t* X = static_cast<const e16_t*>(t.X);
   const e16_t* Y = static_cast<const e16_t*>(t.Y);
@@ -482,19 +493,25 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   // operand-tile pitch would leave room for one: measured 0.6 us slower on the GPT shape).
   const dim3 grid(t.units * t.G);
   if (t.seg_rows >= 128)
-    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, 128>, grid, dim3(512),
+    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 128>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
                          t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
-  return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<D, 64>, grid, dim3(256), 0,
+  return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 64>, grid, dim3(256), 0,
                        t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
                        t.dot_slots, t.dot_out, t.seq_len, t.H);
 }
 
 hipError_t COTTN_SYM(launch_segment_totals)(const SegmentTotalsArgs& t) {
-  switch (t.d) {
-    case 32: return run_segment_totals<32>(t);
-    case 64: return run_segment_totals<64>(t);
-    case 128: return run_segment_totals<128>(t);
+  switch (t.dk * 1000 + t.dv) {
+    case 32032: return run_segment_totals<32, 32>(t);
+    case 32064: return run_segment_totals<32, 64>(t);
+    case 32128: return run_segment_totals<32, 128>(t);
+    case 64032: return run_segment_totals<64, 32>(t);
+    case 64064: return run_segment_totals<64, 64>(t);
+    case 64128: return run_segment_totals<64, 128>(t);
+    case 128032: return run_segment_totals<128, 32>(t);
+    case 128064: return run_segment_totals<128, 64>(t);
+    case 128128: return run_segment_totals<128, 128>(t);
     default: return hipErrorInvalidValue;
   }
 }
@@ -502,7 +519,7 @@ hipError_t COTTN_SYM(launch_segment_totals)(const SegmentTotalsArgs& t) {
 hipError_t COTTN_SYM(launch_fwd_segment_totals)(const CausalArgs& a, float* dst) {
   SegmentTotalsArgs t{};
   t.X = a.K; t.Y = a.V; t.dst = dst;
-  t.units = a.B * a.H; t.N = a.N; t.d = a.d; t.G = a.G; t.n_compute = a.G - 1;
+  t.units = a.B * a.H; t.N = a.N; t.dk = a.dk; t.dv = a.dv; t.G = a.G; t.n_compute = a.G - 1;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
   t.seq_len = a.seq_len; t.H = a.H;
   return COTTN_SYM(launch_segment_totals)(t);
@@ -517,14 +534,21 @@ hipError_t launch_fwd_state_carry(float* seg_state, int units, int G, int elems,
 #endif
 
 hipError_t COTTN_SYM(fwd_causal)(const CausalArgs& a) {
-  switch (a.d * 1000 + a.C) {
-    case 32064: return run_fwd_causal<32, 64>(a);
-    case 32128: return run_fwd_causal<32, 128>(a);
-    case 32256: return run_fwd_causal<32, 256>(a);
-    case 64064: return run_fwd_causal<64, 64>(a);
-    case 64128: return run_fwd_causal<64, 128>(a);
-    case 64256: return run_fwd_causal<64, 256>(a);
-    case 128064: return run_fwd_causal<128, 64>(a);
+  // d_key != d_value: chunks of 64 rows
+  switch ((a.dk * 1000 + a.dv) * 1000 + a.C) {
+    case 32032064: return run_fwd_causal<32, 32, 64>(a);
+    case 32032128: return run_fwd_causal<32, 32, 128>(a);
+    case 32032256: return run_fwd_causal<32, 32, 256>(a);
+    case 64064064: return run_fwd_causal<64, 64, 64>(a);
+    case 64064128: return run_fwd_causal<64, 64, 128>(a);
+    case 64064256: return run_fwd_causal<64, 64, 256>(a);
+    case 128128064: return run_fwd_causal<128, 128, 64>(a);
+    case 32064064: return run_fwd_causal<32, 64, 64>(a);
+    case 32128064: return run_fwd_causal<32, 128, 64>(a);
+    case 64032064: return run_fwd_causal<64, 32, 64>(a);
+    case 64128064: return run_fwd_causal<64, 128, 64>(a);
+    case 128032064: return run_fwd_causal<128, 32, 64>(a);
+    case 128064064: return run_fwd_causal<128, 64, 64>(a);
     default: return hipErrorInvalidValue;
   }
 }

@@ -28,7 +28,9 @@ struct CausalArgs {
   // its workspace (then the backward does not recompute them)
   const float* saved_fwd_states;
   void* workspace;
-  int B, H, N, d, C, G, seg_rows;
+  // dk, dv: head dimensions of queries / keys and of values / outputs (Sec. 2.1: d_H_key,
+  // d_H_value); Q, K, dQ, dK are [B][H][N][dk], V, O, dO, dV [B][H][N][dv], states [dk][dv]
+  int B, H, N, dk, dv, C, G, seg_rows;
   float eps;
   hipStream_t stream;
 };
@@ -41,7 +43,7 @@ constexpr int kMaxSegmentsSummedInScan = 4;
 
 struct StepArgs {
   const void* q; const void* k; const void* v; const float* s; float* state; void* o;
-  int B, H, d;
+  int B, H, dk, dv;  // q, k are [B][H][dk]; v, o [B][H][dv]; state [B][H][dk][dv]
   float eps;
   hipStream_t stream;
 };
@@ -71,13 +73,13 @@ hipError_t launch_bwd_state_carry(float* fwd_tot, float* rev_tot, int units, int
 hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
 hipError_t launch_fwd_segment_totals_f16(const CausalArgs& a, float* dst);
 
-// The same kernel in general: dst[unit][g] = sum over the rows of segment g of N(X)^T Y for
-// g < n_compute (G slots per unit).  With dot_with (stored totals of another d x d matrix,
+// The same kernel in general: dst[unit][g] = sum over the rows of segment g of N(X)^T Y
+// (dk x dv) for g < n_compute (G slots per unit).  With dot_with (stored totals of another d x d matrix,
 // dot_slots slots per unit, added up by the kernel) it also writes
 // dot_out[unit][g] = <dst[unit][g], that matrix>.
 struct SegmentTotalsArgs {
   const void* X; const void* Y; float* dst;
-  int units, N, d, G, n_compute, seg_rows;
+  int units, N, dk, dv, G, n_compute, seg_rows;  // X rows are dk wide, Y rows dv wide
   float eps;
   const float* dot_with; int dot_slots; float* dot_out;
   const int* seq_len; int H;  // padded batches: rows at or beyond seq_len[unit / H] do not exist

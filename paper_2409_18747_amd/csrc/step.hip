@@ -1,5 +1,6 @@
-// One recurrent decode step (Sec. 5, eq. hidden_state_obs) for B*H independent d x d fp32
-// states:  S <- S + kh^T v (in place), then o = s_h * qh S with the updated state.
+// One recurrent decode step (Sec. 5, eq. hidden_state_obs) for B*H independent fp32 states of
+// d_key x d_value (DK x DV; q and k are DK wide, v and o DV wide):
+// S <- S + kh^T v (in place), then o = s_h * qh S with the updated state.
 //
 // The kernel is a pure stream of the state through the chip (read + write of every state
 // byte per step); all arithmetic is fp32 FMAs on the vector ALU.  One workgroup owns one
@@ -44,20 +45,22 @@ __device__ __forceinline__ void store_state_row(float* p, float4 x) {
   __builtin_nontemporal_store(f32x4{x.x, x.y, x.z, x.w}, reinterpret_cast<f32x4*>(p));
 }
 
-template <typename T, int D>
+template <typename T, int DK, int DV>
 __global__ __launch_bounds__(256) void decode_step_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
     const float* __restrict__ s, float* __restrict__ state, T* __restrict__ o, int H, float eps,
     int stream_state) {
-  constexpr int TPR = D / 4;          // threads per state row
+  constexpr int TPR = DV / 4;         // threads per state row
   constexpr int RPP = 256 / TPR;      // rows per pass
-  constexpr int PASSES = D / RPP;
-  __shared__ float qh[D], kh[D];
-  __shared__ float partial[RPP][D];
+  constexpr int PASSES = (DK + RPP - 1) / RPP;
+  constexpr int D = DK;               // width of q and k
+  __shared__ float qh[DK], kh[DK];
+  __shared__ float partial[RPP][DV];
 
   const int unit = blockIdx.x;
   const int tid = threadIdx.x;
-  const size_t vbase = size_t(unit) * D;
+  const size_t vbase = size_t(unit) * DK;   // of q, k
+  const size_t obase = size_t(unit) * DV;   // of v, o
 
   // every wave normalises q and k for itself (d <= 128: at most two elements per lane);
   // wave 0 publishes them
@@ -87,38 +90,44 @@ __global__ __launch_bounds__(256) void decode_step_kernel(
   }
   const int col = (tid % TPR) * 4;
   const int row_in_pass = tid / TPR;
-  const float4 v4 = Elem<T>::load4(v + vbase + col);
-  float* Su = state + size_t(unit) * D * D;
+  const float4 v4 = Elem<T>::load4(v + obase + col);
+  float* Su = state + size_t(unit) * DK * DV;
 
+  // (a pass may reach beyond the last key row when DK < 256 / (DV/4): those threads idle)
   float4 rows[PASSES];
 #pragma unroll
-  for (int p = 0; p < PASSES; ++p)
-    rows[p] = load_state_row(Su + size_t(p * RPP + row_in_pass) * D + col, stream_state != 0);
+  for (int p = 0; p < PASSES; ++p) {
+    const int row = p * RPP + row_in_pass;
+    rows[p] = float4{0.f, 0.f, 0.f, 0.f};
+    if (DK % RPP == 0 || row < DK) rows[p] = load_state_row(Su + size_t(row) * DV + col, stream_state != 0);
+  }
   __syncthreads();
 
   float4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int p = 0; p < PASSES; ++p) {
     const int row = p * RPP + row_in_pass;
-    const float kr = kh[row], qr = qh[row];
-    float4 x = rows[p];
-    x.x += kr * v4.x;
-    x.y += kr * v4.y;
-    x.z += kr * v4.z;
-    x.w += kr * v4.w;
-    store_state_row(Su + size_t(row) * D + col, x);
-    acc.x += qr * x.x;
-    acc.y += qr * x.y;
-    acc.z += qr * x.z;
-    acc.w += qr * x.w;
+    if (DK % RPP == 0 || row < DK) {
+      const float kr = kh[row], qr = qh[row];
+      float4 x = rows[p];
+      x.x += kr * v4.x;
+      x.y += kr * v4.y;
+      x.z += kr * v4.z;
+      x.w += kr * v4.w;
+      store_state_row(Su + size_t(row) * DV + col, x);
+      acc.x += qr * x.x;
+      acc.y += qr * x.y;
+      acc.z += qr * x.z;
+      acc.w += qr * x.w;
+    }
   }
   *reinterpret_cast<float4*>(&partial[row_in_pass][col]) = acc;
   __syncthreads();
-  if (tid < D) {
+  if (tid < DV) {
     float sum = 0.f;
 #pragma unroll
     for (int rpp = 0; rpp < RPP; ++rpp) sum += partial[rpp][tid];
-    Elem<T>::store(o + vbase + tid, s[unit % H] * sum);
+    Elem<T>::store(o + obase + tid, s[unit % H] * sum);
   }
 }
 
@@ -130,20 +139,19 @@ hipError_t run_step(const StepArgs& a) {
   const T* v = static_cast<const T*>(a.v);
   T* o = static_cast<T*>(a.o);
   const dim3 grid(units), block(256);
-  const int stream_state = double(units) * a.d * a.d * sizeof(float) > 32.0 * 1024 * 1024 ? 1 : 0;
-  switch (a.d) {
-    case 32:
-      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 32>, grid, block, 0, a.stream,
-                           q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
-    case 64:
-      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 64>, grid, block, 0, a.stream,
-                           q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
-    case 128:
-      return launch_kernel("decode_step_kernel", decode_step_kernel<T, 128>, grid, block, 0,
-                           a.stream, q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
+  const int stream_state = double(units) * a.dk * a.dv * sizeof(float) > 32.0 * 1024 * 1024 ? 1 : 0;
+#define COTTN_STEP_CASE(DK, DV)                                                                   \
+  case DK * 1000 + DV:                                                                            \
+    return launch_kernel("decode_step_kernel", decode_step_kernel<T, DK, DV>, grid, block, 0,     \
+                         a.stream, q, k, v, a.s, a.state, o, a.H, a.eps, stream_state);
+  switch (a.dk * 1000 + a.dv) {
+    COTTN_STEP_CASE(32, 32) COTTN_STEP_CASE(32, 64) COTTN_STEP_CASE(32, 128)
+    COTTN_STEP_CASE(64, 32) COTTN_STEP_CASE(64, 64) COTTN_STEP_CASE(64, 128)
+    COTTN_STEP_CASE(128, 32) COTTN_STEP_CASE(128, 64) COTTN_STEP_CASE(128, 128)
     default:
       return hipErrorInvalidValue;
   }
+#undef COTTN_STEP_CASE
 }
 
 }  // namespace

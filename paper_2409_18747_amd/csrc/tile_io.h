@@ -120,34 +120,37 @@ struct TileStage {
   }
 };
 
-// Which 16x16 tiles of a D x D fp32 accumulator matrix a wave owns, for a workgroup of NW
-// waves.  The matrix is cut into (D/16)^2 tiles indexed (row tile, column tile).  A wave
-// keeps one or more whole tile columns when there are fewer waves than columns (so the
+// Which 16x16 tiles of a DR x DC fp32 accumulator matrix a wave owns, for a workgroup of NW
+// waves.  The matrix is cut into (DR/16) x (DC/16) tiles indexed (row tile, column tile).  A
+// wave keeps one or more whole tile columns when there are fewer waves than columns (so the
 // column-side operand is loaded once per wave); otherwise the waves that share a tile column
-// split its row tiles.
-template <int D, int NW>
+// split its row tiles.  (The state K^T V is d_key x d_value; which of the two is the row side
+// depends on the kernel's accumulator orientation.)
+template <int DR, int DC, int NW>
 struct AccTiles {
-  static constexpr int DT = D / 16;
-  static constexpr int NCT = (NW >= DT) ? 1 : DT / NW;      // column tiles per wave
-  static constexpr int WPC = (NW >= DT) ? NW / DT : 1;      // waves per tile column
-  static constexpr int NRT = (WPC >= DT) ? 1 : DT / WPC;    // row tiles per wave
+  static constexpr int RT = DR / 16, CT = DC / 16;
+  static constexpr int NCT = (NW >= CT) ? 1 : CT / NW;      // column tiles per wave
+  static constexpr int WPC = (NW >= CT) ? NW / CT : 1;      // waves per tile column
+  static constexpr int NRT = (WPC >= RT) ? 1 : RT / WPC;    // row tiles per wave
   // stored states a wave loads at once when it seeds its accumulators (register budget)
   static constexpr int STATE_BATCH = NCT * NRT <= 4 ? 3 : NCT * NRT <= 8 ? 2 : 1;
-  __device__ static __forceinline__ bool active(int w) { return (w / DT) * NRT < DT; }
-  __device__ static __forceinline__ int col_tile(int w, int x) { return (w % DT) + x * NW; }
+  __device__ static __forceinline__ bool active(int w) { return (w / CT) * NRT < RT; }
+  __device__ static __forceinline__ int col_tile(int w, int x) { return (w % CT) + x * NW; }
   __device__ static __forceinline__ int row_tile(int w, int y) {
-    return (NW >= DT) ? (w / DT) * NRT + y : y;
+    return (NW >= CT) ? (w / CT) * NRT + y : y;
   }
 };
 
 // The same ownership when the C/16 row groups of a chunk are each served by CS waves that
 // split the result columns between them (wave = (row group rg, column part cp)).  CS = 1 is
-// AccTiles over the row groups.  CS > 1: a wave owns the key tiles rg, rg + RG, ... and the
-// value tiles of its own column part, which are the tiles whose V fragments it reads anyway.
-template <int D, int RG, int CS>
+// AccTiles over the row groups.  CS > 1 (square matrices only): a wave owns the key tiles rg,
+// rg + RG, ... and the value tiles of its own column part, which are the tiles whose V
+// fragments it reads anyway.
+template <int DR, int DC, int RG, int CS>
 struct SplitTiles {
-  using One = AccTiles<D, RG>;
-  static constexpr int DT = D / 16;
+  using One = AccTiles<DR, DC, RG>;
+  static_assert(CS == 1 || DR == DC, "column parts are implemented for square matrices");
+  static constexpr int DT = DC / 16;
   static constexpr int NCT = CS == 1 ? One::NCT : (RG >= DT ? 1 : DT / RG);
   static constexpr int NRT = CS == 1 ? One::NRT : DT / CS;
   // whether the row-side operand of the state update is among the V fragments of the wave's

@@ -12,34 +12,34 @@ struct SeqPlan {
   int seg_rows;
 };
 
-bool make_plan(int op, int B, int H, int N, int d, int chunk, int dtype, SeqPlan* plan);
+bool make_plan(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype, SeqPlan* plan);
 
 inline size_t round_up_256(size_t x) { return (x + 255) & ~size_t(255); }
 
-// Workspace layouts (all fp32):
-//   causal forward   G > 1: [units][G][d][d]   segment totals, turned in place into the state
-//                            at each segment start
+// Workspace layouts (all fp32; a state is dk x dv, [d_key][d_value]):
+//   causal forward   G > 1: [units][G][dk][dv]   segment totals, turned in place into the
+//                            state at each segment start
 //   causal backward  G > 1: the same array for the forward-time states, a second one for
 //                            the reverse-time states; always: [units][G] partial sums of ds
-//   bidirectional forward : [units][G][d][d]   segment totals, slot 0 becomes the full state
-//   bidirectional backward: [units][G][2][d][d] totals of Kh^T V and Qh^T dO, slot 0 becomes
-//                            the full pair when the combine kernel runs; per unit max(G,
-//                            d*d/256) partial sums of ds (the totals kernel leaves G, the
-//                            combine kernel d*d/256)
-inline size_t state_array_bytes(int B, int H, int d, int G) {
-  return round_up_256(size_t(B) * H * G * d * d * sizeof(float));
+//   bidirectional forward : [units][G][dk][dv]   segment totals, slot 0 becomes the full state
+//   bidirectional backward: two arrays [units][G][dk][dv], totals of Kh^T V and of Qh^T dO,
+//                            slot 0 becomes the full matrix when the combine kernel runs; per
+//                            unit max(G, dk*dv/256) partial sums of ds (the totals kernel
+//                            leaves G, the combine kernel dk*dv/256)
+inline size_t state_array_bytes(int B, int H, int dk, int dv, int G) {
+  return round_up_256(size_t(B) * H * G * dk * dv * sizeof(float));
 }
 inline size_t ds_partials_bytes(int B, int H, int G) {
   return round_up_256(size_t(B) * H * G * sizeof(float));
 }
 
-inline size_t workspace_bytes_for(int op, int B, int H, int d, const SeqPlan& p) {
+inline size_t workspace_bytes_for(int op, int B, int H, int dk, int dv, const SeqPlan& p) {
   switch (op) {
-    case 0: return p.G > 1 ? state_array_bytes(B, H, d, p.G) : 0;
-    case 1: return (p.G > 1 ? 2 * state_array_bytes(B, H, d, p.G) : 0) + ds_partials_bytes(B, H, p.G);
-    case 2: return state_array_bytes(B, H, d, p.G);
-    case 3: return 2 * state_array_bytes(B, H, d, p.G) +
-                   ds_partials_bytes(B, H, p.G > d * d / 256 ? p.G : d * d / 256);
+    case 0: return p.G > 1 ? state_array_bytes(B, H, dk, dv, p.G) : 0;
+    case 1: return (p.G > 1 ? 2 * state_array_bytes(B, H, dk, dv, p.G) : 0) + ds_partials_bytes(B, H, p.G);
+    case 2: return state_array_bytes(B, H, dk, dv, p.G);
+    case 3: return 2 * state_array_bytes(B, H, dk, dv, p.G) +
+                   ds_partials_bytes(B, H, p.G > dk * dv / 256 ? p.G : dk * dv / 256);
     default: return 0;
   }
 }

@@ -78,8 +78,10 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
 
 
-def draw(B, H, N, d, dtype="f32", seed=0, value_scale=1.0, with_dO=True):
+def draw(B, H, N, d, dtype="f32", seed=0, value_scale=1.0, with_dO=True, d_value=None):
     """Q, K, V (and dO) ~ value_scale * N(0, 1) of shape [B, H, N, d], s ~ U(0.5, 1.5) of shape [H].
+    With d_value, V and dO are [B, H, N, d_value] (the paper's separate head dimension of the
+    values, Sec. 2.1).
 
     Values are float32 arrays already rounded to ``dtype``, so converting them to that
     dtype anywhere is exact.  Returns a dict with keys Q, K, V, dO (optional), s.
@@ -87,7 +89,8 @@ def draw(B, H, N, d, dtype="f32", seed=0, value_scale=1.0, with_dO=True):
     rng = np.random.Generator(np.random.Philox(seed))
     out = {}
     for name in ("Q", "K", "V", "dO"):
-        x = rng.standard_normal((B, H, N, d), dtype=np.float32)
+        width = d if (d_value is None or name in ("Q", "K")) else d_value
+        x = rng.standard_normal((B, H, N, width), dtype=np.float32)
         if value_scale != 1.0:
             x = x * np.float32(value_scale)
         if name == "dO" and not with_dO:

@@ -34,6 +34,12 @@ def lib():
     l.cottn_bwd_bidir_varlen.argtypes = [vp] * 11 + [sz, vp, sz, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m_varlen.argtypes = [vp, vp, vp, i, i, vp]
     l.cottn_fwd_causal_static.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, vp]
+    l.cottn_workspace_bytes_dkdv.restype = ctypes.c_size_t
+    l.cottn_workspace_bytes_dkdv.argtypes = [ctypes.c_int] * 8
+    l.cottn_segments_dkdv.argtypes = [ctypes.c_int] * 8
+    l.cottn_fwd_causal_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, i, f, vp]
+    l.cottn_bwd_bidir_dkdv.argtypes = [vp] * 10 + [sz, vp, sz, i, i, i, i, i, i, f, vp]
+    l.cottn_step_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, f, vp]
     l.cottn_scale_from_m.argtypes = [vp, vp, i, f, vp]
     l.cottn_scale_backward.argtypes = [vp, vp, vp, i, f, vp]
     yield l
@@ -216,3 +222,34 @@ def test_static_workspace_forward_rejects_on_the_host(lib):
     lib.cottn_tune_segments(0)
     # the benchmarked shape fits
     assert 0 < lib.cottn_workspace_bytes(0, 8, 12, 1024, 64, 0, BF16) <= limit
+
+
+def test_rectangular_head_dimensions_on_the_host(lib):
+    """d_key != d_value (Sec. 2.1): workspace sizes follow dk * dv, the one-dimension calls are
+    the dk = dv case, and unsupported combinations are refused before any launch."""
+    E_NULL, E_SHAPE, E_WS = 1, 2, 5
+    lib.cottn_tune_segments(4)
+    wb = lib.cottn_workspace_bytes_dkdv
+    assert wb(0, 8, 12, 1024, 64, 64, 0, BF16) == lib.cottn_workspace_bytes(0, 8, 12, 1024, 64, 0, BF16)
+    assert wb(0, 8, 12, 1024, 32, 128, 0, BF16) == 8 * 12 * 4 * 32 * 128 * 4
+    assert wb(1, 8, 12, 1024, 128, 64, 0, BF16) == 2 * 8 * 12 * 4 * 128 * 64 * 4 + 1536
+    assert wb(3, 2, 2, 512, 64, 32, 0, BF16) == 2 * 2 * 2 * 4 * 64 * 32 * 4 + 256   # ds partials: max(G, dk*dv/256) = 8 per unit
+    assert lib.cottn_segments_dkdv(0, 8, 12, 1024, 64, 128, 0, BF16) == 4
+    lib.cottn_tune_segments(0)
+    assert wb(4, 256, 16, 1, 32, 128, 0, BF16) == 0             # decode needs none
+    assert wb(0, 1, 1, 8, 64, 128, 128, BF16) == NOSIZE          # rectangular: chunk 64 only
+    assert wb(0, 1, 1, 8, 64, 96, 0, BF16) == NOSIZE             # unsupported d_value
+    assert wb(0, 1, 1, 8, 64, 32, 0, F32) == NOSIZE              # fp32 kernels are square
+    buf = ctypes.create_string_buffer(1 << 16)
+    base = (ctypes.addressof(buf) + 255) & ~255
+    p = lambda: ctypes.c_void_p(base)
+    eps = 1e-6
+    f = lib.cottn_fwd_causal_dkdv
+    assert f(p(), p(), None, p(), p(), None, None, 0, 1, 1, 8, 32, 64, 0, BF16, eps, None) == E_NULL
+    assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 48, 0, BF16, eps, None) == E_SHAPE
+    assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 64, 128, BF16, eps, None) == E_SHAPE
+    assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 64, 0, F32, eps, None) == E_SHAPE
+    assert lib.cottn_bwd_bidir_dkdv(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 16,
+                                    1, 1, 8, 64, 128, BF16, eps, None) == E_WS
+    assert lib.cottn_step_dkdv(p(), p(), p(), p(), p(), p(), 1, 1, 64, 100, BF16, eps, None) == E_SHAPE
+    assert lib.cottn_step_dkdv(p(), p(), p(), p(), None, p(), 1, 1, 64, 128, BF16, eps, None) == E_NULL

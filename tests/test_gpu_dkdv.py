@@ -1,0 +1,112 @@
+"""GPU parity: different head dimensions for keys and values (Sec. 2.1: d_H_key, d_H_value) —
+the *_dkdv entry points through the C ABI against the CPU oracle, for the causal and the
+bidirectional forward + backward and the decode step."""
+import numpy as np
+import pytest
+
+from helpers import TOL, ds_errors, ds_terms_rss, rel_err, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(32, 64), (64, 128), (128, 64), (64, 32), (32, 128), (128, 32)]
+
+
+@pytest.fixture(scope="module")
+def cottn():
+    import paper_2409_18747_amd.binding as b
+    yield b
+    b.cottn_tune_segments(0)
+
+
+def run(cottn, oracle, causal, B, H, N, dk, dv, dtype, seed, segments=0, saved=False):
+    import torch
+    from paper_2409_18747_amd import workloads
+    x = workloads.draw(B, H, N, dk, dtype, seed, d_value=dv)
+    Q, K, V, dO = (to_device(x[k], dtype) for k in ("Q", "K", "V", "dO"))
+    s = to_device(x["s"], "f32")
+    code = {"bf16": cottn.COTTN_BF16, "f16": cottn.COTTN_F16}[dtype]
+    cottn.cottn_tune_segments(segments)
+    fwd = cottn.cottn_fwd_causal_dkdv if causal else cottn.cottn_fwd_bidir_dkdv
+    bwd = cottn.cottn_bwd_causal_dkdv if causal else cottn.cottn_bwd_bidir_dkdv
+    op = cottn.OP_FWD_CAUSAL if causal else cottn.OP_FWD_BIDIR
+    fwd_ws = None
+    if saved:
+        need = cottn.cottn_workspace_bytes_dkdv(op, B, H, N, dk, dv, 0, code)
+        fwd_ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    nan_like = lambda t: torch.full_like(t, float("nan"))
+    O, dQ, dK, dV = nan_like(V), nan_like(Q), nan_like(Q), nan_like(V)
+    state = torch.full((B, H, dk, dv), float("nan"), dtype=torch.float32, device="cuda")
+    fwd(Q, K, V, s, O=O, state=state, workspace=fwd_ws)
+    _, _, _, ds = bwd(Q, K, V, s, dO, dQ=dQ, dK=dK, dV=dV, fwd_workspace=fwd_ws)
+    torch.cuda.synchronize()
+    O_ref = oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"], causal=causal)
+    S_ref = oracle.state_total(x["K"], x["V"])
+    g_ref = oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], causal=causal)
+    errs = {"O": rel_err(to_host(O), O_ref), "state": rel_err(to_host(state), S_ref)}
+    for name, got, want in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g_ref):
+        errs[name] = rel_err(to_host(got), want)
+    dse = ds_errors(to_host(ds), g_ref[3], ds_terms_rss(oracle, x, causal))
+    errs["ds"] = dse["ds"]
+    print("dkdv %s %s B%d H%d N%d dk%d dv%d seg%d saved%d: %s ds_plain %.2e" %
+          ("causal" if causal else "bidir", dtype, B, H, N, dk, dv, segments, saved,
+           {k: "%.2e" % v for k, v in errs.items()}, dse["ds_plain"]), flush=True)
+    for name, e in errs.items():
+        assert e <= TOL[dtype], (name, e)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("dk,dv", SHAPES)
+def test_bf16_shapes(cottn, oracle, causal, dk, dv):
+    """Several chunks, a ragged tail, several segments."""
+    run(cottn, oracle, causal, 2, 3, 333, dk, dv, "bf16", seed=500 + dk + dv, segments=3)
+
+
+@pytest.mark.parametrize("dk,dv", [(32, 64), (64, 128), (128, 64)])
+@pytest.mark.parametrize("N,segments", [(1, 1), (63, 1), (65, 2), (700, 7), (517, 0)])
+def test_bf16_lengths_and_splits(cottn, oracle, dk, dv, N, segments):
+    run(cottn, oracle, True, 1, 2, N, dk, dv, "bf16", seed=N + dk, segments=segments, saved=N % 2 == 1)
+
+
+@pytest.mark.parametrize("dk,dv", [(32, 64), (64, 128), (128, 64)])
+def test_f16_and_saved_states(cottn, oracle, dk, dv):
+    run(cottn, oracle, True, 2, 2, 300, dk, dv, "f16", seed=9, segments=4, saved=True)
+    run(cottn, oracle, False, 2, 2, 300, dk, dv, "f16", seed=10, segments=2, saved=True)
+
+
+@pytest.mark.parametrize("dk,dv", [(64, 128), (128, 64)])
+def test_bf16_training_shape(cottn, oracle, dk, dv):
+    """A GPT-shaped call (default split) with d_key != d_value."""
+    run(cottn, oracle, True, 2, 12, 1024, dk, dv, "bf16", seed=77)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("dk,dv", SHAPES)
+def test_step_continues_prefill(cottn, oracle, dk, dv, dtype):
+    """Prefill writes a d_key x d_value state; single-token steps continue it (Sec. 5)."""
+    import torch
+    from paper_2409_18747_amd import workloads
+    B, H, N, T = 2, 3, 70, 5
+    pre = "bf16" if dtype == "f32" else dtype   # the rectangular prefill exists for the 16-bit types
+    x = workloads.draw(B, H, N + T, dk, pre, 40 + dk + dv, d_value=dv)
+    s = to_device(x["s"], "f32")
+    state = torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda")
+    cottn.cottn_tune_segments(0)
+    cottn.cottn_fwd_causal_dkdv(*(to_device(x[k][:, :, :N], pre) for k in ("Q", "K", "V")), s, state=state)
+    O_ref, _ = oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"])
+    worst = 0.0
+    for t in range(N, N + T):
+        q, k, v = (to_device(x[n][:, :, t], dtype) for n in ("Q", "K", "V"))
+        o = cottn.cottn_step_dkdv(q, k, v, s, state)
+        torch.cuda.synchronize()
+        worst = max(worst, float(np.abs(to_host(o) - O_ref[:, :, t]).max() / np.abs(O_ref).max()))
+    print("step dkdv %s dk%d dv%d: %.2e" % (dtype, dk, dv, worst), flush=True)
+    assert worst <= TOL["bf16" if dtype == "f32" else dtype]   # the prefill state is a 16-bit path result
+
+
+def test_rectangular_fp32_is_refused(cottn):
+    import torch
+    Q = torch.zeros(1, 1, 8, 32, device="cuda")
+    V = torch.zeros(1, 1, 8, 64, device="cuda")
+    with pytest.raises(cottn.CottnError) as e:
+        cottn.cottn_fwd_causal_dkdv(Q, Q, V, torch.ones(1, device="cuda"))
+    assert e.value.status == 2   # COTTN_E_SHAPE

@@ -23,8 +23,13 @@ def rand_inputs(seed, B, H, N, d, with_s=True):
 
 
 # ---------------------------------------------------------------- worked example
-def test_worked_example(oracle):
-    g = json.load(open(os.path.join(GOLDEN, "worked_example_n3_d2.json")))
+@pytest.mark.parametrize("name", ["worked_example_n3_d2.json", "worked_example_n3_dk2_dv3.json"])
+def test_worked_example(oracle, name):
+    check_worked_example(oracle, name)
+
+
+def check_worked_example(oracle, name="worked_example_n3_d2.json"):
+    g = json.load(open(os.path.join(GOLDEN, name)))
     A = lambda k: np.array(g[k], dtype=np.float64)[None, None]
     Q, K, V, dO, s = A("Q"), A("K"), A("V"), A("dO"), np.array(g["s"])
     tol = dict(rtol=0, atol=1e-12)
@@ -482,7 +487,16 @@ class _Mistaken:
             return O - np.asarray(s).reshape(1, -1, 1, 1) * diag * V
         if kind == "sign":
             return -O
+        if kind == "value_columns_rotated":   # a wrong column stride on the value side
+            return np.roll(O, 1, axis=-1)
         return O
+
+    def fwd_recurrent(self, Q, K, V, s, eps=1e-6, S0=None):
+        O, S = self._o.fwd_recurrent(Q, K, V, s, eps=eps, S0=S0)
+        if self._kind == "state_keys_truncated":  # state accumulated over d_value x d_value
+            S = S.copy()
+            S[:, :, -1, :] = 0.0
+        return O, S
 
     def bwd_quadratic(self, Q, K, V, s, dO, eps=1e-6, causal=True):
         dQ, dK, dV, ds = self._o.bwd_quadratic(Q, K, V, s, dO, eps=eps, causal=causal)
@@ -496,6 +510,10 @@ class _Mistaken:
             return dQ, dK, dV / np.asarray(s).reshape(1, -1, 1, 1), ds
         if kind == "ds_per_batch_only":    # summed over one batch entry instead of all
             return dQ, dK, dV, ds * 0.5
+        if kind == "dv_over_key_width":    # dV filled over d_key columns only
+            dV = dV.copy()
+            dV[..., Q.shape[-1]:] = 0.0
+            return dQ, dK, dV, ds
         return dQ, dK, dV, ds
 
 
@@ -507,11 +525,117 @@ class _Mistaken:
     ("dv_unscaled", "differences"), ("ds_per_batch_only", "differences"),
     ("projection_dropped", "identities"), ("dq_dk_exchanged", "worked")])
 def test_pins_reject_planted_mistakes(oracle, kind, pin):
-    pins = {"worked": lambda o: test_worked_example(o),
+    pins = {"worked": lambda o: check_worked_example(o),
             "closed_form": lambda o: test_orthonormal_keys_select_query_components(o),
             "mask": lambda o: test_mask_includes_diagonal_and_is_causal(o),
             "differences": lambda o: test_gradients_by_central_differences(o, True),
             "identities": lambda o: test_gradient_identities(o, True)}
     pins[pin](oracle)  # the pin passes on the oracle itself
+    with pytest.raises(AssertionError):
+        pins[pin](_Mistaken(oracle, kind))
+
+
+# ---------------------------------------------------------------- d_key != d_value (Sec. 2.1)
+def rand_inputs_dkdv(seed, B, H, N, dk, dv):
+    r = np.random.default_rng(seed)
+    Q, K = r.standard_normal((B, H, N, dk)), r.standard_normal((B, H, N, dk))
+    V, dO = r.standard_normal((B, H, N, dv)), r.standard_normal((B, H, N, dv))
+    return Q, K, V, dO, r.uniform(0.5, 1.5, size=H)
+
+
+@pytest.mark.parametrize("dk,dv", [(3, 5), (6, 2)])
+def test_dkdv_forms_agree_and_match_dense_algebra(oracle, dk, dv):
+    """Keys and values of different widths: the definition, the recurrence, the sampled rows and
+    the state agree with each other and with the dense matrix expressions written with array
+    ops (P = Qhat Khat^T is N x N whatever the widths; O = s (P (.) M) V has d_value columns)."""
+    Q, K, V, dO, s = rand_inputs_dkdv(60 + dk, 2, 2, 9, dk, dv)
+    Qh, _ = oracle.normalize_rows(Q)
+    Kh, _ = oracle.normalize_rows(K)
+    P = np.einsum("bhik,bhjk->bhij", Qh, Kh)
+    sc = s[None, :, None, None]
+    O_c = sc * np.einsum("bhij,bhjc->bhic", np.tril(P), V)
+    O_b = sc * np.einsum("bhij,bhjc->bhic", P, V)
+    np.testing.assert_allclose(oracle.fwd_quadratic(Q, K, V, s, causal=True), O_c, atol=1e-12)
+    np.testing.assert_allclose(oracle.fwd_quadratic(Q, K, V, s, causal=False), O_b, atol=1e-12)
+    O_r, S = oracle.fwd_recurrent(Q, K, V, s)
+    assert O_r.shape == V.shape and S.shape == (2, 2, dk, dv)
+    np.testing.assert_allclose(O_r, O_c, atol=1e-12)
+    np.testing.assert_allclose(S, np.einsum("bhjk,bhjc->bhkc", Kh, V), atol=1e-12)
+    np.testing.assert_allclose(oracle.state_total(K, V), S, atol=1e-12)
+    rows = [(1, 0, 8), (0, 1, 0), (1, 1, 4)]
+    np.testing.assert_allclose(oracle.fwd_rows(Q, K, V, s, rows), np.stack([O_c[r] for r in rows]), atol=1e-12)
+    # prefill + single steps == one pass, with a d_key x d_value state
+    n1 = 4
+    O1, S1 = oracle.fwd_recurrent(Q[:, :, :n1], K[:, :, :n1], V[:, :, :n1], s)
+    for t in range(n1, 9):
+        o, S1 = oracle.step(Q[:, :, t], K[:, :, t], V[:, :, t], s, S1)
+        np.testing.assert_allclose(o, O_c[:, :, t], atol=1e-12)
+    np.testing.assert_allclose(S1, S, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_dkdv_gradients_by_central_differences(oracle, causal):
+    B, H, N, dk, dv = 1, 2, 5, 3, 4
+    Q, K, V, dO, s = rand_inputs_dkdv(70, B, H, N, dk, dv)
+    dQ, dK, dV, ds = oracle.bwd_quadratic(Q, K, V, s, dO, causal=causal)
+    assert dQ.shape == Q.shape and dK.shape == K.shape and dV.shape == V.shape
+    h = 1e-6
+    for name, X, G in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV), ("s", s, ds)):
+        num = np.zeros_like(X)
+        it = np.nditer(X, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = X[idx]
+            X[idx] = old + h
+            lp = _loss(oracle, Q, K, V, s, dO, causal)
+            X[idx] = old - h
+            lm = _loss(oracle, Q, K, V, s, dO, causal)
+            X[idx] = old
+            num[idx] = (lp - lm) / (2 * h)
+        err = np.abs(num - G).max() / np.abs(num).max()
+        assert err < 1e-6, (name, err)
+
+
+def test_dkdv_backward_forms_and_identities(oracle):
+    Q, K, V, dO, s = rand_inputs_dkdv(80, 2, 3, 12, 4, 7)
+    a = oracle.bwd_quadratic(Q, K, V, s, dO, causal=True)
+    b = oracle.bwd_recurrent(Q, K, V, s, dO)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, atol=1e-11)
+    dQ, dK, dV, ds = a
+    np.testing.assert_allclose((dQ * Q).sum(-1), 0, atol=1e-11)
+    np.testing.assert_allclose((dK * K).sum(-1), 0, atol=1e-11)
+    O = oracle.fwd_quadratic(Q, K, V, s, causal=True)
+    per_head = (dO * O).sum(axis=(0, 2, 3))
+    np.testing.assert_allclose((V * dV).sum(axis=(0, 2, 3)), per_head, rtol=1e-11)
+    np.testing.assert_allclose(s * ds, per_head, rtol=1e-11)
+    rows = [(0, 0, 0), (1, 2, 11), (1, 1, 5)]
+    rq, rk, rv = oracle.bwd_rows(Q, K, V, s, dO, rows)
+    np.testing.assert_allclose(rq, np.stack([dQ[r] for r in rows]), atol=1e-11)
+    np.testing.assert_allclose(rk, np.stack([dK[r] for r in rows]), atol=1e-11)
+    np.testing.assert_allclose(rv, np.stack([dV[r] for r in rows]), atol=1e-11)
+    # bidirectional closed form with rectangular S = Khat^T V and G = Qhat^T dO
+    dQ, dK, dV, ds = oracle.bwd_quadratic(Q, K, V, s, dO, causal=False)
+    Qh, qn = oracle.normalize_rows(Q)
+    Kh, kn = oracle.normalize_rows(K)
+    S = np.einsum("bhjk,bhjc->bhkc", Kh, V)
+    G = np.einsum("bhik,bhic->bhkc", Qh, dO)
+    sc = s[None, :, None, None]
+    proj = lambda Xh, dXh, n: (dXh - Xh * (Xh * dXh).sum(-1, keepdims=True)) / n[..., None]
+    np.testing.assert_allclose(dQ, proj(Qh, sc * np.einsum("bhic,bhkc->bhik", dO, S), qn), atol=1e-11)
+    np.testing.assert_allclose(dK, proj(Kh, sc * np.einsum("bhjc,bhkc->bhjk", V, G), kn), atol=1e-11)
+    np.testing.assert_allclose(dV, sc * np.einsum("bhjk,bhkc->bhjc", Kh, G), atol=1e-11)
+    np.testing.assert_allclose(ds, (S * G).sum(axis=(0, 2, 3)), atol=1e-11)
+
+
+@pytest.mark.parametrize("kind,pin", [
+    ("value_columns_rotated", "worked_dkdv"), ("value_columns_rotated", "forms"),
+    ("state_keys_truncated", "forms"), ("dv_over_key_width", "differences_dkdv"),
+    ("dv_over_key_width", "worked_dkdv"), ("dq_dk_exchanged", "worked_dkdv")])
+def test_dkdv_pins_reject_planted_mistakes(oracle, kind, pin):
+    pins = {"worked_dkdv": lambda o: check_worked_example(o, "worked_example_n3_dk2_dv3.json"),
+            "forms": lambda o: test_dkdv_forms_agree_and_match_dense_algebra(o, 3, 5),
+            "differences_dkdv": lambda o: test_dkdv_gradients_by_central_differences(o, True)}
+    pins[pin](oracle)
     with pytest.raises(AssertionError):
         pins[pin](_Mistaken(oracle, kind))
