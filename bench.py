@@ -70,12 +70,14 @@ def kernel_times(cottn, fn, iters):
     return {name: {"launches_per_step": n / iters, "avg_us": 1e3 * ms / n} for name, (n, ms) in prof.items()}
 
 
-def oracle_rate(fn, tokens):
-    """tokens per second of one call of the CPU oracle (fp64, as it stands)."""
+def oracle_rate(fn, tokens, repeat=1):
+    """tokens per second of the CPU oracle (fp64, as it stands) over `repeat` calls of fn, each
+    of which processes `tokens` tokens; also the seconds all of them took."""
     t0 = time.perf_counter()
-    fn()
+    for _ in range(repeat):
+        fn()
     dt = time.perf_counter() - t0
-    return tokens / dt, dt
+    return repeat * tokens / dt, dt
 
 
 # ---- the other configurations, each timed briefly (random bf16 values of the configured shapes;
@@ -229,14 +231,78 @@ def run_d128(torch, cottn, workloads, cpu):
             "kernels": kernel_times(cottn, d128, 50)}
 
 
+def run_sweep(torch, cottn, workloads, cpu, dims=(32, 64, 128), max_n=1 << 20, heads=16):
+    """Time and memory of forward + backward against sequence length and head dimension (the
+    sweep of Sec. 7, this library's side; no comparison system): B = 1, `heads` heads, bf16, the
+    backward handed the forward's workspace.  With the CPU leg, the linear-time oracle (fp64
+    recurrence, forward + backward) is timed beside every row up to N = 4096, and the
+    quadratic-definition oracle up to N = 1024: the first grows like N, the second like N^2."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    B, H = 1, heads
+    rows = []
+    for mode in ("causal", "bidirectional"):
+        causal = mode == "causal"
+        fwd = cottn.cottn_fwd_causal if causal else cottn.cottn_fwd_bidir
+        bwd = cottn.cottn_bwd_causal if causal else cottn.cottn_bwd_bidir
+        ops = (cottn.OP_FWD_CAUSAL, cottn.OP_BWD_CAUSAL) if causal else (cottn.OP_FWD_BIDIR, cottn.OP_BWD_BIDIR)
+        for d in dims:
+            N = 256
+            while N <= max_n:
+                t = {n: (torch.randn(B, H, N, d, device=dev, generator=gen) * 0.5).to(torch.bfloat16)
+                     for n in ("Q", "K", "V", "dO")}
+                t.update({n: torch.empty_like(t["Q"]) for n in ("O", "dQ", "dK", "dV")})
+                s = torch.ones(H, device=dev)
+                ds = torch.empty(H, device=dev)
+                fb = max(cottn.cottn_workspace_bytes(ops[0], B, H, N, d), 256)
+                bb = max(cottn.cottn_workspace_bytes(ops[1], B, H, N, d), 256)
+                fws = torch.empty(fb, dtype=torch.uint8, device=dev)
+                bws = torch.empty(bb, dtype=torch.uint8, device=dev)
+
+                def step(i):
+                    fwd(t["Q"], t["K"], t["V"], s, O=t["O"], workspace=fws)
+                    bwd(t["Q"], t["K"], t["V"], s, t["dO"], dQ=t["dQ"], dK=t["dK"], dV=t["dV"], ds=ds,
+                        workspace=bws, fwd_workspace=fws)
+                ms = time_calls(torch, step, 50 if N <= 16384 else 10 if N <= 262144 else 4, 3)
+                row = {"mode": mode, "d": d, "N": N, "ms": ms, "tokens_per_s": B * N / (ms * 1e-3),
+                       "tensor_bytes": 8 * B * H * N * d * 2, "workspace_bytes": fb + bb,
+                       "segments": cottn.cottn_segments(ops[0], B, H, N, d),
+                       "oracle_linear_ms": None, "oracle_quadratic_ms": None}
+                if cpu and N <= 4096:
+                    import oracle
+                    x = {n: t[n].double().cpu().numpy() for n in ("Q", "K", "V", "dO")}
+                    one = s.double().cpu().numpy()
+                    if causal:
+                        lin = lambda: (oracle.fwd_recurrent(x["Q"], x["K"], x["V"], one),
+                                       oracle.bwd_recurrent(x["Q"], x["K"], x["V"], one, x["dO"]))
+                        row["oracle_linear_ms"] = 1e3 * oracle_rate(lin, B * N)[1]
+                    if N <= 1024:
+                        quad = lambda: (oracle.fwd_quadratic(x["Q"], x["K"], x["V"], one, causal=causal),
+                                        oracle.bwd_quadratic(x["Q"], x["K"], x["V"], one, x["dO"], causal=causal))
+                        row["oracle_quadratic_ms"] = 1e3 * oracle_rate(quad, B * N)[1]
+                rows.append(row)
+                print("sweep %s d=%d N=%d: %.3f ms" % (mode, d, N, ms), file=sys.stderr, flush=True)
+                del t, fws, bws
+                N *= 4
+    out = {"batch": B, "heads": H, "dtype": "bf16", "rows": rows,
+           "unsupported": "d = 256 (head dimensions are 32, 64, 128 in this library)"}
+    if cpu:
+        import oracle
+        out["oracle_cores"] = oracle.num_threads()
+    return out
+
+
 OTHER = {"cfg5": ("cfg5_decode_step", run_decode), "cfg3": ("cfg3_bidir_fwd_bwd", run_bidir),
          "cfg4": (None, run_long), "d128": ("d128_causal_fwd_bwd_B8_H12_N1024", run_d128)}
+# run only when named (--workload sweep): minutes of GPU and CPU time, not part of the default line
+ON_REQUEST = {"sweep": ("time_memory_sweep", run_sweep)}
 
 
 def other_workloads(torch, cottn, workloads, cpu, only=None):
     out = {}
-    for key, (name, fn) in OTHER.items():
-        if only is not None and key != only:
+    for key, (name, fn) in {**OTHER, **ON_REQUEST}.items():
+        if key != only and (only is not None or key in ON_REQUEST):
             continue
         res = fn(torch, cottn, workloads, cpu)
         if name is None:
@@ -258,7 +324,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the brief timings of the decode, bidirectional and long-context shapes")
-    ap.add_argument("--workload", choices=sorted(OTHER), default=None,
+    ap.add_argument("--workload", choices=sorted({**OTHER, **ON_REQUEST}), default=None,
                     help="time only this one of the other configurations (for profiling runs)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB a few times before the "
@@ -377,16 +443,16 @@ def main():
         # Sec. 4 backward: the same O(N d^2) work as the GPU path), and the quadratic definition
         lin_rate, lin_dt = oracle_rate(lambda: (oracle.fwd_recurrent(hi["Q"], hi["K"], hi["V"], hi["s"]),
                                                 oracle.bwd_recurrent(hi["Q"], hi["K"], hi["V"], hi["s"], hi["dO"])),
-                                       B * N)
+                                       B * N, repeat=40)
         quad_rate, quad_dt = oracle_rate(lambda: (oracle.fwd_quadratic(hi["Q"], hi["K"], hi["V"], hi["s"]),
                                                   oracle.bwd_quadratic(hi["Q"], hi["K"], hi["V"], hi["s"], hi["dO"])),
-                                         B * N)
+                                         B * N, repeat=8)
         cpu = {"value": lin_rate, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "one full step of the same workload (B=8,H=12,N=1024,d=64): fp64 linear-time "
-                         "(recurrent) forward + backward, %.2f s" % lin_dt,
+               "sample": "40 full steps of the same workload (B=8,H=12,N=1024,d=64): fp64 linear-time "
+                         "(recurrent) forward + backward, %.1f s" % lin_dt,
                "quadratic_definition": {"value": quad_rate, "unit": "tokens/s",
-                                        "sample": "the same step by the fp64 quadratic definition "
-                                                  "(forward + brute-force backward), %.2f s" % quad_dt}}
+                                        "sample": "8 of the same steps by the fp64 quadratic definition "
+                                                  "(forward + brute-force backward), %.1f s" % quad_dt}}
 
     out = {
         "metric": "causal cosine-attn fwd+bwd tokens/s (B8 H12 N1024 d64 bf16)",
