@@ -111,9 +111,9 @@ def run_decode(torch, cottn, workloads, cpu):
         rng = np.random.default_rng(0)
         qs, ks, vs = (rng.standard_normal((Bs, H, d)) for _ in range(3))
         S = np.zeros((Bs, H, d, d))
-        rate, dt = oracle_rate(lambda: [oracle.step(qs, ks, vs, np.ones(H), S) for _ in range(8)], 8 * Bs)
+        rate, dt = oracle_rate(lambda: [oracle.step(qs, ks, vs, np.ones(H), S) for _ in range(8)], 8 * Bs, repeat=50)
         out["cpu_oracle"] = {"tokens_per_s": rate, "cores": oracle.num_threads(),
-                             "sample": "8 steps of %d of the %d sequences (fp64 recurrence), %.2f s" % (Bs, B, dt)}
+                             "sample": "400 steps of %d of the %d sequences (fp64 recurrence), %.1f s" % (Bs, B, dt)}
     return out
 
 
@@ -152,9 +152,9 @@ def run_bidir(torch, cottn, workloads, cpu):
         x = workloads.draw(Bs, H, N, d, "bf16", w.seed)
         rate, dt = oracle_rate(lambda: (oracle.fwd_quadratic(x["Q"], x["K"], x["V"], x["s"], causal=False),
                                         oracle.bwd_quadratic(x["Q"], x["K"], x["V"], x["s"], x["dO"], causal=False)),
-                               Bs * N)
+                               Bs * N, repeat=10)
         out["cpu_oracle"] = {"tokens_per_s": rate, "cores": oracle.num_threads(),
-                             "sample": "%d of the %d sequences: fp64 quadratic-definition forward + backward, %.2f s" % (Bs, B, dt)}
+                             "sample": "10 times %d of the %d sequences: fp64 quadratic-definition forward + backward, %.1f s" % (Bs, B, dt)}
     return out
 
 
@@ -195,10 +195,10 @@ def run_long(torch, cottn, workloads, cpu, chunks=(64, 128, 256)):
         x = workloads.draw(B, H, Ns, d, "bf16", w.seed, w.value_scale)
         rate, dt = oracle_rate(lambda: (oracle.fwd_recurrent(x["Q"], x["K"], x["V"], x["s"]),
                                         oracle.bwd_recurrent(x["Q"], x["K"], x["V"], x["s"], x["dO"])),
-                               B * Ns)
+                               B * Ns, repeat=10)
         out["cfg4_long_context_chunk64"]["cpu_oracle"] = {
             "tokens_per_s": rate, "cores": oracle.num_threads(),
-            "sample": "the first %d of the %d tokens of all %d heads: fp64 linear-time (recurrent) forward + backward, %.2f s" % (Ns, N, H, dt)}
+            "sample": "10 times the first %d of the %d tokens of all %d heads: fp64 linear-time (recurrent) forward + backward, %.1f s" % (Ns, N, H, dt)}
     return out
 
 
