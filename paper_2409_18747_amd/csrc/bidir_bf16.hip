@@ -119,7 +119,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
   __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::FWD_OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
 
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const e16_t* Qu = Q + size_t(unit) * N * DK;
@@ -203,7 +204,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
   __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
   __shared__ float rq[C], rk[C];
 
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const e16_t* Qu = Q + size_t(unit) * N * DK;

@@ -63,9 +63,8 @@ struct BwdCfg {
   static constexpr int TPK = tile_pitch(DK, C), TPV = tile_pitch(DV, C);   // operand tiles
   static constexpr int SPK = lds_pitch(DK), SPV = lds_pitch(DV);   // state copies
   static constexpr int TILEK = C * TPK, TILEV = C * TPV;
-  // the larger of the two state copies ([d_value][d_key] in the dQ scan, [d_key][d_value] in
-  // the dK/dV scan)
-  static constexpr int STATE = DV * SPK > DK * SPV ? DV * SPK : DK * SPV;
+  // the bf16 copy of the running state, [d_key][d_value] in both scans
+  static constexpr int STATE = DK * SPV;
   static constexpr int LDS_BYTES = 2 * (2 * TILEK + 2 * TILEV + STATE) + 4 * C + 64;
   static constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES;
   // the dQ kernel adds a staging tile when that does not lower the workgroups per compute
@@ -109,11 +108,13 @@ __global__ __launch_bounds__(256) void bwd_state_carry(float* __restrict__ fwd_t
 
 // ---------------------------------------------------------------------------------------
 // Kernel 3: dQ of one segment, chunks in forward order.  Wave w owns query rows 16w..16w+15.
-// The running state S ([d_key][d_value]) sits in accumulators with key rows and value
-// columns: element [v] of lane (r, q4) of tile (y, x) is S[16 rt + 4 q4 + v][16 ct + r].  A
-// lane thus holds 4 consecutive keys of one value column and publishes them with one 8-byte
-// write to the transposed LDS copy St[d_value][d_key]; the update's row-side operand is the
-// K fragment already read for the intra-chunk product.
+// The running state S ([d_key][d_value]) sits in accumulators with the keys along the lanes:
+// element [v] of lane (r, q4) of tile (key tile y, value tile x) is
+// S[16 rt + r][16 ct + 4 q4 + v], the orientation the forward scan and the totals kernel use
+// (so the stored states are read tile by tile, one 1 KB instruction per tile).  A lane holds 4
+// consecutive values of one key row and publishes them with one 8-byte write to the row-major
+// LDS copy St[d_key][d_value]; the update's key-side operand is the K fragment already read
+// for the intra-chunk product.
 template <int DK, int DV, int C>
 __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTTN_SYM(bwd_dq_scan)(
     const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
@@ -127,12 +128,12 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
   using RT = AccTiles<DV, DK, Cfg::NW>;   // reverse-time total: value rows, key columns
   using StageK = TileStage<DK, C, Cfg::NT>;
   using StageV = TileStage<DV, C, Cfg::NT>;
-  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SPK;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SPV;
   __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // qh = r_i q_i
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // kh = r_j k_j
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];   // raw v
   __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILEV];   // dO
-  __shared__ __attribute__((aligned(16))) e16_t St[DV * Cfg::SPK];  // state, [d_value][d_key]
+  __shared__ __attribute__((aligned(16))) e16_t St[DK * Cfg::SPV];  // state, [d_key][d_value]
   // Every wave reads all rows of all four tiles until the end of a chunk (the reverse total
   // contracts Qs and Gs over the tokens), so finished dQ rows are staged in a tile of their
   // own when LDS has room for one; otherwise behind a barrier in the dead dO tile.
@@ -140,7 +141,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
   __shared__ float rq[C];
   __shared__ float ds_wave[Cfg::NW];
 
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const e16_t* Qu = Q + size_t(unit) * N * DK;
@@ -181,9 +183,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
     const float* src = fwd_states + size_t(unit) * G * DK * DV;
     add_stored_states<AT::STATE_BATCH>(
         sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
-          const float* p = src + size_t(gp) * DK * DV + (16 * AT::row_tile(w, y) + 4 * q4) * DV +
-                           16 * AT::col_tile(w, x) + r;
-          return f32x4{p[0], p[DV], p[2 * DV], p[3 * DV]};
+          return *reinterpret_cast<const f32x4*>(
+              src + size_t(gp) * DK * DV +
+              tiled_state_offset(AT::row_tile(w, y), AT::col_tile(w, x), DV / 16, l));
         });
   }
   // the state of the rows before this piece of the sequence belongs to every segment's start
@@ -192,10 +194,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
 #pragma unroll
     for (int x = 0; x < AT::NCT; ++x)
 #pragma unroll
-      for (int y = 0; y < AT::NRT; ++y) {
-        const float* p = src + (16 * AT::row_tile(w, y) + 4 * q4) * DV + 16 * AT::col_tile(w, x) + r;
-        sacc[x][y] += f32x4{p[0], p[DV], p[2 * DV], p[3 * DV]};
-      }
+      for (int y = 0; y < AT::NRT; ++y)
+        sacc[x][y] += *reinterpret_cast<const f32x4*>(src + (16 * AT::row_tile(w, y) + r) * DV +
+                                                      16 * AT::col_tile(w, x) + 4 * q4);
   }
 
   RowPieces<DK> finished;  // dQ rows of the previous chunk, stored one chunk late
@@ -210,8 +211,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
           uint2 pk;
           pk.x = pack2(sacc[x][y][0], sacc[x][y][1]);
           pk.y = pack2(sacc[x][y][2], sacc[x][y][3]);
-          *reinterpret_cast<uint2*>(St + (16 * AT::col_tile(w, x) + r) * SP +
-                                    16 * AT::row_tile(w, y) + 4 * q4) = pk;
+          *reinterpret_cast<uint2*>(St + (16 * AT::row_tile(w, y) + r) * SP +
+                                    16 * AT::col_tile(w, x) + 4 * q4) = pk;
         }
     }
     {
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
     if (row0 > row_begin) store_row_pieces<DK>(finished, dQu, row0 - C + 16 * w, row_end, l);
     __syncthreads();
 
-    // earlier chunks: dqh^T += S dO^T (contraction over d_value = rows of St)
+    // earlier chunks: dqh^T += S dO^T (contraction over d_value = along the rows of St)
     frag8 gf[Cfg::KSV];  // dO rows of this wave: column-side operand of every product
 #pragma unroll
     for (int ks = 0; ks < Cfg::KSV; ++ks)
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
       frag8 sf[Cfg::DTK];
 #pragma unroll
       for (int nt = 0; nt < Cfg::DTK; ++nt)
-        sf[nt] = lds_col_frag(St, SP, 32 * ks + 8 * q4, 32 * ks + 8 * q4 + 4, 16 * nt, r);
+        sf[nt] = lds_row_frag(St + (16 * nt + r) * SP + 32 * ks + 8 * q4);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = mma16(sf[nt], gf[ks], dq[nt]);
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
         for (int y = 0; y < AT::NRT; ++y)
 #pragma unroll
           for (int x = 0; x < AT::NCT; ++x)
-            sacc[x][y] = mma16(AT::WPC == 1 ? kc[y] : krow[y], vcol[x], sacc[x][y]);
+            sacc[x][y] = mma16(vcol[x], AT::WPC == 1 ? kc[y] : krow[y], sacc[x][y]);
       }
       // reverse total: R^T += dO^T qh over the same tokens
       if (with_rev && RT::active(w)) {
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
     for (int x = 0; x < RT::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < RT::NRT; ++y)
-        store_state_words(out + (16 * RT::col_tile(w, x) + r) * DV + 16 * RT::row_tile(w, y) + 4 * q4,
+        store_state_words(out + tiled_state_offset(RT::col_tile(w, x), RT::row_tile(w, y), DV / 16, l),
                           racc[x][y]);
   }
 
@@ -390,7 +391,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
   __shared__ __attribute__((aligned(16))) e16_t Rl[DK * Cfg::SPV];  // reverse state, [d_key][d_value]
   __shared__ float rk[C];
 
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const e16_t* Qu = Q + size_t(unit) * N * DK;
@@ -439,9 +441,9 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
     const float* src = rev_states + size_t(unit) * G * DK * DV;
     add_stored_states<AT::STATE_BATCH>(
         racc, sum_totals ? g + 1 : g, sum_totals ? G - 1 : g, [&](int gp, int x, int y) {
-          return *reinterpret_cast<const f32x4*>(src + size_t(gp) * DK * DV +
-                                                 (16 * AT::col_tile(w, x) + r) * DV +
-                                                 16 * AT::row_tile(w, y) + 4 * q4);
+          return *reinterpret_cast<const f32x4*>(
+              src + size_t(gp) * DK * DV +
+              tiled_state_offset(AT::col_tile(w, x), AT::row_tile(w, y), DV / 16, l));
         });
   }
   // the reverse state of the rows after this piece of the sequence belongs to every segment

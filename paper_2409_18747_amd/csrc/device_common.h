@@ -217,6 +217,39 @@ __device__ __forceinline__ void store_state_words(float* dst, f32x4 v) {
   __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
 }
 
+// States that only two kernels of this library hand to each other (workspace arrays that no
+// caller reads) need not be row-major.  Stored tile by tile in the order the accumulator
+// registers hold them - the 16x16 tile (a, b) as 256 consecutive floats, the four values of
+// lane l at 4 l - a wave writes or reads a tile with one instruction that covers 1 KB of
+// consecutive addresses.  Row-major, the same four-value pieces lie a matrix row apart and one
+// instruction touches 16 to 64 cache lines, which the vector L1 looks up one per cycle: with
+// up to three stored states per workgroup that was most of the 2 us by which a scan
+// workgroup's first chunk started later than its rows arrived.
+__device__ __forceinline__ int tiled_state_offset(int tile_a, int tile_b, int tiles_b, int lane) {
+  return (tile_a * tiles_b + tile_b) * 256 + 4 * lane;
+}
+
+// Which (batch-head unit, segment) a workgroup of a units * G grid works on.  Workgroups are
+// dealt to the 8 XCDs round robin by their index, and each XCD has an L2 of its own.  The
+// kernels of one call that share this numbering pass data to each other through that L2: the
+// rows a totals workgroup read are there for the scan workgroup of the same (unit, segment),
+// and the G segments of a unit all land on one XCD (workgroup indices 8 apart), so the segment
+// states that the workgroups of a unit write for each other never cross to another L2.
+// (Measured on B8 H12 N1024 d64: 1.6 us of a 56 us step against unit = index / G.)
+// Units beyond the last whole group of 8 are numbered plainly.
+__device__ __forceinline__ void unit_and_segment(int index, int G, int& unit, int& g) {
+  const int n_units = gridDim.x / G;
+  const int grouped = (n_units / 8) * 8 * G;
+  if (index < grouped) {
+    const int in_group = index % (8 * G);
+    unit = (index / (8 * G)) * 8 + in_group % 8;
+    g = in_group / 8;
+  } else {
+    unit = (n_units / 8) * 8 + (index - grouped) / G;
+    g = (index - grouped) % G;
+  }
+}
+
 // In place, for 4 neighbouring elements of a stack of n matrices `stride` floats apart:
 // matrix k (in walking order: first to last, or last to first with `reverse`) <- sum of the
 // matrices walked before it.  The last matrix walked never held a value and is not read.  The

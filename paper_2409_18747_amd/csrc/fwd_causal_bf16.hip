@@ -97,7 +97,7 @@ template <> struct FwdSplit<128, 128, 64> { static constexpr int CS = 2; };
 // path uses it for Kh^T V and, with (K, V) := (Q, dO), for Qh^T dO; there, given the stored
 // segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
 // also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
-template <int DK, int DV, int C>
+template <int DK, int DV, int C, bool TILED>
 __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     const e16_t* __restrict__ K, const e16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
@@ -111,7 +111,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
   __shared__ float dot_wave[Cfg::NW];
 
-  const int unit = blockIdx.x / n_slots, g = blockIdx.x % n_slots;
+  int unit, g;
+  unit_and_segment(blockIdx.x, n_slots, unit, g);
   if (g >= n_compute) return;
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
@@ -120,7 +121,9 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
   const int row_begin = g * seg_rows;
   const int row_end = min(valid_rows(seq_len, unit, H, N), row_begin + seg_rows);
 
-  // acc[x][y] = S tile (key tile row_tile(y), value tile col_tile(x))
+  // acc[x][y] = S tile (key tile row_tile(y), value tile col_tile(x)), held with the keys
+  // along the lanes: element [v] of lane (r, q4) is S[16 kt + r][16 vt + 4 q4 + v], the
+  // orientation the forward and the dQ scan keep their running state in
   f32x4 acc[ST::NCT][ST::NRT];
 #pragma unroll
   for (int x = 0; x < ST::NCT; ++x)
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
 #pragma unroll
         for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
-          for (int x = 0; x < ST::NCT; ++x) acc[x][y] = mma16(ak[y], bv[x], acc[x][y]);
+          for (int x = 0; x < ST::NCT; ++x) acc[x][y] = mma16(bv[x], ak[y], acc[x][y]);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -168,10 +171,9 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     for (int x = 0; x < ST::NCT; ++x)
 #pragma unroll
       for (int y = 0; y < ST::NRT; ++y)
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-          store_state_word(out + (16 * ST::row_tile(w, y) + 4 * q4 + v) * DV +
-                               16 * ST::col_tile(w, x) + r, acc[x][y][v]);
+        store_state_words(out + (TILED ? tiled_state_offset(ST::row_tile(w, y), ST::col_tile(w, x), DV / 16, l)
+                                       : (16 * ST::row_tile(w, y) + r) * DV + 16 * ST::col_tile(w, x) + 4 * q4),
+                          acc[x][y]);
   }
   if (dot_with != nullptr) {  // workgroup-uniform
     float dot = 0.f;
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
         for (int y = 0; y < ST::NRT; ++y)
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const int e = (16 * ST::row_tile(w, y) + 4 * q4 + v) * DV + 16 * ST::col_tile(w, x) + r;
+            const int e = (16 * ST::row_tile(w, y) + r) * DV + 16 * ST::col_tile(w, x) + 4 * q4 + v;
             float o = 0.f;
             for (int j = 0; j < dot_slots; ++j) o += other[size_t(j) * DK * DV + e];
             dot += acc[x][y][v] * o;
@@ -248,7 +250,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<DK, DV, C>::template waves_per_
   // wider than the queries they do not fit the q rows: own staging tile
   __shared__ __attribute__((aligned(16))) e16_t Os[OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
-  const int unit = blockIdx.x / G, g = blockIdx.x % G;
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const int rg = w % RG, cp = w / RG;  // row group, column part
@@ -288,14 +291,12 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<DK, DV, C>::template waves_per_
                                                       16 * ST::row_tile(rg, cp, y) + 4 * q4);
   }
   if (seg_states != nullptr && g > 0 && ST::active(rg, cp)) {
-    const float* src = seg_states + size_t(unit) * G * DK * DV + (16 * ST::col_tile(rg, cp, 0) + r) * DV +
-                       16 * ST::row_tile(rg, cp, 0) + 4 * q4;
+    const float* src = seg_states + size_t(unit) * G * DK * DV + 4 * l;
     add_stored_states<ST::STATE_BATCH>(
         sacc, sum_totals ? 0 : g, sum_totals ? g - 1 : g, [&](int gp, int x, int y) {
           return *reinterpret_cast<const f32x4*>(
               src + size_t(gp) * DK * DV +
-              16 * (ST::col_tile(rg, cp, x) - ST::col_tile(rg, cp, 0)) * DV +
-              16 * (ST::row_tile(rg, cp, y) - ST::row_tile(rg, cp, 0)));
+              tiled_state_offset(ST::col_tile(rg, cp, x), ST::row_tile(rg, cp, y), DV / 16, 0));
         });
   }
 
@@ -482,7 +483,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
 
 }  // namespace
 
-template <int DK, int DV>
+template <int DK, int DV, bool TILED>
 static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   const e16_t* X = static_cast<const e16_t*>(t.X);
   const e16_t* Y = static_cast<const e16_t*>(t.Y);
@@ -493,25 +494,25 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   // operand-tile pitch would leave room for one: measured 0.6 us slower on the GPT shape).
   const dim3 grid(t.units * t.G);
   if (t.seg_rows >= 128)
-    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 128>, grid, dim3(512),
+    return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 128, TILED>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
                          t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
-  return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 64>, grid, dim3(256), 0,
+  return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 64, TILED>, grid, dim3(256), 0,
                        t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
                        t.dot_slots, t.dot_out, t.seq_len, t.H);
 }
 
 hipError_t COTTN_SYM(launch_segment_totals)(const SegmentTotalsArgs& t) {
   switch (t.dk * 1000 + t.dv) {
-    case 32032: return run_segment_totals<32, 32>(t);
-    case 32064: return run_segment_totals<32, 64>(t);
-    case 32128: return run_segment_totals<32, 128>(t);
-    case 64032: return run_segment_totals<64, 32>(t);
-    case 64064: return run_segment_totals<64, 64>(t);
-    case 64128: return run_segment_totals<64, 128>(t);
-    case 128032: return run_segment_totals<128, 32>(t);
-    case 128064: return run_segment_totals<128, 64>(t);
-    case 128128: return run_segment_totals<128, 128>(t);
+    case 32032: return t.tiled ? run_segment_totals<32, 32, true>(t) : run_segment_totals<32, 32, false>(t);
+    case 32064: return t.tiled ? run_segment_totals<32, 64, true>(t) : run_segment_totals<32, 64, false>(t);
+    case 32128: return t.tiled ? run_segment_totals<32, 128, true>(t) : run_segment_totals<32, 128, false>(t);
+    case 64032: return t.tiled ? run_segment_totals<64, 32, true>(t) : run_segment_totals<64, 32, false>(t);
+    case 64064: return t.tiled ? run_segment_totals<64, 64, true>(t) : run_segment_totals<64, 64, false>(t);
+    case 64128: return t.tiled ? run_segment_totals<64, 128, true>(t) : run_segment_totals<64, 128, false>(t);
+    case 128032: return t.tiled ? run_segment_totals<128, 32, true>(t) : run_segment_totals<128, 32, false>(t);
+    case 128064: return t.tiled ? run_segment_totals<128, 64, true>(t) : run_segment_totals<128, 64, false>(t);
+    case 128128: return t.tiled ? run_segment_totals<128, 128, true>(t) : run_segment_totals<128, 128, false>(t);
     default: return hipErrorInvalidValue;
   }
 }
@@ -522,6 +523,7 @@ hipError_t COTTN_SYM(launch_fwd_segment_totals)(const CausalArgs& a, float* dst)
   t.units = a.B * a.H; t.N = a.N; t.dk = a.dk; t.dv = a.dv; t.G = a.G; t.n_compute = a.G - 1;
   t.seg_rows = a.seg_rows; t.eps = a.eps; t.stream = a.stream;
   t.seq_len = a.seq_len; t.H = a.H;
+  t.tiled = true;  // read by the scan kernels only
   return COTTN_SYM(launch_segment_totals)(t);
 }
 

@@ -83,6 +83,9 @@ struct SegmentTotalsArgs {
   float eps;
   const float* dot_with; int dot_slots; float* dot_out;
   const int* seq_len; int H;  // padded batches: rows at or beyond seq_len[unit / H] do not exist
+  // dst row-major [dk][dv] per slot (false), or in the tile order the causal scan kernels read
+  // their stored states in (device_common.h: tiled_state_offset, tile (key tile, value tile))
+  bool tiled;
   hipStream_t stream;
 };
 hipError_t launch_segment_totals_bf16(const SegmentTotalsArgs& t);

@@ -16,7 +16,10 @@ bool make_plan(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype
 
 inline size_t round_up_256(size_t x) { return (x + 255) & ~size_t(255); }
 
-// Workspace layouts (all fp32; a state is dk x dv, [d_key][d_value]):
+// Workspace layouts (all fp32; a state is dk x dv: row-major [d_key][d_value] on the
+// bidirectional and fp32 paths; the 16-bit causal kernels, which alone read what they write
+// here, keep each state in 16x16 tiles of 256 consecutive floats in accumulator-register order,
+// device_common.h: tiled_state_offset):
 //   causal forward   G > 1: [units][G][dk][dv]   segment totals, turned in place into the
 //                            state at each segment start
 //   causal backward  G > 1: the same array for the forward-time states, a second one for
