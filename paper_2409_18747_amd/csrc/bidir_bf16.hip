@@ -119,6 +119,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
   __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::FWD_OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
 
+  fetch_argument_now(Q, s, O, totals, slots, n_sum, state, H, N, G, seg_rows, inv_eps, seq_len,
+                     s_per_unit);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
@@ -204,6 +206,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
   __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
   __shared__ float rq[C], rk[C];
 
+  fetch_argument_now(Q, K, V, dO, s, dQ, dK, dV, s_totals, g_totals, slots, n_sum, ds_partial, n_ds,
+                     ds, B, H, N, G, seg_rows, inv_eps, seq_len, s_per_unit);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,

@@ -141,6 +141,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
   __shared__ float rq[C];
   __shared__ float ds_wave[Cfg::NW];
 
+  fetch_argument_now(Q, K, V, dO, s, dQ, fwd_states, rev_totals, ds_partial, H, N, G, seg_rows,
+                     inv_eps, sum_totals, seq_len, s_per_unit, state_in);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
@@ -391,6 +393,8 @@ __global__ __launch_bounds__(C * 4, (BwdCfg<DK, DV, C>::WAVES_PER_EU)) void COTT
   __shared__ __attribute__((aligned(16))) e16_t Rl[DK * Cfg::SPV];  // reverse state, [d_key][d_value]
   __shared__ float rk[C];
 
+  fetch_argument_now(Q, K, V, dO, s, dK, dV, rev_states, ds_partial, ds, B, H, N, G, seg_rows,
+                     inv_eps, sum_totals, seq_len, s_per_unit, rev_in, rev_out);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,

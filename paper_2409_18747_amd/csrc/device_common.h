@@ -229,6 +229,20 @@ __device__ __forceinline__ int tiled_state_offset(int tile_a, int tile_b, int ti
   return (tile_a * tiles_b + tile_b) * 256 + 4 * lane;
 }
 
+// Makes the compiler fetch a kernel argument where this stands.  Left alone it fetches each
+// argument where it is first used, one scalar load and one wait after the other down the
+// kernel's prologue (six or more round trips to the scalar cache before the first row is
+// requested); pinned at the top, all of them come with one or two wide loads and one wait.
+template <class T>
+__device__ __forceinline__ void fetch_argument_now(const T& x) {
+  asm volatile("" ::"s"(x));
+}
+template <class T, class... Rest>
+__device__ __forceinline__ void fetch_argument_now(const T& x, const Rest&... rest) {
+  fetch_argument_now(x);
+  fetch_argument_now(rest...);
+}
+
 // Which (batch-head unit, segment) a workgroup of a units * G grid works on.  Workgroups are
 // dealt to the 8 XCDs round robin by their index, and each XCD has an L2 of its own.  The
 // kernels of one call that share this numbering pass data to each other through that L2: the

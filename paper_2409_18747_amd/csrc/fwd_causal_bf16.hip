@@ -111,6 +111,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
   __shared__ float dot_wave[Cfg::NW];
 
+  fetch_argument_now(K, V, seg_state, N, n_slots, n_compute, seg_rows, inv_eps, dot_with, dot_slots,
+                     dot_out, seq_len, H);
   int unit, g;
   unit_and_segment(blockIdx.x, n_slots, unit, g);
   if (g >= n_compute) return;
@@ -250,6 +252,8 @@ __global__ __launch_bounds__(C * 4 * CS, (FwdCfg<DK, DV, C>::template waves_per_
   // wider than the queries they do not fit the q rows: own staging tile
   __shared__ __attribute__((aligned(16))) e16_t Os[OWN_STAGE ? Cfg::TILEV : 8];
   __shared__ float rq[C];
+  fetch_argument_now(Q, K, V, s, O, state_out, seg_states, state_in, H, N, G, seg_rows, inv_eps,
+                     sum_totals, seq_len, s_per_unit, stream_q);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
