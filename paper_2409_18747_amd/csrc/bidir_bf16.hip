@@ -10,16 +10,17 @@
 // followed by the chain rule through the row normalisation.
 //
 // Launches per call:
-//   totals   the segment-totals kernel of the causal forward reduces N(X)^T Y over one
-//            segment of rows per workgroup (split over the sequence because B*H alone may
-//            not fill the chip), for (X, Y) = (K, V) and, in the backward, (Q, dO);
-//   combine  only with many segments, or in a backward that was not handed the forward's
-//            totals: sums the segment totals per (batch, head) into slot 0 and forms the
-//            per-(b,h) share of ds;
-//   apply    streams the rows once more and multiplies them with the d x d matrices; with
-//            few segments it adds up the segment totals itself while staging them.
-// A backward that is handed the forward's workspace does not reduce Kh^T V again, and its
-// totals kernel forms <S, G_segment> on the fly, so it is two launches.
+//   forward   totals: the segment-totals kernel of the causal forward reduces Kh^T V over one
+//             segment of rows per workgroup (split over the sequence because B*H alone may not
+//             fill the chip); apply: streams the Q rows and multiplies them with S;
+//   backward  first sweep (Q, dO -> dQ): dQ needs only S, which the forward left behind, so
+//             the sweep that has to read Q and dO for G = Qh^T dO forms dQ on the way and
+//             leaves G's segment totals and the shares of ds (= sum_i qh_i . dqh_i, the same
+//             number as <S, G>); second sweep (K, V -> dK, dV) applies G.  Every row of the
+//             seven tensors is moved once.  A backward that was not handed the forward's
+//             totals reduces Kh^T V first;
+//   combine   only with many segments: sums the segment totals per (batch, head) into slot 0;
+//             with few, the kernels add the totals up themselves while staging them.
 //
 // The apply kernels follow the scheme of the causal kernels: raw rows as MFMA operands,
 // normalisation factors on result rows, results accumulated transposed and staged through
@@ -182,41 +183,174 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_bidir_apply)(
   if (seq_len != nullptr) zero_rows_e16<DV>(Ou, row_end, seg_end);  // rows that do not exist
 }
 
-// dQ, dK, dV rows of one segment; the first H workgroups also finish ds from the n_ds
-// partial sums per (batch, head).  All products are accumulated transposed:
-//   dqh^T = S dO^T (over d_value),  dkh^T = G V^T (over d_value),  (k G)^T = G^T k^T (over
-//   d_key), then dq_i = s r_i (dqh_i - qh_i (qh_i . dqh_i)), dk_j likewise, dv_j = s r_j (k_j G).
+// Backward, first sweep: dQ rows of one segment and the segment's total of Qh^T dO.  It needs
+// only S = Kh^T V, which the forward already reduced, so the rows of Q and dO are read once,
+// here, for both dQ and the matrix G that the second sweep applies:
+//   dqh^T = S dO^T (over d_value),  dq_i = s r_i (dqh_i - qh_i (qh_i . dqh_i)),
+//   G_segment = sum over the rows of qh_i^T dO_i,  ds share = sum of qh_i . dqh_i.
+// Q is stored in LDS as qh = r_i q_i: it is contracted over the tokens in G, and the chain
+// rule wants the normalised row anyway.  Every wave reads all rows of both tiles (the total
+// contracts them over the tokens), so finished dQ rows are staged in a tile of their own.
 template <int DK, int DV, int C>
-__global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
-    const e16_t* __restrict__ Q, const e16_t* __restrict__ K, const e16_t* __restrict__ V,
-    const e16_t* __restrict__ dO, const float* __restrict__ s, e16_t* __restrict__ dQ,
-    e16_t* __restrict__ dK, e16_t* __restrict__ dV, const float* __restrict__ s_totals,
-    const float* __restrict__ g_totals, int slots, int n_sum, const float* __restrict__ ds_partial,
-    int n_ds, float* __restrict__ ds, int B, int H, int N, int G, int seg_rows, float inv_eps,
-    const int* __restrict__ seq_len, int s_per_unit) {
+__global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_dq)(
+    const e16_t* __restrict__ Q, const e16_t* __restrict__ dO, const float* __restrict__ s,
+    e16_t* __restrict__ dQ, const float* __restrict__ s_totals, int slots, int n_sum,
+    float* __restrict__ g_totals, float* __restrict__ ds_partial, int H, int N, int G,
+    int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
   using Cfg = BiCfg<DK, DV, C>;
+  using RT = AccTiles<DV, DK, Cfg::NW>;   // total of Qh^T dO: value rows, key columns
   using StageK = TileStage<DK, C, Cfg::NT>;
   using StageV = TileStage<DV, C, Cfg::NT>;
   constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SP;
-  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // raw q
-  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // raw k
-  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
+  __shared__ __attribute__((aligned(16))) e16_t Qs[Cfg::TILEK];   // qh = r_i q_i
   __shared__ __attribute__((aligned(16))) e16_t Gs[Cfg::TILEV];   // dO
-  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];  // Kh^T V,  [d_key][d_value]
-  __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
-  __shared__ float rq[C], rk[C];
+  __shared__ __attribute__((aligned(16))) e16_t Os[Cfg::TILEK];   // finished dQ rows
+  __shared__ __attribute__((aligned(16))) e16_t Sl[Cfg::STATE];   // Kh^T V, [d_key][d_value]
+  __shared__ float rq[C];
+  __shared__ float ds_wave[Cfg::NW];
 
-  fetch_argument_now(Q, K, V, dO, s, dQ, dK, dV, s_totals, g_totals, slots, n_sum, ds_partial, n_ds,
-                     ds, B, H, N, G, seg_rows, inv_eps, seq_len, s_per_unit);
+  fetch_argument_now(Q, dO, s, dQ, s_totals, slots, n_sum, g_totals, ds_partial, H, N, G, seg_rows,
+                     inv_eps, seq_len, s_per_unit);
   int unit, g;
   unit_and_segment(blockIdx.x, G, unit, g);
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
             r = l % 16, q4 = l / 16;
   const e16_t* Qu = Q + size_t(unit) * N * DK;
-  const e16_t* Ku = K + size_t(unit) * N * DK;
-  const e16_t* Vu = V + size_t(unit) * N * DV;
   const e16_t* Gu = dO + size_t(unit) * N * DV;
   e16_t* dQu = dQ + size_t(unit) * N * DK;
+  const float scale = unit_scale(s, unit, H, s_per_unit);
+  const int row_begin = g * seg_rows;
+  const int seg_end = min(N, row_begin + seg_rows);
+  const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
+
+  StageK qst;
+  StageV gst;
+  qst.fetch(Qu, row_begin, row_end);
+  gst.fetch(Gu, row_begin, row_end);
+  stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Sl, s_totals + size_t(unit) * slots * DK * DV, n_sum, nullptr);
+
+  // racc[x][y]: element [v] of lane (r, q4) is G[key 16 ct + r][value 16 rt + 4 q4 + v]
+  f32x4 racc[RT::NCT][RT::NRT];
+#pragma unroll
+  for (int x = 0; x < RT::NCT; ++x)
+#pragma unroll
+    for (int y = 0; y < RT::NRT; ++y) racc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float ds_lane = 0.f;
+  RowPieces<DK> finished;  // dQ rows of the previous chunk, stored one chunk late
+#pragma unroll
+  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) finished.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int row0 = row_begin; row0 < row_end; row0 += C) {
+    {
+      float rqv[StageK::PASSES];
+      qst.row_rinv(inv_eps, rqv);
+      qst.commit_scaled(Qs, rqv);
+      qst.store_rinv(rq, rqv);
+      gst.commit_plain(Gs);
+    }
+    if (row0 + C < row_end) {
+      qst.fetch(Qu, row0 + C, row_end);
+      gst.fetch(Gu, row0 + C, row_end);
+    }
+    if (row0 > row_begin) store_row_pieces<DK>(finished, dQu, row0 - C + 16 * w, row_end, l);
+    __syncthreads();
+
+    // dq[nt][v] = dqh[row 16w + r][key feature 16 nt + 4 q4 + v]
+    f32x4 dq[Cfg::DTK];
+#pragma unroll
+    for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < Cfg::KSV; ++ks) {
+      const frag8 gf = lds_row_frag(Gs + (16 * w + r) * TPV + 32 * ks + 8 * q4);
+      frag8 srow[Cfg::DTK];
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DTK; ++nt)
+        srow[nt] = lds_row_frag(Sl + (16 * nt + r) * SP + 32 * ks + 8 * q4);
+      __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
+#pragma unroll
+      for (int nt = 0; nt < Cfg::DTK; ++nt) dq[nt] = mma16(srow[nt], gf, dq[nt]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // G^T += dO^T qh over the chunk's tokens, 32 at a time (rows beyond the sequence are zero)
+    if (RT::active(w)) {
+#pragma unroll
+      for (int p = 0; p < C / 32; ++p) {
+        const int t0 = 32 * p + 4 * q4, t1 = 32 * p + 16 + 4 * q4;
+        frag8 qcol[RT::NCT], grow[RT::NRT];
+#pragma unroll
+        for (int x = 0; x < RT::NCT; ++x)
+          qcol[x] = lds_col_frag(Qs, TPK, t0, t1, 16 * RT::col_tile(w, x), r);
+#pragma unroll
+        for (int y = 0; y < RT::NRT; ++y)
+          grow[y] = lds_col_frag(Gs, TPV, t0, t1, 16 * RT::row_tile(w, y), r);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int y = 0; y < RT::NRT; ++y)
+#pragma unroll
+          for (int x = 0; x < RT::NCT; ++x) racc[x][y] = mma16(grow[y], qcol[x], racc[x][y]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    const float ri = rq[16 * w + r];
+    const float rho = project_out_row<DK, TPK, true>(dq, Qs + 16 * w * TPK, ri, inv_eps, r, q4);
+    if (q4 == 0) ds_lane += rho;
+    gather_rows_transposed<DK>(dq, scale * ri, Os + 16 * w * TPK, l, finished);
+    __syncthreads();
+  }
+  if (row_begin < row_end) {
+    const int last = row_begin + (row_end - row_begin - 1) / C * C;
+    store_row_pieces<DK>(finished, dQu, last + 16 * w, row_end, l);
+  }
+  if (seq_len != nullptr) zero_rows_e16<DK>(dQu, row_end, seg_end);  // rows that do not exist
+
+  if (RT::active(w)) {
+    float* out = g_totals + (size_t(unit) * slots + g) * DK * DV;
+#pragma unroll
+    for (int x = 0; x < RT::NCT; ++x)
+#pragma unroll
+      for (int y = 0; y < RT::NRT; ++y)
+        store_state_words(out + (16 * RT::col_tile(w, x) + r) * DV + 16 * RT::row_tile(w, y) + 4 * q4,
+                          racc[x][y]);
+  }
+  // the segment's share of ds: lanes of the first lane row hold the row sums
+  ds_lane = group_sum<64>(ds_lane);
+  if (l == 0) ds_wave[w] = ds_lane;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < Cfg::NW; ++i) t += ds_wave[i];
+    ds_partial[size_t(unit) * G + g] = t;
+  }
+}
+
+// Backward, second sweep: dK and dV rows of one segment from G = Qh^T dO (the sum of the n_sum
+// stored matrices at g_totals); the first H workgroups also finish ds from the n_ds partial
+// sums per (batch, head) that the first sweep left.  Accumulated transposed:
+//   dkh^T = G V^T (over d_value),  (k G)^T = G^T k^T (over d_key),
+//   dk_j = s r_j (dkh_j - kh_j (kh_j . dkh_j)),  dv_j = s r_j (k_j G).
+template <int DK, int DV, int C>
+__global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_dkdv)(
+    const e16_t* __restrict__ K, const e16_t* __restrict__ V, const float* __restrict__ s,
+    e16_t* __restrict__ dK, e16_t* __restrict__ dV, const float* __restrict__ g_totals, int slots,
+    int n_sum, const float* __restrict__ ds_partial, int n_ds, float* __restrict__ ds, int B, int H,
+    int N, int G, int seg_rows, float inv_eps, const int* __restrict__ seq_len, int s_per_unit) {
+  using Cfg = BiCfg<DK, DV, C>;
+  using StageK = TileStage<DK, C, Cfg::NT>;
+  using StageV = TileStage<DV, C, Cfg::NT>;
+  constexpr int TPK = Cfg::TPK, TPV = Cfg::TPV, SP = Cfg::SP;
+  __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];   // raw k
+  __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
+  __shared__ __attribute__((aligned(16))) e16_t Gl[Cfg::STATE];  // Qh^T dO, [d_key][d_value]
+  __shared__ float rk[C];
+
+  fetch_argument_now(K, V, s, dK, dV, g_totals, slots, n_sum, ds_partial, n_ds, ds, B, H, N, G,
+                     seg_rows, inv_eps, seq_len, s_per_unit);
+  int unit, g;
+  unit_and_segment(blockIdx.x, G, unit, g);
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid / 64), l = tid % 64,
+            r = l % 16, q4 = l / 16;
+  const e16_t* Ku = K + size_t(unit) * N * DK;
+  const e16_t* Vu = V + size_t(unit) * N * DV;
   e16_t* dKu = dK + size_t(unit) * N * DK;
   e16_t* dVu = dV + size_t(unit) * N * DV;
   const float scale = unit_scale(s, unit, H, s_per_unit);
@@ -224,12 +358,10 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
   const int seg_end = min(N, row_begin + seg_rows);
   const int row_end = max(row_begin, min(valid_rows(seq_len, unit, H, N), seg_end));
 
-  StageK qst, kst;
-  StageV vst, gst;
-  qst.fetch(Qu, row_begin, row_end);
+  StageK kst;
+  StageV vst;
   kst.fetch(Ku, row_begin, row_end);
   vst.fetch(Vu, row_begin, row_end);
-  gst.fetch(Gu, row_begin, row_end);
 
   // ds[h] = sum of the shares of all batches (ds[b][h], one batch, with a scale per unit)
   if (int(blockIdx.x) < (s_per_unit ? B * H : H) && w == 0) {
@@ -241,67 +373,49 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
     t = group_sum<64>(t);
     if (l == 0) ds[blockIdx.x] = t;
   }
-  stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Sl, s_totals + size_t(unit) * slots * DK * DV, n_sum, nullptr);
   stage_summed_matrix<DK, DV, Cfg::NT, Cfg::SP>(Gl, g_totals + size_t(unit) * slots * DK * DV, n_sum, nullptr);
 
-  RowPieces<DK> done_q, done_k;  // rows of the previous chunk, stored one chunk late
+  RowPieces<DK> done_k;  // rows of the previous chunk, stored one chunk late
   RowPieces<DV> done_v;
 #pragma unroll
-  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) done_q.v[j] = done_k.v[j] = uint4{0u, 0u, 0u, 0u};
+  for (int j = 0; j < RowPieces<DK>::PER_LANE; ++j) done_k.v[j] = uint4{0u, 0u, 0u, 0u};
 #pragma unroll
   for (int j = 0; j < RowPieces<DV>::PER_LANE; ++j) done_v.v[j] = uint4{0u, 0u, 0u, 0u};
   for (int row0 = row_begin; row0 < row_end; row0 += C) {
     {
-      float rqv[StageK::PASSES], rkv[StageK::PASSES];
-      qst.row_rinv(inv_eps, rqv);
+      float rkv[StageK::PASSES];
       kst.row_rinv(inv_eps, rkv);
-      qst.commit_plain(Qs);
-      qst.store_rinv(rq, rqv);
       kst.commit_plain(Ks);
       kst.store_rinv(rk, rkv);
       vst.commit_plain(Vs);
-      gst.commit_plain(Gs);
     }
     if (row0 + C < row_end) {
-      qst.fetch(Qu, row0 + C, row_end);
       kst.fetch(Ku, row0 + C, row_end);
       vst.fetch(Vu, row0 + C, row_end);
-      gst.fetch(Gu, row0 + C, row_end);
     }
     if (row0 > row_begin) {
-      store_row_pieces<DK>(done_q, dQu, row0 - C + 16 * w, row_end, l);
       store_row_pieces<DK>(done_k, dKu, row0 - C + 16 * w, row_end, l);
       store_row_pieces<DV>(done_v, dVu, row0 - C + 16 * w, row_end, l);
     }
     __syncthreads();
 
     // d*[nt][v] = result[row 16w + r][feature 16 nt + 4 q4 + v]
-    f32x4 dq[Cfg::DTK], dk[Cfg::DTK], dv[Cfg::DTV];
+    f32x4 dk[Cfg::DTK], dv[Cfg::DTV];
 #pragma unroll
-    for (int nt = 0; nt < Cfg::DTK; ++nt) {
-      dq[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      dk[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int nt = 0; nt < Cfg::DTK; ++nt) dk[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < Cfg::DTV; ++nt) dv[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // S dO^T and G V^T contract over d_value (row fragments of Sl / Gl along their rows)
+    // G V^T contracts over d_value (row fragments of Gl along its rows)
 #pragma unroll
     for (int ks = 0; ks < Cfg::KSV; ++ks) {
-      const int off = (16 * w + r) * TPV + 32 * ks + 8 * q4;
-      const frag8 gf = lds_row_frag(Gs + off), vf = lds_row_frag(Vs + off);
-      frag8 srow[Cfg::DTK], grow[Cfg::DTK];
+      const frag8 vf = lds_row_frag(Vs + (16 * w + r) * TPV + 32 * ks + 8 * q4);
+      frag8 grow[Cfg::DTK];
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DTK; ++nt) {
-        const int soff = (16 * nt + r) * SP + 32 * ks + 8 * q4;
-        srow[nt] = lds_row_frag(Sl + soff);
-        grow[nt] = lds_row_frag(Gl + soff);
-      }
+      for (int nt = 0; nt < Cfg::DTK; ++nt)
+        grow[nt] = lds_row_frag(Gl + (16 * nt + r) * SP + 32 * ks + 8 * q4);
       __builtin_amdgcn_sched_barrier(0);  // all LDS reads are issued before the first MFMA
 #pragma unroll
-      for (int nt = 0; nt < Cfg::DTK; ++nt) {
-        dq[nt] = mma16(srow[nt], gf, dq[nt]);   // S dO^T   (over d_value)
-        dk[nt] = mma16(grow[nt], vf, dk[nt]);   // G V^T    (over d_value)
-      }
+      for (int nt = 0; nt < Cfg::DTK; ++nt) dk[nt] = mma16(grow[nt], vf, dk[nt]);
       __builtin_amdgcn_sched_barrier(0);
     }
     // G^T k^T contracts over d_key (fragments down the rows of Gl)
@@ -318,24 +432,20 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(bwd_bidir_apply)(
       __builtin_amdgcn_sched_barrier(0);
     }
     // every tile row is private to its wave here: chain rule on the raw rows, then the
-    // results are staged in place (Q rows for dQ, K rows for dK, V rows for dV)
-    const float ri = rq[16 * w + r], rj = rk[16 * w + r];
-    project_out_row<DK, TPK, false>(dq, Qs + 16 * w * TPK, ri, inv_eps, r, q4);
+    // results are staged in place (K rows for dK, V rows for dV)
+    const float rj = rk[16 * w + r];
     project_out_row<DK, TPK, false>(dk, Ks + 16 * w * TPK, rj, inv_eps, r, q4);
-    wave_lds_sync();  // own rows of Qs, Ks, Vs were read before the staging writes
-    gather_rows_transposed<DK>(dq, scale * ri, Qs + 16 * w * TPK, l, done_q);
+    wave_lds_sync();  // own rows of Ks, Vs were read before the staging writes
     gather_rows_transposed<DK>(dk, scale * rj, Ks + 16 * w * TPK, l, done_k);
     gather_rows_transposed<DV>(dv, scale * rj, Vs + 16 * w * TPV, l, done_v);
     __syncthreads();
   }
   if (row_begin < row_end) {
     const int last = row_begin + (row_end - row_begin - 1) / C * C;
-    store_row_pieces<DK>(done_q, dQu, last + 16 * w, row_end, l);
     store_row_pieces<DK>(done_k, dKu, last + 16 * w, row_end, l);
     store_row_pieces<DV>(done_v, dVu, last + 16 * w, row_end, l);
   }
   if (seq_len != nullptr) {  // rows that do not exist
-    zero_rows_e16<DK>(dQu, row_end, seg_end);
     zero_rows_e16<DK>(dKu, row_end, seg_end);
     zero_rows_e16<DV>(dVu, row_end, seg_end);
   }
@@ -381,37 +491,37 @@ hipError_t run_bwd_bidir(const CausalArgs& a) {
   const size_t pair_stride = state_array_bytes(a.B, a.H, DK, DV, a.G) / sizeof(float);
   float* g_totals = s_totals + pair_stride;
   float* ds_partial = reinterpret_cast<float*>(ws + 2 * state_array_bytes(a.B, a.H, DK, DV, a.G));
+  // few segments: the sweeps add the segment totals up themselves while staging them; many:
+  // the combine kernel leaves the sum in slot 0
   const bool few = a.G <= kMaxSegmentsSummedInScan;
   hipError_t err;
-  const float* s_src = s_totals;
-  int n_sum = 1, n_ds = 1;
-  if (few && a.saved_fwd_states != nullptr) {
-    // the forward left the segment totals of Kh^T V behind: only Qh^T dO is reduced here, and
-    // the same kernel forms the share <S, G_segment> of ds
-    SegmentTotalsArgs t = totals_args(a, a.Q, a.dO, g_totals);
-    t.dot_with = a.saved_fwd_states; t.dot_slots = a.G; t.dot_out = ds_partial;
-    err = COTTN_SYM(launch_segment_totals)(t);
-    if (err != hipSuccess) return err;
-    s_src = a.saved_fwd_states;
-    n_sum = a.G;
-    n_ds = a.G;
-  } else {
+  // S = Kh^T V: the totals the forward left behind (slot 0 is their sum already when the
+  // forward ran the combine kernel), or reduced here
+  const float* s_src = a.saved_fwd_states;
+  if (s_src == nullptr) {
     err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.K, a.V, s_totals));
     if (err != hipSuccess) return err;
-    err = COTTN_SYM(launch_segment_totals)(totals_args(a, a.Q, a.dO, g_totals));
-    if (err != hipSuccess) return err;
-    err = launch_bidir_combine(s_totals, pair_stride, 2, units, a.G, DK * DV, nullptr, ds_partial,
-                               a.stream);
-    if (err != hipSuccess) return err;
-    n_ds = DK * DV / 256;  // the combine kernel's partial sums per (batch, head)
+    if (!few) {
+      err = launch_bidir_combine(s_totals, 0, 1, units, a.G, DK * DV, nullptr, nullptr, a.stream);
+      if (err != hipSuccess) return err;
+    }
+    s_src = s_totals;
   }
-  return launch_kernel(COTTN_SYM_STR(bwd_bidir_apply), COTTN_SYM(bwd_bidir_apply)<DK, DV, C>, dim3(units * a.G),
-                       dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q),
-                       static_cast<const e16_t*>(a.K), static_cast<const e16_t*>(a.V),
-                       static_cast<const e16_t*>(a.dO), a.s, static_cast<e16_t*>(a.dQ),
-                       static_cast<e16_t*>(a.dK), static_cast<e16_t*>(a.dV), s_src, g_totals, a.G,
-                       n_sum, ds_partial, n_ds, a.ds, a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
-                       a.seq_len, a.s_per_unit);
+  err = launch_kernel(COTTN_SYM_STR(bwd_bidir_dq), COTTN_SYM(bwd_bidir_dq)<DK, DV, C>, dim3(units * a.G),
+                      dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.Q),
+                      static_cast<const e16_t*>(a.dO), a.s, static_cast<e16_t*>(a.dQ), s_src, a.G,
+                      few ? a.G : 1, g_totals, ds_partial, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps,
+                      a.seq_len, a.s_per_unit);
+  if (err != hipSuccess) return err;
+  if (!few) {
+    err = launch_bidir_combine(g_totals, 0, 1, units, a.G, DK * DV, nullptr, nullptr, a.stream);
+    if (err != hipSuccess) return err;
+  }
+  return launch_kernel(COTTN_SYM_STR(bwd_bidir_dkdv), COTTN_SYM(bwd_bidir_dkdv)<DK, DV, C>, dim3(units * a.G),
+                       dim3(Cfg::NT), 0, a.stream, static_cast<const e16_t*>(a.K),
+                       static_cast<const e16_t*>(a.V), a.s, static_cast<e16_t*>(a.dK),
+                       static_cast<e16_t*>(a.dV), g_totals, a.G, few ? a.G : 1, ds_partial, a.G, a.ds,
+                       a.B, a.H, a.N, a.G, a.seg_rows, 1.0f / a.eps, a.seq_len, a.s_per_unit);
 }
 
 }  // namespace

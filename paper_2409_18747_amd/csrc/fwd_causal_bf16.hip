@@ -94,14 +94,12 @@ template <> struct FwdSplit<128, 128, 64> { static constexpr int CS = 2; };
 // scan workgroup of the same (unit, g) in the next launch.  Segment g of a unit writes slot g
 // of the unit's n_slots slots; segments at or beyond n_compute have no total to form and
 // leave at once (the causal forward needs all segments but the last).  The bidirectional
-// path uses it for Kh^T V and, with (K, V) := (Q, dO), for Qh^T dO; there, given the stored
-// segment totals of the other matrix (dot_with, dot_slots slots per unit, added up here), it
-// also leaves the Frobenius product of its total with that matrix in dot_out[unit][g].
+// path uses it for Kh^T V (row-major slots, TILED = false; the causal scans read theirs tile
+// by tile, TILED = true).
 template <int DK, int DV, int C, bool TILED>
 __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
     const e16_t* __restrict__ K, const e16_t* __restrict__ V, float* __restrict__ seg_state,
     int N, int n_slots, int n_compute, int seg_rows, float inv_eps,
-    const float* __restrict__ dot_with, int dot_slots, float* __restrict__ dot_out,
     const int* __restrict__ seq_len, int H) {
   using Cfg = FwdCfg<DK, DV, C>;
   using ST = AccTiles<DK, DV, Cfg::NW>;   // key rows, value columns
@@ -109,10 +107,8 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
   using StageV = TileStage<DV, C, Cfg::NT>;
   __shared__ __attribute__((aligned(16))) e16_t Ks[Cfg::TILEK];
   __shared__ __attribute__((aligned(16))) e16_t Vs[Cfg::TILEV];
-  __shared__ float dot_wave[Cfg::NW];
 
-  fetch_argument_now(K, V, seg_state, N, n_slots, n_compute, seg_rows, inv_eps, dot_with, dot_slots,
-                     dot_out, seq_len, H);
+  fetch_argument_now(K, V, seg_state, N, n_slots, n_compute, seg_rows, inv_eps, seq_len, H);
   int unit, g;
   unit_and_segment(blockIdx.x, n_slots, unit, g);
   if (g >= n_compute) return;
@@ -176,32 +172,6 @@ __global__ __launch_bounds__(C * 4) void COTTN_SYM(fwd_segment_state)(
         store_state_words(out + (TILED ? tiled_state_offset(ST::row_tile(w, y), ST::col_tile(w, x), DV / 16, l)
                                        : (16 * ST::row_tile(w, y) + r) * DV + 16 * ST::col_tile(w, x) + 4 * q4),
                           acc[x][y]);
-  }
-  if (dot_with != nullptr) {  // workgroup-uniform
-    float dot = 0.f;
-    if (ST::active(w)) {
-      const float* other = dot_with + size_t(unit) * dot_slots * DK * DV;
-#pragma unroll
-      for (int x = 0; x < ST::NCT; ++x)
-#pragma unroll
-        for (int y = 0; y < ST::NRT; ++y)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int e = (16 * ST::row_tile(w, y) + r) * DV + 16 * ST::col_tile(w, x) + 4 * q4 + v;
-            float o = 0.f;
-            for (int j = 0; j < dot_slots; ++j) o += other[size_t(j) * DK * DV + e];
-            dot += acc[x][y][v] * o;
-          }
-    }
-    dot = group_sum<64>(dot);
-    if (l == 0) dot_wave[w] = dot;
-    __syncthreads();
-    if (tid == 0) {
-      float t = 0.f;
-#pragma unroll
-      for (int i = 0; i < Cfg::NW; ++i) t += dot_wave[i];
-      dot_out[size_t(unit) * n_slots + g] = t;
-    }
   }
 }
 
@@ -500,10 +470,9 @@ static hipError_t run_segment_totals(const SegmentTotalsArgs& t) {
   if (t.seg_rows >= 128)
     return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 128, TILED>, grid, dim3(512),
                          0, t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps,
-                         t.dot_with, t.dot_slots, t.dot_out, t.seq_len, t.H);
+                         t.seq_len, t.H);
   return launch_kernel(COTTN_SYM_STR(fwd_segment_state), COTTN_SYM(fwd_segment_state)<DK, DV, 64, TILED>, grid, dim3(256), 0,
-                       t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.dot_with,
-                       t.dot_slots, t.dot_out, t.seq_len, t.H);
+                       t.stream, X, Y, t.dst, t.N, t.G, t.n_compute, t.seg_rows, inv_eps, t.seq_len, t.H);
 }
 
 hipError_t COTTN_SYM(launch_segment_totals)(const SegmentTotalsArgs& t) {

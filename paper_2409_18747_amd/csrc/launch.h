@@ -74,14 +74,11 @@ hipError_t launch_fwd_segment_totals_bf16(const CausalArgs& a, float* dst);
 hipError_t launch_fwd_segment_totals_f16(const CausalArgs& a, float* dst);
 
 // The same kernel in general: dst[unit][g] = sum over the rows of segment g of N(X)^T Y
-// (dk x dv) for g < n_compute (G slots per unit).  With dot_with (stored totals of another d x d matrix,
-// dot_slots slots per unit, added up by the kernel) it also writes
-// dot_out[unit][g] = <dst[unit][g], that matrix>.
+// (dk x dv) for g < n_compute (G slots per unit).
 struct SegmentTotalsArgs {
   const void* X; const void* Y; float* dst;
   int units, N, dk, dv, G, n_compute, seg_rows;  // X rows are dk wide, Y rows dv wide
   float eps;
-  const float* dot_with; int dot_slots; float* dot_out;
   const int* seq_len; int H;  // padded batches: rows at or beyond seq_len[unit / H] do not exist
   // dst row-major [dk][dv] per slot (false), or in the tile order the causal scan kernels read
   // their stored states in (device_common.h: tiled_state_offset, tile (key tile, value tile))
