@@ -9,7 +9,8 @@
 // running backward.  With S_t = sum_{j<=t} kh_j^T v_j and R_t = sum_{i>=t} qh_i^T dO_i:
 //     dqh_t = s dO_t S_t^T,    dkh_t = s v_t R_t^T,    dv_t = s kh_t R_t.
 // Both sums are regrouped exactly into chunks of C rows inside G segments per (batch, head):
-//   forward-time states   per-segment totals of Kh^T V, [d_key][d_value]: taken over from the
+//   forward-time states   per-segment totals of Kh^T V (d_key x d_value, stored tile by tile
+//             like all states that only these kernels exchange): taken over from the
 //             forward call when it hands its workspace on, else rebuilt by the forward's
 //             totals kernel; with many segments a carry kernel turns totals into prefixes
 //             (and the reverse-time totals into suffixes), with few the scans add them up;

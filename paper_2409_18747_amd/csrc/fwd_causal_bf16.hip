@@ -87,7 +87,7 @@ template <int DK, int DV, int C> struct FwdSplit { static constexpr int CS = 1; 
 template <> struct FwdSplit<128, 128, 64> { static constexpr int CS = 2; };
 
 // ---------------------------------------------------------------------------------------
-// Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, [d_key][d_value];
+// Kernel 1: T[unit][g] = sum over the rows of segment g of kh^T v   (fp32, d_key x d_value;
 // K rows are DK wide, V rows DV wide)
 // grid = units * n_slots workgroups, workgroup (unit, g) as in the scan kernels: workgroups are
 // dealt to the XCDs by their index, and what this kernel reads stays in that XCD's L2 for the
@@ -430,7 +430,7 @@ hipError_t run_fwd_causal(const CausalArgs& a) {
   const e16_t* Q = static_cast<const e16_t*>(a.Q);
   const e16_t* K = static_cast<const e16_t*>(a.K);
   const e16_t* V = static_cast<const e16_t*>(a.V);
-  float* ws = static_cast<float*>(a.workspace);  // [units][G][D][D] when G > 1
+  float* ws = static_cast<float*>(a.workspace);  // [units][G] states of DK x DV (tiled) when G > 1
   const float inv_eps = 1.0f / a.eps;
   hipError_t err = hipSuccess;
   // few segments: no carry launch, each scan workgroup adds up the totals before its segment
