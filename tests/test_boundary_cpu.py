@@ -101,6 +101,23 @@ def test_workspace_sizes(lib):
     assert b <= 2 * a
 
 
+def test_heuristic_split_per_operation(lib):
+    """The split the library chooses by itself: the causal forward and backward agree (the
+    backward takes the forward's states over only then), so do the bidirectional pair, and the
+    bidirectional calls, which have no chain of chunks to shorten, are cut finer but never into
+    more segments than their kernels add up themselves (four)."""
+    lib.cottn_tune_segments(0)
+    for B, H, N, d in [(8, 12, 1024, 64), (32, 12, 512, 64), (1, 16, 65536, 64), (2, 3, 333, 32),
+                       (8, 12, 1024, 128), (1, 1, 64, 64)]:
+        assert lib.cottn_segments(0, B, H, N, d, 0, BF16) == lib.cottn_segments(1, B, H, N, d, 0, BF16)
+        assert lib.cottn_segments(2, B, H, N, d, 0, BF16) == lib.cottn_segments(3, B, H, N, d, 0, BF16)
+    assert lib.cottn_segments(0, 8, 12, 1024, 64, 0, BF16) == 4     # 384 workgroups
+    assert lib.cottn_segments(0, 32, 12, 512, 64, 0, BF16) == 1     # 384 units fill the chip
+    assert lib.cottn_segments(2, 32, 12, 512, 64, 0, BF16) == 2     # 768 workgroups
+    assert lib.cottn_segments(2, 8, 12, 1024, 64, 0, BF16) == 4     # capped at four
+    assert lib.cottn_segments(0, 1, 16, 65536, 64, 0, BF16) == 32   # long chains: 512 workgroups
+
+
 @pytest.mark.parametrize("args", [
     (0, 0, 1, 8, 64, 0, BF16),      # B < 1
     (0, 1, 0, 8, 64, 0, BF16),      # H < 1
