@@ -232,7 +232,7 @@ int cottn_step(const void* q, const void* k, const void* v, const float* s, floa
  *   Q, K, dQ, dK are [B][H][N][dk];  V, O, dO, dV are [B][H][N][dv];  q, k are [B][H][dk] and
  *   v, o [B][H][dv];  every state is float[B][H][dk][dv] = sum_j kh_j^T v_j.
  * dk and dv are each one of 32, 64, 128.  With dk == dv these calls are the ones above.  With
- * dk != dv: the 16-bit types only (COTTN_F32 gives COTTN_E_SHAPE) and chunk 0 or 64.
+ * dk != dv: every dtype; chunk 0 or 64 for the 16-bit types (0 or 32 for fp32, as always).
  * Everything else (workspaces, fwd_workspace, errors, conventions) is as for the functions
  * without the suffix; sizes and splits come from the *_dkdv variants of the two queries. */
 size_t cottn_workspace_bytes_dkdv(int op, int B, int H, int N, int dk, int dv, int chunk,

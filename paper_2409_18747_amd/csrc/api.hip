@@ -54,7 +54,6 @@ bool make_plan(int op, int B, int H, int N, int dk, int dv, int chunk, int dtype
   } else {
     C = chunk == 0 ? 32 : chunk;
     if (C != 32) return false;
-    if (dk != dv) return false;  // the fp32 kernels are written for d_key = d_value
   }
   const long units = long(B) * H;
   const long n_chunks = (long(N) + C - 1) / C;
@@ -188,7 +187,7 @@ const char* cottn_status_string(int status) {
     case COTTN_E_NULL: return "a required pointer is NULL";
     case COTTN_E_SHAPE: return "unsupported shape: need B,H >= 1, N >= 0, d (d_key, d_value) in "
                                "{32,64,128}, chunk in {0,64,128,256} (16-bit; 64 only when a "
-                               "dimension is 128 or d_key != d_value) or {0,32} (fp32, d_key = d_value)";
+                               "dimension is 128 or d_key != d_value) or {0,32} (fp32)";
     case COTTN_E_DTYPE: return "dtype must be COTTN_F32 (0), COTTN_BF16 (1) or COTTN_F16 (2)";
     case COTTN_E_ALIGN: return "tensor pointers must be 16-byte aligned, the workspace 256-byte aligned";
     case COTTN_E_WORKSPACE: return "workspace is NULL or smaller than cottn_workspace_bytes()";

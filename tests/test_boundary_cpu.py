@@ -256,7 +256,8 @@ def test_rectangular_head_dimensions_on_the_host(lib):
     assert wb(4, 256, 16, 1, 32, 128, 0, BF16) == 0             # decode needs none
     assert wb(0, 1, 1, 8, 64, 128, 128, BF16) == NOSIZE          # rectangular: chunk 64 only
     assert wb(0, 1, 1, 8, 64, 96, 0, BF16) == NOSIZE             # unsupported d_value
-    assert wb(0, 1, 1, 8, 64, 32, 0, F32) == NOSIZE              # fp32 kernels are square
+    assert wb(0, 1, 1, 8, 64, 32, 0, F32) == 0                   # fp32: any pair; one segment needs none
+    assert wb(0, 1, 1, 8, 64, 32, 64, F32) == NOSIZE             # fp32 chunk is 32
     buf = ctypes.create_string_buffer(1 << 16)
     base = (ctypes.addressof(buf) + 255) & ~255
     p = lambda: ctypes.c_void_p(base)
@@ -265,7 +266,7 @@ def test_rectangular_head_dimensions_on_the_host(lib):
     assert f(p(), p(), None, p(), p(), None, None, 0, 1, 1, 8, 32, 64, 0, BF16, eps, None) == E_NULL
     assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 48, 0, BF16, eps, None) == E_SHAPE
     assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 64, 128, BF16, eps, None) == E_SHAPE
-    assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 64, 0, F32, eps, None) == E_SHAPE
+    assert f(p(), p(), p(), p(), p(), None, None, 0, 1, 1, 8, 32, 64, 64, F32, eps, None) == E_SHAPE
     assert lib.cottn_bwd_bidir_dkdv(p(), p(), p(), p(), p(), p(), p(), p(), p(), None, 0, p(), 16,
                                     1, 1, 8, 64, 128, BF16, eps, None) == E_WS
     assert lib.cottn_step_dkdv(p(), p(), p(), p(), p(), p(), 1, 1, 64, 100, BF16, eps, None) == E_SHAPE

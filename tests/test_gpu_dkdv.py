@@ -24,7 +24,7 @@ def run(cottn, oracle, causal, B, H, N, dk, dv, dtype, seed, segments=0, saved=F
     x = workloads.draw(B, H, N, dk, dtype, seed, d_value=dv)
     Q, K, V, dO = (to_device(x[k], dtype) for k in ("Q", "K", "V", "dO"))
     s = to_device(x["s"], "f32")
-    code = {"bf16": cottn.COTTN_BF16, "f16": cottn.COTTN_F16}[dtype]
+    code = {"bf16": cottn.COTTN_BF16, "f16": cottn.COTTN_F16, "f32": cottn.COTTN_F32}[dtype]
     cottn.cottn_tune_segments(segments)
     fwd = cottn.cottn_fwd_causal_dkdv if causal else cottn.cottn_fwd_bidir_dkdv
     bwd = cottn.cottn_bwd_causal_dkdv if causal else cottn.cottn_bwd_bidir_dkdv
@@ -73,6 +73,15 @@ def test_f16_and_saved_states(cottn, oracle, dk, dv):
     run(cottn, oracle, False, 2, 2, 300, dk, dv, "f16", seed=10, segments=2, saved=True)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("dk,dv", SHAPES)
+def test_f32_shapes(cottn, oracle, causal, dk, dv):
+    """The fp32 path at d_key != d_value: several chunks of 32, a ragged tail, several segments,
+    and a split the forward leaves nothing behind for (fp32 ignores a forward workspace)."""
+    run(cottn, oracle, causal, 2, 2, 150, dk, dv, "f32", seed=900 + dk + dv, segments=3)
+    run(cottn, oracle, causal, 1, 2, 45, dk, dv, "f32", seed=901 + dk + dv, segments=1, saved=True)
+
+
 @pytest.mark.parametrize("dk,dv", [(64, 128), (128, 64)])
 def test_bf16_training_shape(cottn, oracle, dk, dv):
     """A GPT-shaped call (default split) with d_key != d_value."""
@@ -86,7 +95,7 @@ def test_step_continues_prefill(cottn, oracle, dk, dv, dtype):
     import torch
     from paper_2409_18747_amd import workloads
     B, H, N, T = 2, 3, 70, 5
-    pre = "bf16" if dtype == "f32" else dtype   # the rectangular prefill exists for the 16-bit types
+    pre = dtype
     x = workloads.draw(B, H, N + T, dk, pre, 40 + dk + dv, d_value=dv)
     s = to_device(x["s"], "f32")
     state = torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda")
@@ -100,13 +109,13 @@ def test_step_continues_prefill(cottn, oracle, dk, dv, dtype):
         torch.cuda.synchronize()
         worst = max(worst, float(np.abs(to_host(o) - O_ref[:, :, t]).max() / np.abs(O_ref).max()))
     print("step dkdv %s dk%d dv%d: %.2e" % (dtype, dk, dv, worst), flush=True)
-    assert worst <= TOL["bf16" if dtype == "f32" else dtype]   # the prefill state is a 16-bit path result
+    assert worst <= TOL[dtype]
 
 
-def test_rectangular_fp32_is_refused(cottn):
+def test_fp32_chunk_is_32_for_rectangular_shapes_too(cottn):
     import torch
     Q = torch.zeros(1, 1, 8, 32, device="cuda")
     V = torch.zeros(1, 1, 8, 64, device="cuda")
     with pytest.raises(cottn.CottnError) as e:
-        cottn.cottn_fwd_causal_dkdv(Q, Q, V, torch.ones(1, device="cuda"))
+        cottn.cottn_fwd_causal_dkdv(Q, Q, V, torch.ones(1, device="cuda"), chunk=64)
     assert e.value.status == 2   # COTTN_E_SHAPE
